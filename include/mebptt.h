@@ -1,0 +1,184 @@
+/*
+ * mebptt -- memory-efficient LSTM back-propagation through time on AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Two halves:
+ *
+ *   mebptt_plan(...)  host only.  Solves the paper's dynamic programs for the optimal
+ *                     checkpointing policy under a budget of m memory slots -- BPTT-HSM
+ *                     (Section 3.1, eq. 1-3, Algorithm 1), BPTT-ISM (Section 3.2, eq. 4-5),
+ *                     BPTT-MSM (Sections 3.3-3.4, eq. 6-10) -- and flattens the policy for
+ *                     (t, m) into a linear schedule of forward runs and backward steps
+ *                     (Algorithm 2; Section 3.2 steps 1-4; Section 3.3 last paragraph).
+ *   mebptt_run(...)   one gradient step of a single-layer LSTM (the experiment of Section 4):
+ *                     executes the schedule on the GPU inside the caller's slot pool and
+ *                     returns dW, db, dh0, dc0 (and optionally dx and the outputs h_1..h_t).
+ *
+ * Conventions
+ *   - Every function returns MEBPTT_OK (0) or a negative mebptt_status; it never throws or
+ *     aborts.  On a validation error no device work has been enqueued.  mebptt_last_error()
+ *     gives a thread-local message for the last failure on the calling thread.
+ *   - "host" / "device" on a pointer says which memory it must point to.  The library
+ *     allocates no device memory: slots, workspace, inputs and outputs belong to the caller.
+ *   - Time steps are 1-based: step s consumes x[s-1] and the hidden state of step s-1 and
+ *     produces the hidden state of step s.  "Hidden state" is the pair (h_s, c_s) that one LSTM
+ *     core hands to the next (Definition 2); it is the memory UNIT: two [B,H] fp32 planes.
+ *     An "internal state" (Definition 3) is four units: (h_s, c_s), (i, f), (g, o) and the
+ *     input hidden state (h_{s-1}, c_{s-1}); the last unit is omitted when that state is
+ *     already held elsewhere (Section 3.4), which gives alpha = 4 and beta = 3 for an LSTM.
+ *   - LSTM: G = x_s W_ih^T + h_{s-1} W_hh^T + b, gate order i, f, g, o along the 4H axis;
+ *     i, f, o = sigmoid, g = tanh; c_s = f c_{s-1} + i g; h_s = o tanh(c_s).
+ *   - All matrices are dense row-major with no padding.
+ */
+#ifndef MEBPTT_H
+#define MEBPTT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MEBPTT_OK = 0,
+  MEBPTT_EINVAL = -1,       /* bad argument (null pointer, t < 1, m < 1, alpha < 2, beta > alpha ...) */
+  MEBPTT_ENOMEM_SLOTS = -2, /* slot pool smaller than mebptt_slot_pool_bytes()                       */
+  MEBPTT_EWORKSPACE = -3,   /* workspace smaller than mebptt_workspace_bytes() or misaligned         */
+  MEBPTT_ESHAPE = -4,       /* descriptor and plan disagree (t)                                      */
+  MEBPTT_EINFEASIBLE = -5,  /* the dynamic program prices (t, m) at infinity                         */
+  MEBPTT_EHIP = -6,         /* a HIP call failed; the message carries hipGetErrorString              */
+  MEBPTT_ENOMEM_HOST = -7   /* host allocation for the tables or the schedule failed                 */
+} mebptt_status;
+
+/* Which states the slots memorise. */
+typedef enum {
+  MEBPTT_HSM = 0, /* hidden states only (Section 3.1); m counts slots of one unit, h_0 included      */
+  MEBPTT_ISM = 1, /* internal states only (Section 3.2); m counts slots of four units, h_0 excluded  */
+  MEBPTT_MSM = 2  /* mixed (Sections 3.3-3.4); m counts units, h_0 included                          */
+} mebptt_kind;
+
+typedef struct mebptt_plan_s mebptt_plan_t; /* opaque; host memory owned by the library */
+
+/* ---- schedule ---------------------------------------------------------------------------- */
+
+/* A location names one unit of memory.  Values >= 0 index units of the caller's slot pool;
+ * the negative values are units inside the workspace (the "single RNN core available for
+ * intermediate calculations" of Section 3.1, outside the budget). */
+enum {
+  MEBPTT_LOC_NONE = -1,
+  MEBPTT_LOC_T0 = -2,   /* transient hidden state, ping          */
+  MEBPTT_LOC_T1 = -3,   /* transient hidden state, pong          */
+  MEBPTT_LOC_CORE = -4, /* working core: (h,c) here, then (i,f), (g,o) in its next two units */
+  MEBPTT_LOC_INIT = -5  /* copy of the caller's (h0, c0); ISM start state */
+};
+
+enum { MEBPTT_OP_FWD_RUN = 1, MEBPTT_OP_BWD = 2 };
+
+/* One schedule entry.
+ * FWD_RUN: `count` consecutive forward operations, steps step .. step+count-1.  The first reads
+ *          the hidden state at `src`; the last writes its hidden state to `dst` and, when
+ *          keep != 0, its gates to the two units after `dst`; the state of step
+ *          step+count-2 (count > 1) is written to `prev`; earlier ones alternate T0/T1.
+ * BWD:     one backward operation of `step` through the internal state at `dst`, whose input
+ *          hidden state is at `src`.  The loss gradient of that step is injected here.
+ *          Backward entries appear in the order t, t-1, ..., 1. */
+typedef struct {
+  int32_t op;
+  int32_t step;
+  int32_t count;
+  int32_t src;
+  int32_t dst;
+  int32_t keep;
+  int32_t prev;
+} mebptt_op;
+
+/* Alg. 1 generalised to the three strategies.  Builds the tables for every t' <= t and
+ * m' <= m and flattens the policy of (t, m).  alpha, beta are used by MSM only (integers,
+ * alpha >= 2, 1 <= beta <= alpha; beta == alpha disables Section 3.4).  *out receives a plan to
+ * be released with mebptt_plan_free.  Errors: EINVAL, EINFEASIBLE, ENOMEM_HOST. */
+int mebptt_plan(int32_t t, int32_t m, int32_t kind, int32_t alpha, int32_t beta, mebptt_plan_t** out);
+void mebptt_plan_free(mebptt_plan_t* plan);
+
+/* Borrowed read-only views, valid until mebptt_plan_free.  Tables are row-major
+ * [(t+1) x (m+1)], entry [t'][m'].  Infeasible cost cells hold MEBPTT_COST_INF; undefined
+ * split/choice cells hold 0.
+ *   cost   which = 0: C.  MSM also 1: C_1 (hidden push), 2: C_2 (internal push)  (eq. 2, 9)
+ *   split  which = 0: D (HSM, ISM).  MSM: 1: D_1, 2: D_2                            (eq. 3, 5, 8)
+ *   choice H (eq. 9): 1 = hidden, 2 = internal; MSM only, otherwise NULL.
+ * A `which` that the plan's kind does not define returns NULL. */
+#define MEBPTT_COST_INF ((int64_t)1 << 60)
+const int64_t* mebptt_plan_cost(const mebptt_plan_t* plan, int32_t which);
+const int32_t* mebptt_plan_split(const mebptt_plan_t* plan, int32_t which);
+const uint8_t* mebptt_plan_choice(const mebptt_plan_t* plan);
+int32_t mebptt_plan_length(const mebptt_plan_t* plan);
+int32_t mebptt_plan_budget(const mebptt_plan_t* plan);
+int32_t mebptt_plan_kind(const mebptt_plan_t* plan);
+/* Number of forward operations in the schedule; equals C(t, m) (Section 3.1: the cost is the
+ * total number of forward operations).  Counted from the flattened schedule, not read from C. */
+int64_t mebptt_plan_forward_ops(const mebptt_plan_t* plan);
+/* High-water mark of the stack while the schedule runs, in the plan's budget unit (slots for
+ * HSM and ISM, units for MSM); never above m. */
+int32_t mebptt_plan_peak(const mebptt_plan_t* plan);
+/* The flat schedule; *n receives the number of entries. */
+const mebptt_op* mebptt_plan_schedule(const mebptt_plan_t* plan, size_t* n);
+
+/* ---- LSTM execution ---------------------------------------------------------------------- */
+
+typedef struct {
+  int32_t B, I, H, t;
+  int32_t gemm_dtype;    /* 0: fp32 GEMM operands; 1: bf16 GEMM operands.  Accumulation, state
+                            storage and all pointwise arithmetic are fp32 either way.          */
+  int32_t loss;          /* 0: upstream gradients come from `dy`; 1: built-in loss
+                            0.5 * sum_s sum(h_s^2), i.e. dy_s = h_s                             */
+  int32_t dy_first_step; /* loss 0: `dy` covers steps dy_first_step .. t (1-based); the steps
+                            before carry no loss.  Use 1 for a loss at every step.              */
+} mebptt_lstm_desc;
+
+typedef struct {
+  int64_t forward_ops;    /* forward operations launched (== C(t, m))   */
+  int64_t backward_ops;   /* backward operations launched (== t)        */
+  int32_t peak;           /* as mebptt_plan_peak                        */
+  int32_t reserved;
+  size_t peak_slot_bytes; /* peak * bytes per budget unit               */
+} mebptt_stats;
+
+/* Bytes of one unit: a hidden state (h, c) in fp32 = 2 * B * H * 4. */
+size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc);
+/* Bytes of the slot pool for this plan: m budget units (ISM: m slots of four units). */
+size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan);
+/* Bytes of workspace: working core, transients, running gradients, operand copies of the
+ * weights and bounded staging for the time-batched weight-gradient GEMM.  Independent of t
+ * and of the budget. */
+size_t mebptt_workspace_bytes(const mebptt_lstm_desc* desc);
+/* Largest budget, in the given kind's unit, whose slot pool fits in budget_bytes (0 if none). */
+int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_t budget_bytes);
+
+/* Alg. 2 / Section 3.2 / Section 3.3: one combined forward-and-backward gradient step.
+ *
+ * device, read:  W_ih [4H,I], W_hh [4H,H], b [4H] (NULL = zeros), x [t,B,I],
+ *                dy [t-dy_first_step+1, B, H] (loss 0; ignored for loss 1),
+ *                h0, c0 [B,H] (NULL = zeros).
+ * device, r/w:   slots (>= mebptt_slot_pool_bytes, 256-byte aligned), workspace
+ *                (>= mebptt_workspace_bytes, 256-byte aligned).  Contents on entry are ignored;
+ *                contents on exit are unspecified.
+ * device, write: dW_ih [4H,I], dW_hh [4H,H], db [4H], dh0, dc0 [B,H]: OVERWRITTEN with the
+ *                gradients.  dx [t,B,I] and y_out [t,B,H] may be NULL (then not computed).
+ * host, write:   stats (may be NULL); filled before the call returns.
+ * stream:        a hipStream_t (NULL = the default stream).  The call only enqueues work; results
+ *                are valid once the caller has synchronised the stream.
+ * Errors: EINVAL, ESHAPE, ENOMEM_SLOTS, EWORKSPACE, EHIP. */
+int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
+               const float* W_ih, const float* W_hh, const float* b,
+               const float* x, const float* dy, const float* h0, const float* c0,
+               void* slots, size_t slots_bytes, void* workspace, size_t workspace_bytes,
+               float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
+               float* dx, float* y_out, mebptt_stats* stats, void* stream);
+
+const char* mebptt_last_error(void);
+/* Library version string, e.g. "mebptt 0.1 (gfx950)". */
+const char* mebptt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEBPTT_H */

@@ -1,0 +1,209 @@
+"""ctypes binding of ``libmebptt.so`` -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see ``include/mebptt.h``); all
+planning and all arithmetic run inside the library.  PyTorch appears only as the owner of
+device memory and of the HIP stream.  There is no fallback: if the library has not been built
+the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmebptt.so")
+_lib = None
+
+OK, EINVAL, ENOMEM_SLOTS, EWORKSPACE, ESHAPE, EINFEASIBLE, EHIP, ENOMEM_HOST = 0, -1, -2, -3, -4, -5, -6, -7
+HSM, ISM, MSM = 0, 1, 2
+OP_FWD_RUN, OP_BWD = 1, 2
+LOC_NONE, LOC_T0, LOC_T1, LOC_CORE, LOC_INIT = -1, -2, -3, -4, -5
+COST_INF = 1 << 60
+
+
+class MebpttError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"mebptt error {code}: {message}")
+        self.code = code
+
+
+class mebptt_op(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("op", "step", "count", "src", "dst", "keep", "prev")]
+
+
+class mebptt_lstm_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "I", "H", "t", "gemm_dtype", "loss", "dy_first_step")]
+
+
+class mebptt_stats(C.Structure):
+    _fields_ = [("forward_ops", C.c_int64), ("backward_ops", C.c_int64), ("peak", C.c_int32),
+                ("reserved", C.c_int32), ("peak_slot_bytes", C.c_size_t)]
+
+
+# name -> (restype, argtypes): every symbol the header declares
+_P = C.c_void_p
+_DESC = C.POINTER(mebptt_lstm_desc)
+SIGNATURES = {
+    "mebptt_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
+    "mebptt_plan_free": (None, [_P]),
+    "mebptt_plan_cost": (C.POINTER(C.c_int64), [_P, C.c_int32]),
+    "mebptt_plan_split": (C.POINTER(C.c_int32), [_P, C.c_int32]),
+    "mebptt_plan_choice": (C.POINTER(C.c_uint8), [_P]),
+    "mebptt_plan_length": (C.c_int32, [_P]),
+    "mebptt_plan_budget": (C.c_int32, [_P]),
+    "mebptt_plan_kind": (C.c_int32, [_P]),
+    "mebptt_plan_forward_ops": (C.c_int64, [_P]),
+    "mebptt_plan_peak": (C.c_int32, [_P]),
+    "mebptt_plan_schedule": (C.POINTER(mebptt_op), [_P, C.POINTER(C.c_size_t)]),
+    "mebptt_unit_bytes": (C.c_size_t, [_DESC]),
+    "mebptt_slot_pool_bytes": (C.c_size_t, [_DESC, _P]),
+    "mebptt_workspace_bytes": (C.c_size_t, [_DESC]),
+    "mebptt_units_for_bytes": (C.c_int32, [_DESC, C.c_int32, C.c_size_t]),
+    "mebptt_run": (C.c_int, [_DESC, _P] + [_P] * 7 + [_P, C.c_size_t, _P, C.c_size_t] + [_P] * 7
+                   + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_last_error": (C.c_char_p, []),
+    "mebptt_version": (C.c_char_p, []),
+}
+
+
+def lib() -> C.CDLL:
+    """Loads the library on first use.  Raises if it is missing: there is no other code path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_1606_03401_amd.build`")
+        l = C.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def mebptt_last_error() -> str:
+    return lib().mebptt_last_error().decode()
+
+
+def mebptt_version() -> str:
+    return lib().mebptt_version().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise MebpttError(rc, mebptt_last_error())
+
+
+class Plan:
+    """Owner of a ``mebptt_plan_t*``; the table properties are read-only numpy views of the
+    library's memory (valid while this object lives)."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.mebptt_plan_free(self.handle)
+            self.handle = None
+
+    @property
+    def t(self) -> int:
+        return lib().mebptt_plan_length(self.handle)
+
+    @property
+    def m(self) -> int:
+        return lib().mebptt_plan_budget(self.handle)
+
+    @property
+    def kind(self) -> int:
+        return lib().mebptt_plan_kind(self.handle)
+
+    @property
+    def forward_ops(self) -> int:
+        return lib().mebptt_plan_forward_ops(self.handle)
+
+    @property
+    def peak(self) -> int:
+        return lib().mebptt_plan_peak(self.handle)
+
+    def _table(self, ptr, dtype):
+        if not ptr:
+            return None
+        shape = (self.t + 1, self.m + 1)
+        a = np.ctypeslib.as_array(ptr, shape=shape)
+        a = a.view(dtype)
+        a.flags.writeable = False
+        return a
+
+    def cost(self, which: int = 0):
+        return self._table(lib().mebptt_plan_cost(self.handle, which), np.int64)
+
+    def split(self, which: int = 0):
+        return self._table(lib().mebptt_plan_split(self.handle, which), np.int32)
+
+    def choice(self):
+        return self._table(lib().mebptt_plan_choice(self.handle), np.uint8)
+
+    def schedule(self) -> np.ndarray:
+        """Structured array with fields op, step, count, src, dst, keep, prev (a copy)."""
+        n = C.c_size_t(0)
+        ptr = lib().mebptt_plan_schedule(self.handle, C.byref(n))
+        dt = np.dtype([(f, np.int32) for f, _ in mebptt_op._fields_])
+        if n.value == 0:
+            return np.zeros(0, dt)
+        raw = np.ctypeslib.as_array(C.cast(ptr, C.POINTER(C.c_int32)), shape=(n.value, 7))
+        return raw.copy().view(dt).reshape(n.value)
+
+
+def mebptt_plan(t: int, m: int, kind: int, alpha: int = 4, beta: int = 3) -> Plan:
+    out = _P()
+    _check(lib().mebptt_plan(t, m, kind, alpha, beta, C.byref(out)))
+    return Plan(out.value)
+
+
+def make_desc(B: int, I: int, H: int, t: int, gemm_dtype: int, loss: int, dy_first_step: int = 1) -> mebptt_lstm_desc:
+    return mebptt_lstm_desc(B, I, H, t, gemm_dtype, loss, dy_first_step)
+
+
+def mebptt_unit_bytes(desc: mebptt_lstm_desc) -> int:
+    return lib().mebptt_unit_bytes(C.byref(desc))
+
+
+def mebptt_slot_pool_bytes(desc: mebptt_lstm_desc, plan: Plan) -> int:
+    return lib().mebptt_slot_pool_bytes(C.byref(desc), plan.handle)
+
+
+def mebptt_workspace_bytes(desc: mebptt_lstm_desc) -> int:
+    return lib().mebptt_workspace_bytes(C.byref(desc))
+
+
+def mebptt_units_for_bytes(desc: mebptt_lstm_desc, kind: int, budget_bytes: int) -> int:
+    return lib().mebptt_units_for_bytes(C.byref(desc), kind, budget_bytes)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to mebptt_run must be contiguous")
+    return t.data_ptr()
+
+
+def mebptt_run(desc: mebptt_lstm_desc, plan: Plan, W_ih, W_hh, b, x, dy, h0, c0, slots, workspace,
+               dW_ih, dW_hh, db, dh0, dc0, dx=None, y_out=None, stream: Optional[int] = None) -> mebptt_stats:
+    """Enqueues one gradient step.  Tensor arguments are torch CUDA tensors (float32; `slots` and
+    `workspace` are uint8 buffers); `stream` is a raw hipStream_t (default: torch's current stream).
+    Returns the host-side statistics.  The caller synchronises."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    stats = mebptt_stats()
+    rc = lib().mebptt_run(C.byref(desc), plan.handle, _ptr(W_ih), _ptr(W_hh), _ptr(b), _ptr(x), _ptr(dy), _ptr(h0),
+                          _ptr(c0), _ptr(slots), slots.numel() * slots.element_size(), _ptr(workspace),
+                          workspace.numel() * workspace.element_size(), _ptr(dW_ih), _ptr(dW_hh), _ptr(db), _ptr(dh0),
+                          _ptr(dc0), _ptr(dx), _ptr(y_out), C.byref(stats), stream)
+    _check(rc)
+    return stats

@@ -1,0 +1,89 @@
+// Launch wrappers for the HIP kernels (defined in kernels.hip).  Not part of the ABI.
+//
+// Shapes and padded operand layouts (all chosen so that every vector load of a GEMM operand is
+// 16-byte aligned and in bounds; padding is zero):
+//   HP = H rounded up to 16,  KX = I rounded up to 32,  KH = H rounded up to 32,  KP = KX + KH,
+//   NX = I rounded up to 16,  BP = B rounded up to 16,  G4 = 4 * HP.
+//   Wp  [HP/4][16][KP]   forward operand: row 4*u_local + gate of group u/4 is row gate*H + u of
+//                        [W_ih | W_hh]; columns [0,KX) hold W_ih, [KX,KP) hold W_hh.
+//   bp  [G4] fp32        bias in the same permuted order: bp[4u + gate] = b[gate*H + u].
+//   WTh [HP][G4]         WTh[n][4u+gate] = W_hh[gate*H+u][n]  (operand of dh_{s-1} = dG_s W_hh)
+//   WTx [NX][G4]         WTx[n][4u+gate] = W_ih[gate*H+u][n]  (operand of dx_s   = dG_s W_ih)
+//   dG  [CH][BP][G4]     gate pre-activation gradients of one chunk of CH consecutive steps,
+//                        columns in the permuted order 4u + gate; chunk slot = (step-1) % CH.
+//   dGT [G4][KC]         the same values transposed, KC = CH*B rounded up to 32, column
+//                        slot*B + b: operand of the weight-gradient GEMM.
+//   aT  [NX+HP][KC]      rows [0,NX): x_s transposed; rows [NX,NX+HP): h_{s-1} transposed.
+// OpT is float (gemm_dtype 0) or bf16 (gemm_dtype 1); accumulation is always fp32.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace mebptt {
+
+struct Dims {
+  int B, I, H;
+  int HP, KX, KH, KP, NX, BP, G4;
+  int CH, KC;   // steps per weight-gradient chunk, padded K of that GEMM
+  int dtype;    // 0 fp32, 1 bf16
+  size_t op_bytes() const { return dtype ? 2 : 4; }
+};
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+Dims make_dims(int B, int I, int H, int dtype);
+
+// One unit = (h, c): two consecutive [B,H] fp32 planes.
+struct UnitPtr {
+  float* p;
+  float* plane(const Dims& d, int k) const { return p + (size_t)k * d.B * d.H; }
+};
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_prep_weights(const Dims& d, const float* W_ih, const float* W_hh, const float* b, void* Wp,
+                               float* bp, void* WTh, void* WTx, hipStream_t st);
+// dst unit <- (h0, c0), NULL meaning zeros.
+hipError_t launch_init_state(const Dims& d, const float* h0, const float* c0, float* dst_unit, hipStream_t st);
+
+// One forward operation: reads x_s [B,I] and the hidden state at src; writes (h,c) to dst and,
+// when gates != NULL, (i,f) and (g,o) to the two units starting at `gates`.
+hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const float* x_s, const float* src_unit,
+                          float* dst_unit, float* gates_units, hipStream_t st);
+
+struct BackwardArgs {
+  const void* WTh;
+  const void* dG_next;    // [BP][G4] of step s+1, or NULL for s = t
+  const float* state;     // unit (h_s, c_s); the gates follow in the next two units
+  const float* prev;      // unit (h_{s-1}, c_{s-1})
+  const float* dy_s;      // [B,H] or NULL
+  int dy_is_h;            // built-in loss: the injected gradient is h_s itself
+  float* dc;              // [B,H] running gradient w.r.t. the cell state, updated in place
+  void* dG_cur;           // [BP][G4] of step s (written)
+  void* dGT;              // chunk-transposed copy (written at column col0 + b)
+  void* aT;               // h_{s-1} transposed goes to rows [NX, NX+HP) at column col0 + b
+  int col0;               // slot * B
+  float* y_out_s;         // [B,H] or NULL
+};
+// One backward operation (the sequential half): dh_s = dG_{s+1} W_hh + dy_s, then the pointwise
+// LSTM backward producing dG_s and dc_{s-1}.
+hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st);
+
+// out[b][n] = sum_k dG[b][k] * WT[n][k] for b < rows(valid), n < N; ld_out = row stride of out.
+// `rows_per_step`/`BP` describe the padded row layout of dG: logical row r = step_slot*B + b
+// lives at dG row step_slot*BP + b.
+hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,
+                             int ld_out, hipStream_t st);
+
+// x of `nslots` consecutive steps -> rows [0,NX) of aT.
+hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, void* aT, hipStream_t st);
+
+// dW_ih / dW_hh (+)= dGT * aT^T over K = nslots*B columns; db (+)= row sums of dGT.
+hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dW_ih,
+                        float* dW_hh, float* db, hipStream_t st);
+
+hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, hipStream_t st);
+
+}  // namespace mebptt

@@ -1,0 +1,230 @@
+// Executor: walks the flat schedule of a plan and enqueues the HIP kernels of one gradient step
+// (Algorithm 2 for hidden-state pushes, Section 3.2's four steps for internal-state pushes).
+//
+// Memory outside the slot budget (the "single RNN core available for intermediate
+// calculations" of Section 3.1, plus bounded staging) lives in the caller's workspace:
+//   operand copies of the weights | transient states T0, T1 | working core (3 units) |
+//   copy of (h0, c0) | running dc | two chunk buffers each of dG, dG^T and [x ; h_prev]^T.
+// The weight gradient is accumulated once per chunk of CH consecutive time steps.  Chunks are
+// aligned to absolute step numbers, so the summation order of dW depends only on t -- never on
+// the budget or the policy -- and gradients are bit-identical for every budget.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "common.h"
+#include "kernels.h"
+
+using namespace mebptt;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Workspace {
+  size_t Wp, bp, WTh, WTx, state, dc, dG[2], dGT[2], aT[2], total;
+};
+
+Workspace layout(const Dims& d) {
+  Workspace w{};
+  const size_t op = d.op_bytes();
+  const size_t unit = 2 * (size_t)d.B * d.H * sizeof(float);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes);
+    return o;
+  };
+  w.Wp = take((size_t)d.G4 * d.KP * op);
+  w.bp = take((size_t)d.G4 * sizeof(float));
+  w.WTh = take((size_t)d.HP * d.G4 * op);
+  w.WTx = take((size_t)d.NX * d.G4 * op);
+  w.state = take(6 * unit);
+  w.dc = take(unit / 2);
+  for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
+  for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
+  for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)(d.NX + d.HP) * d.KC * op);
+  w.total = off;
+  return w;
+}
+
+int check_desc(const mebptt_lstm_desc* desc) {
+  if (!desc) return set_error(MEBPTT_EINVAL, "desc is NULL");
+  if (desc->B < 1 || desc->I < 1 || desc->H < 1 || desc->t < 1)
+    return set_error(MEBPTT_EINVAL, "B, I, H, t must be >= 1 (got %d, %d, %d, %d)", desc->B, desc->I, desc->H, desc->t);
+  if (desc->gemm_dtype != 0 && desc->gemm_dtype != 1)
+    return set_error(MEBPTT_EINVAL, "gemm_dtype must be 0 (fp32) or 1 (bf16)");
+  if (desc->loss != 0 && desc->loss != 1) return set_error(MEBPTT_EINVAL, "loss must be 0 or 1");
+  if (desc->loss == 0 && (desc->dy_first_step < 1 || desc->dy_first_step > desc->t))
+    return set_error(MEBPTT_EINVAL, "dy_first_step must be in [1, t] (got %d)", desc->dy_first_step);
+  if ((int64_t)desc->B * desc->H > (int64_t)1 << 28 || (int64_t)desc->H * 4 * ((int64_t)desc->I + desc->H) > (int64_t)1 << 31)
+    return set_error(MEBPTT_EINVAL, "shape too large");
+  return MEBPTT_OK;
+}
+
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+#define HIP_TRY(expr)                                                                                 \
+  do {                                                                                                \
+    hipError_t e_ = (expr);                                                                           \
+    if (e_ != hipSuccess) return set_error(MEBPTT_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc) {
+  if (!desc || desc->B < 1 || desc->H < 1) return 0;
+  return 2 * (size_t)desc->B * desc->H * sizeof(float);
+}
+
+size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan) {
+  if (!desc || !plan) return 0;
+  size_t per = mebptt_unit_bytes(desc) * (plan->kind == MEBPTT_ISM ? 4 : 1);
+  return align_up(per * (size_t)plan->m);
+}
+
+size_t mebptt_workspace_bytes(const mebptt_lstm_desc* desc) {
+  if (check_desc(desc) != MEBPTT_OK) return 0;
+  return layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype)).total;
+}
+
+int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_t budget_bytes) {
+  size_t per = mebptt_unit_bytes(desc) * (kind == MEBPTT_ISM ? 4 : 1);
+  if (per == 0) return 0;
+  size_t n = budget_bytes / per;
+  return n > 0x7fffffff ? 0x7fffffff : (int32_t)n;
+}
+
+int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih, const float* W_hh,
+               const float* b, const float* x, const float* dy, const float* h0, const float* c0, void* slots,
+               size_t slots_bytes, void* workspace, size_t workspace_bytes, float* dW_ih, float* dW_hh, float* db,
+               float* dh0, float* dc0, float* dx, float* y_out, mebptt_stats* stats, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!plan) return set_error(MEBPTT_EINVAL, "plan is NULL");
+  if (plan->t != desc->t) return set_error(MEBPTT_ESHAPE, "plan is for t=%d, descriptor says t=%d", plan->t, desc->t);
+  if (plan->ops.empty()) return set_error(MEBPTT_EINVAL, "plan carries no LSTM schedule (tables only)");
+  if (!W_ih || !W_hh || !x || !dW_ih || !dW_hh || !db || !dh0 || !dc0)
+    return set_error(MEBPTT_EINVAL, "a required device pointer is NULL");
+  if (desc->loss == 0 && !dy) return set_error(MEBPTT_EINVAL, "dy is NULL but loss == 0");
+  if (!slots) return set_error(MEBPTT_ENOMEM_SLOTS, "slots is NULL");
+  if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
+  if (slots_bytes < mebptt_slot_pool_bytes(desc, plan))
+    return set_error(MEBPTT_ENOMEM_SLOTS, "slot pool has %zu bytes, the plan needs %zu", slots_bytes,
+                     mebptt_slot_pool_bytes(desc, plan));
+  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype);
+  const Workspace w = layout(d);
+  if (workspace_bytes < w.total)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  if (misaligned(slots, ALIGN) || misaligned(workspace, ALIGN))
+    return set_error(MEBPTT_EWORKSPACE, "slots and workspace must be 256-byte aligned");
+  const void* f32ptrs[] = {W_ih, W_hh, b, x, dy, h0, c0, dW_ih, dW_hh, db, dh0, dc0, dx, y_out};
+  for (const void* p : f32ptrs)
+    if (p && misaligned(p, 16)) return set_error(MEBPTT_EINVAL, "device arrays must be 16-byte aligned");
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  const size_t plane = (size_t)d.B * d.H;
+  const size_t unit = 2 * plane;   // floats
+  float* state = reinterpret_cast<float*>(ws + w.state);
+  float* slot0 = reinterpret_cast<float*>(slots);
+  auto loc = [&](int32_t l) -> float* {
+    if (l >= 0) return slot0 + (size_t)l * unit;
+    switch (l) {
+      case MEBPTT_LOC_T0: return state;
+      case MEBPTT_LOC_T1: return state + unit;
+      case MEBPTT_LOC_CORE: return state + 2 * unit;
+      case MEBPTT_LOC_INIT: return state + 5 * unit;
+      default: return nullptr;
+    }
+  };
+  const int64_t pool_units = (int64_t)plan->m * (plan->kind == MEBPTT_ISM ? 4 : 1);
+  // Host-side check of every location before anything is enqueued.
+  for (const mebptt_op& op : plan->ops) {
+    const int32_t locs[3] = {op.src, op.dst, op.prev};
+    for (int i = 0; i < 3; ++i) {
+      int32_t l = locs[i];
+      if (i == 2 && l == MEBPTT_LOC_NONE) continue;
+      int64_t span = (i == 1 && (op.keep || op.op == MEBPTT_OP_BWD)) ? 3 : 1;
+      if (l >= 0 ? (l + span > pool_units) : (loc(l) == nullptr))
+        return set_error(MEBPTT_EINVAL, "schedule names a location outside the pool");
+    }
+    if (op.step < 1 || op.step + op.count - 1 > desc->t) return set_error(MEBPTT_EINVAL, "schedule step out of range");
+  }
+
+  float* bp = reinterpret_cast<float*>(ws + w.bp);
+  float* dc = reinterpret_cast<float*>(ws + w.dc);
+  void* Wp = ws + w.Wp;
+  void* WTh = ws + w.WTh;
+  void* WTx = ws + w.WTx;
+  const size_t op_b = d.op_bytes();
+
+  // Set-up: operand copies of the weights, zeroed staging (the padding must stay zero), start state.
+  HIP_TRY(launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st));
+  HIP_TRY(launch_fill_zero(ws + w.dc, w.total - w.dc, st));
+  HIP_TRY(launch_init_state(d, h0, c0, plan->kind == MEBPTT_ISM ? loc(MEBPTT_LOC_INIT) : loc(0), st));
+
+  int64_t fwd = 0, bwd = 0;
+  bool first_chunk = true;
+  const int t = desc->t, CH = d.CH;
+  const size_t dG_step = (size_t)d.BP * d.G4 * op_b;   // bytes of one step inside a dG chunk buffer
+  for (const mebptt_op& op : plan->ops) {
+    if (op.op == MEBPTT_OP_FWD_RUN) {
+      const float* cur = loc(op.src);
+      for (int j = 1; j <= op.count; ++j) {
+        const int step = op.step + j - 1;
+        float* dst = (j == op.count) ? loc(op.dst)
+                                     : (j == op.count - 1 ? loc(op.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
+        float* gates = (j == op.count && op.keep) ? dst + unit : nullptr;
+        HIP_TRY(launch_forward(d, Wp, bp, x + (size_t)(step - 1) * d.B * d.I, cur, dst, gates, st));
+        cur = dst;
+        ++fwd;
+      }
+    } else if (op.op == MEBPTT_OP_BWD) {
+      const int s = op.step;
+      const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
+      BackwardArgs a{};
+      a.WTh = WTh;
+      a.dG_next = (s == t) ? nullptr : ws + w.dG[(s / CH) & 1] + (size_t)(s % CH) * dG_step;
+      a.state = loc(op.dst);
+      a.prev = loc(op.src);
+      a.dy_s = (desc->loss == 0 && s >= desc->dy_first_step) ? dy + (size_t)(s - desc->dy_first_step) * plane : nullptr;
+      a.dy_is_h = desc->loss == 1;
+      a.dc = dc;
+      a.dG_cur = ws + w.dG[buf] + (size_t)slot * dG_step;
+      a.dGT = ws + w.dGT[buf];
+      a.aT = ws + w.aT[buf];
+      a.col0 = slot * d.B;
+      a.y_out_s = y_out ? y_out + (size_t)(s - 1) * plane : nullptr;
+      HIP_TRY(launch_backward(d, a, st));
+      ++bwd;
+      if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
+        const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
+        const size_t x_off = (size_t)chunk * CH * d.B * d.I;
+        HIP_TRY(launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st));
+        HIP_TRY(launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st));
+        if (dx) HIP_TRY(launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st));
+        first_chunk = false;
+      }
+    } else {
+      return set_error(MEBPTT_EINVAL, "unknown schedule entry %d", op.op);
+    }
+  }
+  // dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
+  HIP_TRY(launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st));
+  HIP_TRY(launch_copy_plane(d, dc, dc0, st));
+
+  if (stats) {
+    stats->forward_ops = fwd;
+    stats->backward_ops = bwd;
+    stats->peak = plan->peak;
+    stats->reserved = 0;
+    stats->peak_slot_bytes = (size_t)plan->peak * mebptt_unit_bytes(desc) * (plan->kind == MEBPTT_ISM ? 4 : 1);
+  }
+  return MEBPTT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+"""Buffer management around ``mebptt_run`` for tests and benchmarks.
+
+Allocates the device buffers a run needs through PyTorch (inputs, outputs, slot pool,
+workspace) and calls the binding.  It performs no arithmetic of its own.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as mb
+from .workloads import Inputs, Workload
+
+
+@dataclasses.dataclass
+class Outputs:
+    dW_ih: np.ndarray
+    dW_hh: np.ndarray
+    db: np.ndarray
+    dh0: np.ndarray
+    dc0: np.ndarray
+    dx: Optional[np.ndarray]
+    y: Optional[np.ndarray]
+    stats: mb.mebptt_stats
+
+
+class Session:
+    """Device-resident inputs and outputs of one workload; `run` enqueues one gradient step."""
+
+    def __init__(self, w: Workload, inp: Inputs, *, kind: Optional[int] = None, m: Optional[int] = None,
+                 gemm_dtype: Optional[int] = None, want_dx: bool = True, want_y: bool = True,
+                 pass_null_state: bool = False, device: str = "cuda:0", plan: Optional[mb.Plan] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("mebptt needs a GPU: no HIP device is visible")
+        self.w = w
+        self.dev = torch.device(device)
+        self.kind = w.kind if kind is None else kind
+        self.m = w.m if m is None else m
+        self.desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype if gemm_dtype is None else gemm_dtype, w.loss,
+                                 w.dy_first_step)
+        self.plan = plan if plan is not None else mb.mebptt_plan(w.t, self.m, self.kind, w.alpha, w.beta)
+        dev = self.dev
+        up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.W_ih, self.W_hh, self.b, self.x, self.dy = up(inp.W_ih), up(inp.W_hh), up(inp.b), up(inp.x), up(inp.dy)
+        self.h0 = None if pass_null_state else up(inp.h0)
+        self.c0 = None if pass_null_state else up(inp.c0)
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.dW_ih = torch.empty((4 * w.H, w.I), **f32)
+        self.dW_hh = torch.empty((4 * w.H, w.H), **f32)
+        self.db = torch.empty((4 * w.H,), **f32)
+        self.dh0 = torch.empty((w.B, w.H), **f32)
+        self.dc0 = torch.empty((w.B, w.H), **f32)
+        self.dx = torch.empty((w.t, w.B, w.I), **f32) if want_dx else None
+        self.y = torch.empty((w.t, w.B, w.H), **f32) if want_y else None
+        self.slot_bytes = mb.mebptt_slot_pool_bytes(self.desc, self.plan)
+        self.ws_bytes = mb.mebptt_workspace_bytes(self.desc)
+        # 0xFF bytes are NaNs as float32: stale memory can never pass for a valid result
+        self.slots = torch.full((self.slot_bytes,), 0xFF, dtype=torch.uint8, device=dev)
+        self.workspace = torch.full((self.ws_bytes,), 0xFF, dtype=torch.uint8, device=dev)
+
+    def run(self, stream: Optional[int] = None) -> mb.mebptt_stats:
+        return mb.mebptt_run(self.desc, self.plan, self.W_ih, self.W_hh, self.b, self.x, self.dy, self.h0, self.c0,
+                             self.slots, self.workspace, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
+                             self.dx, self.y, stream)
+
+    def run_and_fetch(self) -> Outputs:
+        stats = self.run()
+        torch.cuda.synchronize(self.dev)
+        dn = lambda t: None if t is None else t.cpu().numpy()
+        return Outputs(dn(self.dW_ih), dn(self.dW_hh), dn(self.db), dn(self.dh0), dn(self.dc0), dn(self.dx),
+                       dn(self.y), stats)

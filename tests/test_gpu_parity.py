@@ -1,0 +1,130 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances (relative Frobenius error per output tensor):
+  fp32 GEMM operands 1e-4, bf16 GEMM operands 2e-2; forward-operation counts bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import lstm_bptt as ob
+from oracle import policy_dp as dp
+from paper_1606_03401_amd import binding as mb
+from paper_1606_03401_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {wl.GEMM_FP32: 1e-4, wl.GEMM_BF16: 2e-2}
+
+
+def rel_err(a, ref):
+    ref = np.asarray(ref, np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(np.asarray(a, np.float64) - ref) / (den if den > 0 else 1.0))
+
+
+def oracle_cost(kind, t, m, alpha=4, beta=3):
+    if kind == wl.KIND_HSM:
+        return int(dp.hsm_tables(t, m)[0][t, m])
+    if kind == wl.KIND_ISM:
+        return int(dp.ism_tables(t, m)[0][t, m])
+    return int(dp.msm_tables(t, m, alpha, beta)[0][t, m])
+
+
+def check_against_oracle(w, inp, out, ref, tol, label=""):
+    worst = {}
+    for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+        got = getattr(out, name)
+        if got is None:
+            continue
+        assert np.all(np.isfinite(got)), f"{label}{name} has non-finite values"
+        worst[name] = rel_err(got, getattr(ref, name))
+    bad = {k: v for k, v in worst.items() if not v <= tol}
+    assert not bad, f"{label} relative errors above {tol}: {bad} (all: {worst})"
+    return worst
+
+
+def run_case(w, *, kind=None, m=None, nonzero=False, null_state=False, want_dx=True, ref=None, inp=None):
+    from paper_1606_03401_amd.session import Session
+    inp = inp if inp is not None else wl.make_inputs(w, nonzero_state=nonzero, nonzero_bias=nonzero)
+    if ref is None:
+        ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+    kind = w.kind if kind is None else kind
+    m = w.m if m is None else m
+    s = Session(w, inp, kind=kind, m=m, want_dx=want_dx, pass_null_state=null_state)
+    out = s.run_and_fetch()
+    assert out.stats.forward_ops == oracle_cost(kind, w.t, m, w.alpha, w.beta)
+    assert out.stats.backward_ops == w.t
+    assert out.stats.peak <= m
+    assert out.stats.peak_slot_bytes <= s.slot_bytes
+    errs = check_against_oracle(w, inp, out, ref, TOL[w.gemm_dtype], label=f"{w.name} kind={kind} m={m}: ")
+    return out, ref, inp, errs
+
+
+def test_config1_named_budget():
+    run_case(wl.CONFIGS["cfg1"])
+
+
+def test_config1_every_budget_every_strategy():
+    """t = 20: every budget, all three strategies; the result may not depend on the budget at
+    all (recomputation repeats the same arithmetic), so runs are also compared bit for bit."""
+    w = wl.CONFIGS["cfg1"]
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, 1)
+    first = None
+    for kind, budgets in ((wl.KIND_HSM, range(1, 21)), (wl.KIND_ISM, range(1, 21)), (wl.KIND_MSM, [1, 2, 3, 4, 5, 7, 8, 11, 16, 30, 80])):
+        for m in budgets:
+            out, _, _, _ = run_case(w, kind=kind, m=m, ref=ref, inp=inp)
+            if first is None:
+                first = out
+            for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+                assert np.array_equal(getattr(out, name), getattr(first, name)), (kind, m, name)
+
+
+@pytest.mark.parametrize("dtype", [wl.GEMM_FP32, wl.GEMM_BF16])
+@pytest.mark.parametrize("B,I,H,t,kind,m", [
+    (5, 7, 9, 6, wl.KIND_HSM, 3),          # nothing a multiple of anything
+    (37, 50, 72, 9, wl.KIND_ISM, 2),       # ragged batch tile, several unit tiles
+    (64, 40, 200, 12, wl.KIND_MSM, 9),     # several k-steps, ragged tail in K
+    (130, 96, 136, 7, wl.KIND_HSM, 4),     # more than two batch tiles per workgroup row
+    (1, 1, 1, 3, wl.KIND_HSM, 2),          # degenerate
+])
+def test_ragged_shapes(B, I, H, t, kind, m, dtype):
+    for loss, first in ((wl.LOSS_EXTERNAL_DY, 1), (wl.LOSS_EXTERNAL_DY, max(1, t - 1)), (wl.LOSS_HALF_SUM_H2, 1)):
+        w = wl.Workload("ragged", B=B, I=I, H=H, t=t, kind=kind, m=m, gemm_dtype=dtype, loss=loss,
+                        dy_first_step=first, seed=100 + B)
+        run_case(w, nonzero=True)
+
+
+def test_null_state_and_bias_and_no_dx():
+    w = wl.CONFIGS["cfg1"].scaled(loss=wl.LOSS_EXTERNAL_DY)
+    out, _, _, _ = run_case(w, null_state=True, want_dx=False)
+    assert out.dx is None
+
+
+def test_single_step_sequence():
+    for kind in (wl.KIND_HSM, wl.KIND_ISM, wl.KIND_MSM):
+        w = wl.CONFIGS["cfg1"].scaled(t=1, kind=kind, m=1)
+        run_case(w, nonzero=True)
+
+
+def test_error_paths_launch_nothing():
+    import torch
+    from paper_1606_03401_amd.session import Session
+    w = wl.CONFIGS["cfg1"]
+    inp = wl.make_inputs(w)
+    s = Session(w, inp)
+    s.dW_ih.fill_(7.0)
+    small = s.slots[: max(256, s.slot_bytes // 2)]
+    with pytest.raises(mb.MebpttError) as e:
+        mb.mebptt_run(s.desc, s.plan, s.W_ih, s.W_hh, s.b, s.x, s.dy, s.h0, s.c0, small, s.workspace,
+                      s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0)
+    assert e.value.code == mb.ENOMEM_SLOTS
+    with pytest.raises(mb.MebpttError) as e:
+        mb.mebptt_run(s.desc, s.plan, s.W_ih, s.W_hh, s.b, s.x, s.dy, s.h0, s.c0, s.slots, s.workspace[:1024],
+                      s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0)
+    assert e.value.code == mb.EWORKSPACE
+    other = mb.mebptt_plan(w.t + 1, 4, mb.HSM)
+    with pytest.raises(mb.MebpttError) as e:
+        mb.mebptt_run(s.desc, other, s.W_ih, s.W_hh, s.b, s.x, s.dy, s.h0, s.c0, s.slots, s.workspace,
+                      s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0)
+    assert e.value.code == mb.ESHAPE
+    torch.cuda.synchronize()
+    assert bool((s.dW_ih == 7.0).all())

@@ -1,0 +1,179 @@
+"""Host-side tests of the library's planner (no GPU): policy tables bit-exact against the
+oracle's dynamic programs, and the flattened schedule checked by a symbolic memory model."""
+import numpy as np
+import pytest
+
+from oracle import executor_sim as ex
+from oracle import policy_dp as dp
+from paper_1606_03401_amd import binding as mb
+
+
+def _assert_tables_equal(plan, kind, oracle):
+    if kind == mb.MSM:
+        C, C1, C2, D1, D2, H = oracle
+        assert np.array_equal(plan.cost(0), C)
+        assert np.array_equal(plan.cost(1), C1)
+        assert np.array_equal(plan.cost(2), C2)
+        assert np.array_equal(plan.split(1), D1)
+        assert np.array_equal(plan.split(2), D2)
+        assert np.array_equal(plan.choice(), H)
+        assert plan.split(0) is None
+    else:
+        C, D = oracle
+        assert np.array_equal(plan.cost(0), C)
+        assert np.array_equal(plan.split(0), D)
+        assert plan.choice() is None and plan.cost(1) is None
+
+
+def check_schedule(plan, t, m, kind, exact_peak=True):
+    """Replays the schedule on a symbolic memory: every read must find exactly the state it
+    expects, backward steps must come in the order t..1, and no unit beyond the pool is touched."""
+    units_per = 4 if kind == mb.ISM else 1
+    capacity = m * units_per
+    mem = {}
+    if kind == mb.ISM:
+        mem[mb.LOC_INIT] = ("hc", 0)
+    else:
+        mem[0] = ("hc", 0)
+    touched = 0 if kind == mb.ISM else 1
+    next_bwd = t
+    forwards = 0
+
+    def put(loc, label):
+        nonlocal touched
+        assert loc != mb.LOC_NONE
+        if loc >= 0:
+            assert loc < capacity, f"unit {loc} outside the pool of {capacity}"
+            touched = max(touched, loc + 1)
+        else:
+            assert loc in (mb.LOC_T0, mb.LOC_T1, mb.LOC_CORE, mb.LOC_CORE - 1, mb.LOC_CORE - 2) or loc <= -100
+        mem[loc] = label
+
+    def gate_loc(dst, k):
+        return dst + k if dst >= 0 else (-100 - k)      # the working core's private gate units
+
+    for op in plan.schedule():
+        if op["op"] == mb.OP_FWD_RUN:
+            n, first = int(op["count"]), int(op["step"])
+            assert n >= 1
+            assert mem.get(int(op["src"])) == ("hc", first - 1), (op, mem.get(int(op["src"])))
+            cur = int(op["src"])
+            for j in range(1, n + 1):
+                step = first + j - 1
+                assert mem.get(cur) == ("hc", step - 1)
+                if j == n:
+                    dst = int(op["dst"])
+                elif j == n - 1:
+                    dst = int(op["prev"])
+                else:
+                    dst = mb.LOC_T1 if (j & 1) else mb.LOC_T0
+                assert dst != cur
+                put(dst, ("hc", step))
+                if j == n and op["keep"]:
+                    put(gate_loc(dst, 1), ("if", step))
+                    put(gate_loc(dst, 2), ("go", step))
+                cur = dst
+                forwards += 1
+        else:
+            assert op["op"] == mb.OP_BWD
+            s = int(op["step"])
+            assert s == next_bwd
+            dst = int(op["dst"])
+            assert mem.get(dst) == ("hc", s)
+            assert mem.get(gate_loc(dst, 1)) == ("if", s)
+            assert mem.get(gate_loc(dst, 2)) == ("go", s)
+            assert mem.get(int(op["src"])) == ("hc", s - 1), (op, mem.get(int(op["src"])))
+            next_bwd -= 1
+    assert next_bwd == 0
+    assert forwards == plan.forward_ops
+    assert touched <= capacity
+    assert (touched + units_per - 1) // units_per <= plan.peak
+    if exact_peak:
+        assert (touched + units_per - 1) // units_per == plan.peak
+    return forwards
+
+
+@pytest.mark.parametrize("t,m", [(1, 1), (2, 1), (5, 1), (20, 4), (10, 4), (4, 4), (64, 9), (300, 40), (1000, 50)])
+def test_hsm_tables_and_schedule(t, m):
+    plan = mb.mebptt_plan(t, m, mb.HSM)
+    C, D = dp.hsm_tables(t, m)
+    _assert_tables_equal(plan, mb.HSM, (C, D))
+    assert plan.forward_ops == C[t, m]
+    assert check_schedule(plan, t, m, mb.HSM) == C[t, m]
+    assert plan.peak <= m
+    tr = ex.execute_hsm(D, t, m)
+    assert plan.peak == tr.peak and plan.forward_ops == tr.forwards
+
+
+@pytest.mark.parametrize("t,m", [(1, 1), (2, 1), (7, 1), (20, 4), (20, 20), (64, 9), (300, 40), (1000, 100)])
+def test_ism_tables_and_schedule(t, m):
+    plan = mb.mebptt_plan(t, m, mb.ISM)
+    C, D = dp.ism_tables(t, m)
+    _assert_tables_equal(plan, mb.ISM, (C, D))
+    assert plan.forward_ops == C[t, m]
+    check_schedule(plan, t, m, mb.ISM)
+    tr = ex.execute_ism(D, t, m)
+    assert plan.peak == tr.peak <= m
+
+
+@pytest.mark.parametrize("t,m,alpha,beta", [(1, 1, 4, 3), (2, 2, 4, 3), (9, 1, 4, 3), (20, 4, 4, 3), (20, 13, 4, 3),
+                                            (64, 30, 4, 3), (64, 30, 4, 4), (300, 120, 4, 3), (40, 200, 4, 3),
+                                            (50, 37, 5, 4), (50, 37, 6, 3)])
+def test_msm_tables_and_schedule(t, m, alpha, beta):
+    plan = mb.mebptt_plan(t, m, mb.MSM, alpha, beta)
+    tabs = dp.msm_tables(t, m, alpha, beta)
+    _assert_tables_equal(plan, mb.MSM, tabs)
+    assert plan.forward_ops == tabs[0][t, m]
+    check_schedule(plan, t, m, mb.MSM, exact_peak=(alpha == 4))
+    tr = ex.execute_msm(tabs[3], tabs[4], tabs[5], t, m, alpha, beta)
+    assert plan.peak == tr.peak <= m
+
+
+def test_msm_tables_only_for_non_lstm_state_sizes():
+    plan = mb.mebptt_plan(30, 12, mb.MSM, 3, 2)          # valid tables, but not an LSTM layout
+    _assert_tables_equal(plan, mb.MSM, dp.msm_tables(30, 12, 3, 2))
+    assert len(plan.schedule()) == 0 and plan.forward_ops == 0
+
+
+def test_every_budget_config1():
+    """Configuration 1 (t = 20): every budget 1..20, all three strategies."""
+    for m in range(1, 21):
+        for kind, tabs in ((mb.HSM, dp.hsm_tables(20, m)), (mb.ISM, dp.ism_tables(20, m))):
+            plan = mb.mebptt_plan(20, m, kind)
+            assert plan.forward_ops == tabs[0][20, m]
+            check_schedule(plan, 20, m, kind)
+    for m in range(1, 81):
+        plan = mb.mebptt_plan(20, m, mb.MSM, 4, 3)
+        assert plan.forward_ops == dp.msm_tables(20, m, 4, 3)[0][20, m]
+        check_schedule(plan, 20, m, mb.MSM)
+
+
+def test_full_size_tables_config4_and_config5():
+    """The two largest tables of the named configurations."""
+    plan = mb.mebptt_plan(10000, 100, mb.HSM)
+    C, D = dp.hsm_tables(10000, 100)
+    _assert_tables_equal(plan, mb.HSM, (C, D))
+    assert plan.forward_ops == C[10000, 100]
+    check_schedule(plan, 10000, 100, mb.HSM)
+    plan = mb.mebptt_plan(1000, 1000, mb.MSM, 4, 3)
+    tabs = dp.msm_tables(1000, 1000, 4, 3)
+    _assert_tables_equal(plan, mb.MSM, tabs)
+    for m in (1000, 250, 50, 31, 2):
+        p = mb.mebptt_plan(1000, m, mb.MSM, 4, 3)
+        assert p.forward_ops == tabs[0][1000, m]
+        check_schedule(p, 1000, m, mb.MSM)
+        assert p.peak <= m
+
+
+def test_constant_memory_is_run_length_encoded():
+    plan = mb.mebptt_plan(2000, 1, mb.HSM)
+    assert plan.forward_ops == 2000 * 2001 // 2
+    assert len(plan.schedule()) == 2 * 2000
+
+
+def test_errors():
+    for args in [(0, 4, mb.HSM), (5, 0, mb.HSM), (5, 4, 7), (5, 4, mb.MSM, 1, 1), (5, 4, mb.MSM, 4, 5), (5, 4, mb.MSM, 4, 0)]:
+        with pytest.raises(mb.MebpttError) as e:
+            mb.mebptt_plan(*args)
+        assert e.value.code == mb.EINVAL
+        assert mb.mebptt_last_error()
