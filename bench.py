@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one LSTM gradient step under the DP checkpoint policy.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--sweep]
+
+A "step" is one call of ``mebptt_run``: every forward operation, every recomputation and every
+backward operation of the schedule for one batch of synthetic sequences.  Inputs are resident in
+device memory before the timed region.  Prints ONE JSON line on stdout (everything else goes to
+stderr): throughput in time-steps/s at the named budget, the measured and theoretical cost
+ratio against store-everything BPTT, the roofline position of the dominant kernel measured
+with HIP events on the run's stream, and the CPU oracle timed on this host as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "LSTM BPTT time-steps/s at budget m; cost ratio vs store-all BPTT"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+KIND_NAMES = {0: "HSM", 1: "ISM", 2: "MSM"}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_runs(sess, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        sess.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sess.run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def forward_bytes(w):
+    """Algorithmic bytes of one forward operation: the gate weights once in the GEMM operand
+    type, x_t once, and the hidden state (h, c) read and written once in fp32."""
+    op = 2 if w.gemm_dtype else 4
+    return 4 * w.H * (w.I + w.H) * op + 4 * w.B * w.I + 16 * w.B * w.H
+
+
+def forward_flops(w):
+    return 8 * w.B * w.H * (w.I + w.H)
+
+
+def pmc_traffic():
+    """HBM bytes per forward launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "forward_kernel_cfg2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, inp, budget_s=20.0):
+    """The oracle (float64 store-everything BPTT) on this host, on a prefix of the workload's
+    sequence sized to take roughly `budget_s` seconds."""
+    import numpy as np
+    from oracle import lstm_bptt as ob
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    probe = min(8, w.t)
+
+    def run(n):
+        dy = None if inp.dy is None else inp.dy[:max(0, n - w.dy_first_step + 1)]
+        first = min(w.dy_first_step, n)
+        if inp.dy is not None and dy.shape[0] == 0:
+            dy, first = np.zeros((1,) + inp.dy.shape[1:], np.float32), n
+        t0 = time.perf_counter()
+        ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[:n], inp.h0, inp.c0, dy, first)
+        return time.perf_counter() - t0
+
+    per_step = run(probe) / probe
+    n = int(max(probe, min(w.t, budget_s / max(per_step, 1e-9))))
+    dt = run(n)
+    return {"value": n / dt, "unit": "time-steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n} of {w.t} steps of {w.name} (float64 store-everything BPTT, numpy), {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--sweep", action="store_true", help="also time the budget sweep m = t .. 5%% of t (stderr)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: the path is single-device by design (see DESIGN.md); --gpus must be 1")
+        return 2
+
+    import torch
+    from paper_1606_03401_amd import binding as mb
+    from paper_1606_03401_amd import workloads as wl
+    from paper_1606_03401_amd.session import Session
+
+    if not torch.cuda.is_available():
+        log("no GPU visible: the HIP path cannot run")
+        return 1
+    w = wl.CONFIGS[args.workload]
+    log(f"[bench] {mb.mebptt_version()} workload {w}")
+    inp = wl.make_inputs(w)
+    sess = Session(w, inp, want_dx=True, want_y=False)
+    ms = time_runs(sess, args.steps, args.warmup) * 1e3
+    C = sess.plan.forward_ops
+    log(f"[bench] {KIND_NAMES[sess.kind]} m={sess.m}: {ms:.3f} ms/step, forward ops {C}, peak {sess.plan.peak}")
+
+    # dominant kernel: event-bracketed samples on the run's stream, in extra profiled steps
+    mb.mebptt_profile_enable(8)
+    prof_steps = max(1, min(args.steps, 3))
+    for _ in range(prof_steps):
+        sess.run()
+    torch.cuda.synchronize()
+    prof = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    classes = {}
+    for k, name in enumerate(mb.K_NAMES):
+        n_s = prof.sampled[k]
+        avg_us = prof.sampled_ms[k] / n_s * 1e3 if n_s else None
+        classes[name] = {"launches_per_step": prof.launches[k] / prof_steps, "avg_us": avg_us}
+        log(f"[bench] kernel class {name}: {prof.launches[k] / prof_steps:.0f} launches/step, "
+            f"avg {avg_us if avg_us is None else round(avg_us, 2)} us (event-bracketed, {n_s} samples)")
+    fwd_us = classes["forward"]["avg_us"]
+    achieved = forward_bytes(w) / (fwd_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "forward_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": pmc_traffic(),
+                "avg_launch_us": fwd_us, "bytes_per_launch": forward_bytes(w),
+                "mfma_tflops": forward_flops(w) / (fwd_us * 1e-6) / 1e12,
+                "mfma_frac": forward_flops(w) / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    # store-everything BPTT through the same path: internal-state slots for every step
+    store_all_ms = None
+    try:
+        sa = Session(w, inp, kind=wl.KIND_ISM, m=w.t, want_dx=True, want_y=False)
+        store_all_ms = time_runs(sa, max(2, args.steps // 2), 1) * 1e3
+        log(f"[bench] store-all (ISM m=t): {store_all_ms:.3f} ms/step, forward ops {sa.plan.forward_ops}")
+        del sa
+    except Exception as e:   # e.g. the store-all pool does not fit
+        log(f"[bench] store-all run skipped: {e}")
+
+    if args.sweep:
+        for kind in (wl.KIND_HSM, wl.KIND_ISM):
+            for m in (w.t, w.t // 2, w.t // 4, w.t // 10, w.t // 20):
+                s2 = Session(w, inp, kind=kind, m=m, want_dx=True, want_y=False)
+                ms2 = time_runs(s2, max(2, args.steps // 2), 1) * 1e3
+                Cm = s2.plan.forward_ops
+                log(f"[sweep] {KIND_NAMES[kind]} m={m}: {ms2:.3f} ms, {w.t / ms2 * 1e3:.0f} steps/s, C={Cm}, "
+                    f"theoretical ratio {(Cm + 2 * w.t) / (3 * w.t):.3f}, "
+                    f"measured {ms2 / store_all_ms if store_all_ms else float('nan'):.3f}")
+                del s2
+
+    flops_exec = (C + 2 * w.t) * forward_flops(w)
+    flops_useful = 3 * w.t * forward_flops(w)
+    result = {
+        "metric": METRIC, "value": w.t / (ms * 1e-3), "unit": "time-steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_dtype else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: single-layer LSTM I={w.I} H={w.H} B={w.B} t={w.t}, "
+                               f"BPTT-{KIND_NAMES[sess.kind]} budget m={sess.m}, seed {w.seed}",
+                   "budget_m": sess.m, "forward_ops": C, "peak_slots": sess.plan.peak,
+                   "slot_pool_bytes": sess.slot_bytes, "workspace_bytes": sess.ws_bytes},
+        "cost_ratio_vs_store_all": {"measured": (ms / store_all_ms) if store_all_ms else None,
+                                    "theoretical": (C + 2 * w.t) / (3 * w.t), "store_all_ms": store_all_ms},
+        "gflops": {"executed": flops_exec / (ms * 1e-3) / 1e9, "useful": flops_useful / (ms * 1e-3) / 1e9,
+                   "executed_frac_of_mfma_peak": flops_exec / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "kernel_classes": classes,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, inp)
+        log(f"[bench] cpu baseline {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -174,6 +174,29 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
                float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
                float* dx, float* y_out, mebptt_stats* stats, void* stream);
 
+/* ---- measurement hooks ---------------------------------------------------------------------
+ * Kernel classes of the hot path, for timing with HIP events on the run's own stream. */
+enum {
+  MEBPTT_K_FORWARD = 0,  /* gate GEMM + LSTM pointwise (one forward operation)                 */
+  MEBPTT_K_BACKWARD = 1, /* dh GEMM + loss-gradient injection + pointwise backward            */
+  MEBPTT_K_WGRAD = 2,    /* time-batched dW/db accumulation (with the x transpose feeding it) */
+  MEBPTT_K_DGRAD = 3,    /* time-batched dx GEMM and the final dh0 GEMM                       */
+  MEBPTT_K_SETUP = 4,    /* operand copies of the weights, zero fills, start-state copy       */
+  MEBPTT_K_CLASSES = 5
+};
+typedef struct {
+  int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
+  int64_t sampled[MEBPTT_K_CLASSES];  /* launches that were bracketed by an event pair   */
+  double sampled_ms[MEBPTT_K_CLASSES]; /* sum of the bracketed launches' elapsed times    */
+} mebptt_profile;
+/* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
+ * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;
+ * 0 switches sampling off (the default).  Not thread-safe against concurrent mebptt_run. */
+int mebptt_profile_enable(int32_t every_n);
+/* Waits for the recorded events, writes the sums since the last collect (host memory) and
+ * clears them.  Errors: EINVAL, EHIP. */
+int mebptt_profile_collect(mebptt_profile* out);
+
 const char* mebptt_last_error(void);
 /* Library version string, e.g. "mebptt 0.1 (gfx950)". */
 const char* mebptt_version(void);

@@ -42,6 +42,15 @@ class mebptt_stats(C.Structure):
                 ("reserved", C.c_int32), ("peak_slot_bytes", C.c_size_t)]
 
 
+K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_CLASSES = 0, 1, 2, 3, 4, 5
+K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup")
+
+
+class mebptt_profile(C.Structure):
+    _fields_ = [("launches", C.c_int64 * K_CLASSES), ("sampled", C.c_int64 * K_CLASSES),
+                ("sampled_ms", C.c_double * K_CLASSES)]
+
+
 # name -> (restype, argtypes): every symbol the header declares
 _P = C.c_void_p
 _DESC = C.POINTER(mebptt_lstm_desc)
@@ -63,6 +72,8 @@ SIGNATURES = {
     "mebptt_units_for_bytes": (C.c_int32, [_DESC, C.c_int32, C.c_size_t]),
     "mebptt_run": (C.c_int, [_DESC, _P] + [_P] * 7 + [_P, C.c_size_t, _P, C.c_size_t] + [_P] * 7
                    + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_profile_enable": (C.c_int, [C.c_int32]),
+    "mebptt_profile_collect": (C.c_int, [C.POINTER(mebptt_profile)]),
     "mebptt_last_error": (C.c_char_p, []),
     "mebptt_version": (C.c_char_p, []),
 }
@@ -181,6 +192,16 @@ def mebptt_workspace_bytes(desc: mebptt_lstm_desc) -> int:
 
 def mebptt_units_for_bytes(desc: mebptt_lstm_desc, kind: int, budget_bytes: int) -> int:
     return lib().mebptt_units_for_bytes(C.byref(desc), kind, budget_bytes)
+
+
+def mebptt_profile_enable(every_n: int) -> None:
+    _check(lib().mebptt_profile_enable(every_n))
+
+
+def mebptt_profile_collect() -> mebptt_profile:
+    out = mebptt_profile()
+    _check(lib().mebptt_profile_collect(C.byref(out)))
+    return out
 
 
 def _ptr(t) -> Optional[int]:

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <vector>
 
 #include "common.h"
 #include "kernels.h"
@@ -65,6 +66,47 @@ int check_desc(const mebptt_lstm_desc* desc) {
 
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+// ---- optional event sampling (measurement hook) ------------------------------------------------
+struct Sample {
+  int cls;
+  hipEvent_t start, stop;
+};
+struct Profiler {
+  int every_n = 0;
+  int64_t launches[MEBPTT_K_CLASSES] = {};
+  std::vector<Sample> pending;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) {
+      hipEvent_t e = pool.back();
+      pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Profiler g_prof;
+
+// Brackets one launch with events when it falls on the sampling grid.
+template <class F>
+hipError_t timed(int cls, hipStream_t st, F&& launch) {
+  Profiler& p = g_prof;
+  if (p.every_n <= 0) return launch();
+  const bool sample = (p.launches[cls]++ % p.every_n) == 0 && p.pending.size() < 200000;
+  if (!sample) return launch();
+  Sample s{cls, p.get(), p.get()};
+  if (!s.start || !s.stop) return hipErrorOutOfMemory;
+  hipError_t e = hipEventRecord(s.start, st);
+  if (e != hipSuccess) return e;
+  e = launch();
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(s.stop, st);
+  p.pending.push_back(s);
+  return e;
+}
+
 #define HIP_TRY(expr)                                                                                 \
   do {                                                                                                \
     hipError_t e_ = (expr);                                                                           \
@@ -74,6 +116,38 @@ inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 }  // namespace
 
 extern "C" {
+
+int mebptt_profile_enable(int32_t every_n) {
+  if (every_n < 0) return set_error(MEBPTT_EINVAL, "every_n must be >= 0");
+  g_prof.every_n = every_n;
+  return MEBPTT_OK;
+}
+
+int mebptt_profile_collect(mebptt_profile* out) {
+  if (!out) return set_error(MEBPTT_EINVAL, "out is NULL");
+  std::memset(out, 0, sizeof *out);
+  Profiler& p = g_prof;
+  for (int c = 0; c < MEBPTT_K_CLASSES; ++c) {
+    out->launches[c] = p.launches[c];
+    p.launches[c] = 0;
+  }
+  int rc = MEBPTT_OK;
+  for (Sample& s : p.pending) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(s.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, s.start, s.stop);
+    if (e != hipSuccess) {
+      rc = set_error(MEBPTT_EHIP, "event timing failed: %s", hipGetErrorString(e));
+    } else {
+      out->sampled[s.cls] += 1;
+      out->sampled_ms[s.cls] += ms;
+    }
+    p.pool.push_back(s.start);
+    p.pool.push_back(s.stop);
+  }
+  p.pending.clear();
+  return rc;
+}
 
 size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc) {
   if (!desc || desc->B < 1 || desc->H < 1) return 0;
@@ -163,9 +237,11 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   const size_t op_b = d.op_bytes();
 
   // Set-up: operand copies of the weights, zeroed staging (the padding must stay zero), start state.
-  HIP_TRY(launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st));
-  HIP_TRY(launch_fill_zero(ws + w.dc, w.total - w.dc, st));
-  HIP_TRY(launch_init_state(d, h0, c0, plan->kind == MEBPTT_ISM ? loc(MEBPTT_LOC_INIT) : loc(0), st));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st); }));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] {
+    return launch_init_state(d, h0, c0, plan->kind == MEBPTT_ISM ? loc(MEBPTT_LOC_INIT) : loc(0), st);
+  }));
 
   int64_t fwd = 0, bwd = 0;
   bool first_chunk = true;
@@ -179,7 +255,9 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
         float* dst = (j == op.count) ? loc(op.dst)
                                      : (j == op.count - 1 ? loc(op.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
         float* gates = (j == op.count && op.keep) ? dst + unit : nullptr;
-        HIP_TRY(launch_forward(d, Wp, bp, x + (size_t)(step - 1) * d.B * d.I, cur, dst, gates, st));
+        HIP_TRY(timed(MEBPTT_K_FORWARD, st, [&] {
+          return launch_forward(d, Wp, bp, x + (size_t)(step - 1) * d.B * d.I, cur, dst, gates, st);
+        }));
         cur = dst;
         ++fwd;
       }
@@ -199,14 +277,20 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
       a.aT = ws + w.aT[buf];
       a.col0 = slot * d.B;
       a.y_out_s = y_out ? y_out + (size_t)(s - 1) * plane : nullptr;
-      HIP_TRY(launch_backward(d, a, st));
+      HIP_TRY(timed(MEBPTT_K_BACKWARD, st, [&] { return launch_backward(d, a, st); }));
       ++bwd;
       if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
         const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
         const size_t x_off = (size_t)chunk * CH * d.B * d.I;
-        HIP_TRY(launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st));
-        HIP_TRY(launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st));
-        if (dx) HIP_TRY(launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st));
+        HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {
+          hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st);
+          if (e != hipSuccess) return e;
+          return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st);
+        }));
+        if (dx)
+          HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] {
+            return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st);
+          }));
         first_chunk = false;
       }
     } else {
@@ -214,8 +298,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     }
   }
   // dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
-  HIP_TRY(launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st));
-  HIP_TRY(launch_copy_plane(d, dc, dc0, st));
+  HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, st); }));
 
   if (stats) {
     stats->forward_ops = fwd;
