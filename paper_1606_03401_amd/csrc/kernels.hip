@@ -75,27 +75,6 @@ struct Mma<float> {
   }
 };
 
-// VEC consecutive fp32 values row[k .. k+VEC), zero beyond `limit`, converted to the operand type.
-template <class T>
-__device__ inline typename Mma<T>::Frag load_act(const float* __restrict__ row, int k, int limit, bool vec_ok) {
-  constexpr int VEC = Mma<T>::VEC;
-  float v[VEC];
-  if (vec_ok && k + VEC <= limit) {
-#pragma unroll
-    for (int e = 0; e < VEC; e += 4) {
-      float4 q = *reinterpret_cast<const float4*>(row + k + e);
-      v[e] = q.x;
-      v[e + 1] = q.y;
-      v[e + 2] = q.z;
-      v[e + 3] = q.w;
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) v[e] = (k + e < limit) ? row[k + e] : 0.0f;
-  }
-  return Mma<T>::from_f32(v);
-}
-
 __device__ inline float sigmoidf_(float z) { return 1.0f / (1.0f + expf(-z)); }
 
 // ---- small utility kernels -------------------------------------------------------------------
@@ -115,16 +94,41 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Operand arrays the library builds itself are stored "fragment-tiled": for a logical matrix
+// M[rows][K] the element (row, k) lives at
+//     (((row/16) * (K/KSTEP) + k/KSTEP) * 64 + ((k%KSTEP)/VEC)*16 + row%16) * VEC + k%VEC
+// so that the 64 lanes of a wave fetch the fragment of one 16-row tile and one macro step as one
+// contiguous, fully coalesced block of 64*VEC elements (1 KiB).
+template <class T>
+__device__ inline void ft_decode(size_t idx, int nsteps, int& row, int& k) {
+  constexpr int VEC = Mma<T>::VEC, KSTEP = 4 * VEC;
+  const int e = (int)(idx % VEC);
+  const int lane = (int)((idx / VEC) % 64);
+  const size_t blk = idx / (VEC * 64);
+  const int kstep = (int)(blk % nsteps);
+  const int tile = (int)(blk / nsteps);
+  row = tile * 16 + (lane & 15);
+  k = kstep * KSTEP + (lane >> 4) * VEC + e;
+}
+
+template <class T>
+__device__ inline size_t ft_offset(int row, int k, int nsteps) {
+  constexpr int VEC = Mma<T>::VEC, KSTEP = 4 * VEC;
+  return ((((size_t)(row >> 4) * nsteps + k / KSTEP) * 64 + ((k % KSTEP) / VEC) * 16 + (row & 15)) * VEC) + k % VEC;
+}
+
 template <class T>
 __global__ void prep_weights_kernel(Dims d, const float* __restrict__ W_ih, const float* __restrict__ W_hh,
                                     const float* __restrict__ b, T* __restrict__ Wp, float* __restrict__ bp,
                                     T* __restrict__ WTh, T* __restrict__ WTx) {
+  constexpr int KSTEP = 4 * Mma<T>::VEC;
   const size_t nWp = (size_t)d.G4 * d.KP, nWTh = (size_t)d.HP * d.G4, nWTx = (size_t)d.NX * d.G4;
   const size_t total = nWp + nWTh + nWTx + (size_t)d.G4;
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
-    if (idx < nWp) {   // Wp[row'][k], row' = 4u + gate
-      int rowp = (int)(idx / d.KP), k = (int)(idx % d.KP);
+    if (idx < nWp) {   // Wp: logical [G4][KP], row' = 4u + gate
+      int rowp, k;
+      ft_decode<T>(idx, d.KP / KSTEP, rowp, k);
       int u = rowp >> 2, gate = rowp & 3;
       float v = 0.0f;
       if (u < d.H) {
@@ -136,11 +140,12 @@ __global__ void prep_weights_kernel(Dims d, const float* __restrict__ W_ih, cons
         }
       }
       Wp[idx] = (T)v;
-    } else if (idx < nWp + nWTh + nWTx) {   // WTh[n][4u+gate] / WTx[n][4u+gate]
+    } else if (idx < nWp + nWTh + nWTx) {   // WTh: logical [HP][G4]; WTx: logical [NX][G4]; k' = 4u + gate
       size_t j = idx - nWp;
       bool is_h = j < nWTh;
       if (!is_h) j -= nWTh;
-      int n = (int)(j / d.G4), kp = (int)(j % d.G4);
+      int n, kp;
+      ft_decode<T>(j, d.G4 / KSTEP, n, kp);
       int u = kp >> 2, gate = kp & 3;
       float v = 0.0f;
       if (u < d.H) {
@@ -217,104 +222,128 @@ struct FwdParams {
   int B, I, H, HP, KX, KP;
 };
 
-// Workgroup = BT batch tiles x KS k-slices (one wave each); every wave covers NG unit groups
-// (16 gate rows = 4 hidden units each) and reuses its activation fragment across them.
-template <class T, int NG, int BT, int KS>
-__global__ __launch_bounds__(64 * BT * KS) void forward_kernel(FwdParams p) {
+// Raw (unconverted) activation fragment: VEC fp32 values, zero beyond `limit`.
+template <int VEC>
+struct RawAct {
+  float v[VEC];
+};
+template <int VEC>
+__device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int limit, bool vec_ok) {
+  RawAct<VEC> r;
+  if (vec_ok && k + VEC <= limit) {
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) {
+      float4 q = *reinterpret_cast<const float4*>(row + k + e);
+      r.v[e] = q.x;
+      r.v[e + 1] = q.y;
+      r.v[e + 2] = q.z;
+      r.v[e + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) r.v[e] = (k + e < limit) ? row[k + e] : 0.0f;
+  }
+  return r;
+}
+
+// Workgroup = one batch tile (16 sequences) x NG unit groups (4 hidden units = 16 gate rows
+// each); its KS waves split the K axis, every wave issuing all loads of U macro steps before
+// the first MFMA so that several KiB per wave are in flight.  Partial sums meet in LDS and are
+// added in a fixed order; wave g then runs the LSTM pointwise step of unit group g.
+template <class T, int NG, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
+  static_assert(NG <= KS, "one epilogue wave per unit group");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int bt = wave % BT, ks = wave / BT;
   const int lrow = lane & 15, lq = lane >> 4;
   const int group0 = blockIdx.x * NG;
   const int ngroups = p.HP >> 2;
-  const int b0 = (blockIdx.y * BT + bt) * 16;
+  const int b0 = blockIdx.y * 16;
   const int b_ld = min(b0 + lrow, p.B - 1);
   const float* xrow = p.x_s + (size_t)b_ld * p.I;
   const float* hrow = p.src_h + (size_t)b_ld * p.H;
   const bool x_vec = (p.I & 3) == 0, h_vec = (p.H & 3) == 0;
-  const T* wrow[NG];
+  const int nsteps = p.KP / KSTEP;
+  const T* wbase[NG];   // fragment-tiled: tile (group) stride = nsteps * 64 * VEC
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     int grp = min(group0 + g, ngroups - 1);
-    wrow[g] = reinterpret_cast<const T*>(p.Wp) + ((size_t)grp * 16 + lrow) * p.KP + VEC * lq;
+    wbase[g] = reinterpret_cast<const T*>(p.Wp) + ((size_t)grp * nsteps * 64 + lane) * VEC;
   }
   f32x4 acc[NG];
 #pragma unroll
   for (int g = 0; g < NG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int nsteps = p.KP / KSTEP;
-  for (int s = ks; s < nsteps; s += KS) {
-    const int k = s * KSTEP + VEC * lq;
-    typename M::Frag bf = (k < p.KX) ? load_act<T>(xrow, k, p.I, x_vec) : load_act<T>(hrow, k - p.KX, p.H, h_vec);
+  for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
+    RawAct<VEC> rb[U];
+    typename M::Frag af[U][NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      typename M::Frag af = M::load(wrow[g] + (size_t)s * KSTEP);
-      acc[g] = M::mma(af, bf, acc[g]);
+    for (int u = 0; u < U; ++u) {
+      const int s = min(s0 + u * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
+      const int k = s * KSTEP + VEC * lq;
+      rb[u] = (k < p.KX) ? load_raw<VEC>(xrow, k, p.I, x_vec) : load_raw<VEC>(hrow, k - p.KX, p.H, h_vec);
+#pragma unroll
+      for (int g = 0; g < NG; ++g) af[u][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (s0 + u * KS < nsteps) {
+        typename M::Frag bf = M::from_f32(rb[u].v);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = M::mma(af[u][g], bf, acc[g]);
+      }
     }
   }
 
-  if (KS > 1) {
-    __shared__ float red[(KS > 1 ? KS - 1 : 1) * BT * NG * 4 * 64];
-    if (ks > 0) {
+  __shared__ float red[KS * NG * 4 * 64];
 #pragma unroll
-      for (int g = 0; g < NG; ++g)
+  for (int g = 0; g < NG; ++g)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[((((ks - 1) * BT + bt) * NG + g) * 4 + r) * 64 + lane] = acc[g][r];
-    }
-    __syncthreads();
-    if (ks == 0) {
-      for (int q = 1; q < KS; ++q)   // fixed order: results do not depend on scheduling
+    for (int r = 0; r < 4; ++r) red[((wave * NG + g) * 4 + r) * 64 + lane] = acc[g][r];
+  __syncthreads();
+  if (wave >= NG) return;
+  const int g = wave;
+  float G[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < KS; ++q)   // fixed order: results do not depend on scheduling
 #pragma unroll
-        for (int g = 0; g < NG; ++g)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) acc[g][r] += red[((((q - 1) * BT + bt) * NG + g) * 4 + r) * 64 + lane];
-    }
-  }
-  if (ks != 0) return;
+    for (int r = 0; r < 4; ++r) G[r] += red[((q * NG + g) * 4 + r) * 64 + lane];
 
   const int b = b0 + lrow;
-  if (b >= p.B) return;
-#pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    const int u = (group0 + g) * 4 + lq;
-    if (u >= p.H) continue;
-    const float4 bias = *reinterpret_cast<const float4*>(p.bp + 4 * u);
-    const size_t e = (size_t)b * p.H + u;
-    const float gi = sigmoidf_(acc[g][0] + bias.x);
-    const float gf = sigmoidf_(acc[g][1] + bias.y);
-    const float gg = tanhf(acc[g][2] + bias.z);
-    const float go = sigmoidf_(acc[g][3] + bias.w);
-    const float c = gf * p.src_c[e] + gi * gg;
-    const float h = go * tanhf(c);
-    p.dst_h[e] = h;
-    p.dst_c[e] = c;
-    if (p.g_i) {
-      p.g_i[e] = gi;
-      p.g_f[e] = gf;
-      p.g_g[e] = gg;
-      p.g_o[e] = go;
-    }
+  const int u = (group0 + g) * 4 + lq;
+  if (b >= p.B || u >= p.H) return;
+  const float4 bias = *reinterpret_cast<const float4*>(p.bp + 4 * u);
+  const size_t e = (size_t)b * p.H + u;
+  const float gi = sigmoidf_(G[0] + bias.x);
+  const float gf = sigmoidf_(G[1] + bias.y);
+  const float gg = tanhf(G[2] + bias.z);
+  const float go = sigmoidf_(G[3] + bias.w);
+  const float c = gf * p.src_c[e] + gi * gg;
+  const float h = go * tanhf(c);
+  p.dst_h[e] = h;
+  p.dst_c[e] = c;
+  if (p.g_i) {
+    p.g_i[e] = gi;
+    p.g_f[e] = gf;
+    p.g_g[e] = gg;
+    p.g_o[e] = go;
   }
 }
 
-template <class T, int NG, int BT, int KS>
+template <class T, int NG, int KS, int U>
 static hipError_t launch_forward_cfg(const Dims& d, const FwdParams& p, hipStream_t st) {
-  dim3 grid((d.HP / 4 + NG - 1) / NG, (d.BP / 16 + BT - 1) / BT), block(64 * BT * KS);
-  forward_kernel<T, NG, BT, KS><<<grid, block, 0, st>>>(p);
+  dim3 grid((d.HP / 4 + NG - 1) / NG, d.BP / 16), block(64 * KS);
+  forward_kernel<T, NG, KS, U><<<grid, block, 0, st>>>(p);
   return hipGetLastError();
 }
 
 template <class T>
 static hipError_t launch_forward_t(const Dims& d, const FwdParams& p, hipStream_t st) {
-  const int btiles = d.BP / 16;
-  if (btiles >= 4) {
-    // Large hidden sizes: two unit groups per wave halve the activation traffic per gate row.
-    if ((size_t)d.HP / 4 * ((btiles + 3) / 4) >= 2048) return launch_forward_cfg<T, 2, 4, 4>(d, p, st);
-    return launch_forward_cfg<T, 1, 4, 4>(d, p, st);
-  }
-  if (btiles >= 2) return launch_forward_cfg<T, 1, 2, 8>(d, p, st);
-  return launch_forward_cfg<T, 1, 1, 8>(d, p, st);
+  constexpr int KSTEP = 4 * Mma<T>::VEC;
+  const int nsteps = d.KP / KSTEP;
+  if (nsteps <= 8) return launch_forward_cfg<T, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
+  if (nsteps <= 20) return launch_forward_cfg<T, 4, 4, 5>(d, p, st);
+  return launch_forward_cfg<T, 4, 8, 5>(d, p, st);
 }
 
 hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const float* x_s, const float* src_unit,
@@ -359,96 +388,89 @@ struct BwdParams {
   int B, H, HP, G4, NX, KC, BP;
 };
 
-// Workgroup = one tile of 16 hidden units x BT batch tiles x KS k-slices.
-template <class T, int BT, int KS>
-__global__ __launch_bounds__(64 * BT * KS) void backward_kernel(BwdParams p) {
+// Workgroup = one output tile (16 hidden units x 16 sequences); its KS waves split K = 4*HP,
+// each issuing the loads of U macro steps before the first MFMA.  Partial sums meet in LDS; waves
+// 0..3 then each take one of the four hidden units a lane owns and run the pointwise backward.
+template <class T, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
+  static_assert(KS >= 4, "four epilogue waves");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int bt = wave % BT, ks = wave / BT;
   const int lrow = lane & 15, lq = lane >> 4;
   const int n0 = blockIdx.x * 16;
-  const int b0 = (blockIdx.y * BT + bt) * 16;
-  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int b0 = blockIdx.y * 16;
+  __shared__ float red[KS * 4 * 64];
   if (p.dG_next) {
-    const int brow = min(b0 + lrow, p.BP - 1);
-    const T* arow = reinterpret_cast<const T*>(p.WTh) + (size_t)(n0 + lrow) * p.G4 + VEC * lq;
-    const T* brow_p = reinterpret_cast<const T*>(p.dG_next) + (size_t)brow * p.G4 + VEC * lq;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     const int nsteps = p.G4 / KSTEP;
-    for (int s = ks; s < nsteps; s += KS) {
-      typename M::Frag af = M::load(arow + (size_t)s * KSTEP);
-      typename M::Frag bf = M::load(brow_p + (size_t)s * KSTEP);
-      acc = M::mma(af, bf, acc);
-    }
-    if (KS > 1) {
-      __shared__ float red[(KS > 1 ? KS - 1 : 1) * BT * 4 * 64];
-      if (ks > 0) {
+    const T* abase = reinterpret_cast<const T*>(p.WTh) + ((size_t)blockIdx.x * nsteps * 64 + lane) * VEC;
+    const T* bbase = reinterpret_cast<const T*>(p.dG_next) + ((size_t)blockIdx.y * nsteps * 64 + lane) * VEC;
+    for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
+      typename M::Frag af[U], bf[U];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[(((ks - 1) * BT + bt) * 4 + r) * 64 + lane] = acc[r];
+      for (int u = 0; u < U; ++u) {
+        const int s = min(s0 + u * KS, nsteps - 1);
+        af[u] = M::load(abase + (size_t)s * 64 * VEC);
+        bf[u] = M::load(bbase + (size_t)s * 64 * VEC);
       }
-      __syncthreads();
-      if (ks == 0) {
-        for (int q = 1; q < KS; ++q)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[r] += red[(((q - 1) * BT + bt) * 4 + r) * 64 + lane];
-      }
+      for (int u = 0; u < U; ++u)
+        if (s0 + u * KS < nsteps) acc = M::mma(af[u], bf[u], acc);
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
+    __syncthreads();
   }
-  if (ks != 0) return;
+  if (wave >= 4) return;
+  const int r = wave;
+  float dh = 0.0f;
+  if (p.dG_next)
+    for (int q = 0; q < KS; ++q) dh += red[(q * 4 + r) * 64 + lane];   // fixed order
   const int b = b0 + lrow;
-  if (b >= p.B) return;
-  T* dG_row = reinterpret_cast<T*>(p.dG_cur) + (size_t)b * p.G4;
+  const int n = n0 + 4 * lq + r;
+  if (b >= p.B || n >= p.H) return;
+  const size_t e = (size_t)b * p.H + n;
+  const float h = (p.dy_is_h || p.y_out_s) ? p.h[e] : 0.0f;
+  if (p.dy_is_h)
+    dh += h;
+  else if (p.dy_s)
+    dh += p.dy_s[e];
+  if (p.y_out_s) p.y_out_s[e] = h;
+  const float gi = p.g_i[e], gf = p.g_f[e], gg = p.g_g[e], go = p.g_o[e];
+  const float tc = tanhf(p.c[e]);
+  const float c_prev = p.c_prev[e];
+  const float d_o = dh * tc;
+  const float dct = p.dc[e] + dh * go * (1.0f - tc * tc);
+  const float dGi = dct * gg * gi * (1.0f - gi);
+  const float dGf = dct * c_prev * gf * (1.0f - gf);
+  const float dGg = dct * gi * (1.0f - gg * gg);
+  const float dGo = d_o * go * (1.0f - go);
+  p.dc[e] = dct * gf;
+  const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
+  // dG of this step, fragment-tiled [b][4n + gate]: the four gates are consecutive in one lane slot
+  T* dG4 = reinterpret_cast<T*>(p.dG_cur) + ft_offset<T>(b, 4 * n, p.G4 / KSTEP);
+  dG4[0] = q0;
+  dG4[1] = q1;
+  dG4[2] = q2;
+  dG4[3] = q3;
+  // transposed copies for the weight gradient, fragment-tiled [4n + gate][col] and [NX + n][col]
+  const int col = p.col0 + b, ncs = p.KC / KSTEP;
   T* dGT = reinterpret_cast<T*>(p.dGT);
-  T* aT = reinterpret_cast<T*>(p.aT);
-  const int col = p.col0 + b;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int n = n0 + 4 * lq + r;
-    if (n >= p.H) continue;
-    const size_t e = (size_t)b * p.H + n;
-    const float h = (p.dy_is_h || p.y_out_s) ? p.h[e] : 0.0f;
-    float dh = acc[r];
-    if (p.dy_is_h)
-      dh += h;
-    else if (p.dy_s)
-      dh += p.dy_s[e];
-    if (p.y_out_s) p.y_out_s[e] = h;
-    const float gi = p.g_i[e], gf = p.g_f[e], gg = p.g_g[e], go = p.g_o[e];
-    const float tc = tanhf(p.c[e]);
-    const float c_prev = p.c_prev[e];
-    const float d_o = dh * tc;
-    const float dct = p.dc[e] + dh * go * (1.0f - tc * tc);
-    const float dGi = dct * gg * gi * (1.0f - gi);
-    const float dGf = dct * c_prev * gf * (1.0f - gf);
-    const float dGg = dct * gi * (1.0f - gg * gg);
-    const float dGo = d_o * go * (1.0f - go);
-    p.dc[e] = dct * gf;
-    const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
-    dG_row[4 * n + 0] = q0;
-    dG_row[4 * n + 1] = q1;
-    dG_row[4 * n + 2] = q2;
-    dG_row[4 * n + 3] = q3;
-    dGT[(size_t)(4 * n + 0) * p.KC + col] = q0;
-    dGT[(size_t)(4 * n + 1) * p.KC + col] = q1;
-    dGT[(size_t)(4 * n + 2) * p.KC + col] = q2;
-    dGT[(size_t)(4 * n + 3) * p.KC + col] = q3;
-    aT[(size_t)(p.NX + n) * p.KC + col] = (T)p.h_prev[e];
-  }
+  dGT[ft_offset<T>(4 * n + 0, col, ncs)] = q0;
+  dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
+  dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
+  dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
+  reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)p.h_prev[e];
 }
 
 template <class T>
 static hipError_t launch_backward_t(const Dims& d, const BwdParams& p, hipStream_t st) {
-  const int btiles = d.BP / 16;
-  if (btiles >= 4) {
-    dim3 grid(d.HP / 16, (btiles + 3) / 4);
-    backward_kernel<T, 4, 4><<<grid, dim3(1024), 0, st>>>(p);
-  } else if (btiles >= 2) {
-    dim3 grid(d.HP / 16, (btiles + 1) / 2);
-    backward_kernel<T, 2, 8><<<grid, dim3(1024), 0, st>>>(p);
-  } else {
-    dim3 grid(d.HP / 16, btiles);
-    backward_kernel<T, 1, 8><<<grid, dim3(512), 0, st>>>(p);
-  }
+  dim3 grid(d.HP / 16, d.BP / 16);
+  if (d.G4 / (4 * Mma<T>::VEC) <= 16)
+    backward_kernel<T, 4, 4><<<grid, dim3(256), 0, st>>>(p);
+  else
+    backward_kernel<T, 16, 4><<<grid, dim3(1024), 0, st>>>(p);
   return hipGetLastError();
 }
 
@@ -485,64 +507,55 @@ hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st)
 
 // ---- data-gradient GEMM: out[row][n] = sum_k dG[row][k] * WT[n][k] ---------------------------
 
-template <class T, int BT, int KS>
-__global__ __launch_bounds__(64 * BT * KS) void dgrad_kernel(const T* __restrict__ WT, int N, const T* __restrict__ dG,
-                                                             int nrows_padded, int B, int BP, int G4,
-                                                             float* __restrict__ out, int ld_out) {
+template <class T, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT, int N, const T* __restrict__ dG,
+                                                        int B, int BP, int G4, float* __restrict__ out, int ld_out) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int bt = wave % BT, ks = wave / BT;
   const int lrow = lane & 15, lq = lane >> 4;
   const int n0 = blockIdx.x * 16;
-  const int r0 = (blockIdx.y * BT + bt) * 16;
-  const int row_ld = min(r0 + lrow, nrows_padded - 1);
-  const T* arow = WT + (size_t)(n0 + lrow) * G4 + VEC * lq;
-  const T* brow = dG + (size_t)row_ld * G4 + VEC * lq;
-  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int r0 = blockIdx.y * 16;   // padded row (slot*BP + b); grid.y covers exactly nslots*BP/16 tiles
   const int nsteps = G4 / KSTEP;
-  for (int s = ks; s < nsteps; s += KS) {
-    typename M::Frag af = M::load(arow + (size_t)s * KSTEP);
-    typename M::Frag bf = M::load(brow + (size_t)s * KSTEP);
-    acc = M::mma(af, bf, acc);
-  }
-  if (KS > 1) {
-    __shared__ float red[(KS > 1 ? KS - 1 : 1) * BT * 4 * 64];
-    if (ks > 0) {
+  const T* abase = WT + ((size_t)blockIdx.x * nsteps * 64 + lane) * VEC;
+  const T* bbase = dG + ((size_t)blockIdx.y * nsteps * 64 + lane) * VEC;
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
+    typename M::Frag af[U], bf[U];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[(((ks - 1) * BT + bt) * 4 + r) * 64 + lane] = acc[r];
+    for (int u = 0; u < U; ++u) {
+      const int s = min(s0 + u * KS, nsteps - 1);
+      af[u] = M::load(abase + (size_t)s * 64 * VEC);
+      bf[u] = M::load(bbase + (size_t)s * 64 * VEC);
     }
-    __syncthreads();
-    if (ks == 0) {
-      for (int q = 1; q < KS; ++q)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[r] += red[(((q - 1) * BT + bt) * 4 + r) * 64 + lane];
-    }
+    for (int u = 0; u < U; ++u)
+      if (s0 + u * KS < nsteps) acc = M::mma(af[u], bf[u], acc);
   }
-  if (ks != 0) return;
+  __shared__ float red[KS * 4 * 64];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  if (wave >= 4) return;
+  const int r = wave;
+  float v = 0.0f;
+  for (int q = 0; q < KS; ++q) v += red[(q * 4 + r) * 64 + lane];
   const int row = r0 + lrow;
-  if (row >= nrows_padded) return;
   const int slot = row / BP, b = row % BP;
-  if (b >= B) return;
-  float* orow = out + ((size_t)slot * B + b) * ld_out;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int n = n0 + 4 * lq + r;
-    if (n < N) orow[n] = acc[r];
-  }
+  const int n = n0 + 4 * lq + r;
+  if (b >= B || n >= N) return;
+  out[((size_t)slot * B + b) * ld_out + n] = v;
 }
 
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
                              hipStream_t st) {
-  const int nrows = nslots * d.BP;
-  const int ntiles = round_up(N, 16) / 16, rtiles = nrows / 16;
-  dim3 grid(ntiles, (rtiles + 3) / 4);
+  dim3 grid(round_up(N, 16) / 16, nslots * d.BP / 16);
   if (d.dtype)
-    dgrad_kernel<__bf16, 4, 4><<<grid, dim3(1024), 0, st>>>((const __bf16*)WT, N, (const __bf16*)dG, nrows, d.B, d.BP,
-                                                            d.G4, out, ld_out);
+    dgrad_kernel<__bf16, 8, 4><<<grid, dim3(512), 0, st>>>((const __bf16*)WT, N, (const __bf16*)dG, d.B, d.BP, d.G4, out,
+                                                           ld_out);
   else
-    dgrad_kernel<float, 4, 4><<<grid, dim3(1024), 0, st>>>((const float*)WT, N, (const float*)dG, nrows, d.B, d.BP, d.G4,
-                                                           out, ld_out);
+    dgrad_kernel<float, 8, 4><<<grid, dim3(512), 0, st>>>((const float*)WT, N, (const float*)dG, d.B, d.BP, d.G4, out,
+                                                          ld_out);
   return hipGetLastError();
 }
 
@@ -561,7 +574,7 @@ __global__ void transpose_x_kernel(const float* __restrict__ x, int rows, int I,
   __syncthreads();
   for (int ii = ty; ii < 32; ii += 8) {
     int i = i0 + ii, r = r0 + tx;
-    if (i < I && r < rows) aT[(size_t)i * KC + r] = (T)tile[tx][ii];
+    if (i < I && r < rows) aT[ft_offset<T>(i, r, KC / (4 * Mma<T>::VEC))] = (T)tile[tx][ii];
   }
 }
 
@@ -577,43 +590,58 @@ hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, v
 
 // ---- weight-gradient GEMM: dW[row(m)][n] (+)= sum_k dGT[m][k] * aT[n][k] ------------------------
 
-// Each wave owns a 64 x 64 block (4 x 4 MFMA tiles); a workgroup is 2 x 2 waves.
+// Each wave owns a 64 x 64 block (4 x 4 MFMA tiles); a workgroup is 2 x 2 waves.  Operand
+// fragments are fetched PD-1 macro steps ahead through a ring of register buffers, so several KiB
+// per wave are in flight while the MFMAs of the current step issue.
 template <class T>
 __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, const T* __restrict__ aT, int K, int KC,
                                                     int G4, int NTOT, int NX, int I, int H, int accumulate,
                                                     float* __restrict__ dW_ih, float* __restrict__ dW_hh) {
   using M = Mma<T>;
-  constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
+  constexpr int VEC = M::VEC, KSTEP = 4 * VEC, PD = 4;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
   const int mt0 = (blockIdx.x * 2 + (wave & 1)) * 4;    // first 16-row tile of this wave
   const int nt0 = (blockIdx.y * 2 + (wave >> 1)) * 4;
   const int MT = G4 / 16, NT = NTOT / 16;
   if (mt0 >= MT || nt0 >= NT) return;
+  const int ncs = KC / KSTEP;    // macro steps per row tile in the fragment-tiled operands
+  const int nk = K / KSTEP;      // macro steps that hold data
   const T* ap[4];
   const T* bp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int mt = min(mt0 + i, MT - 1), nt = min(nt0 + i, NT - 1);
-    ap[i] = dGT + (size_t)(mt * 16 + lrow) * KC + VEC * lq;
-    bp[i] = aT + (size_t)(nt * 16 + lrow) * KC + VEC * lq;
+    ap[i] = dGT + ((size_t)mt * ncs * 64 + lane) * VEC;
+    bp[i] = aT + ((size_t)nt * ncs * 64 + lane) * VEC;
   }
   f32x4 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < K; k += KSTEP) {
-    typename M::Frag af[4], bf[4];
+  typename M::Frag af[PD][4], bf[PD][4];
+  auto fetch = [&](int stage, int ks) {
+    const size_t off = (size_t)min(ks, nk - 1) * 64 * VEC;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      af[i] = M::load(ap[i] + k);
-      bf[i] = M::load(bp[i] + k);
+      af[stage][i] = M::load(ap[i] + off);
+      bf[stage][i] = M::load(bp[i] + off);
     }
+  };
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+  for (int st = 0; st < PD - 1; ++st) fetch(st, st);
+  for (int k0 = 0; k0 < nk; k0 += PD) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = M::mma(af[i], bf[j], acc[i][j]);
+    for (int j = 0; j < PD; ++j) {
+      fetch((j + PD - 1) % PD, k0 + j + PD - 1);
+      if (k0 + j < nk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) acc[i][jj] = M::mma(af[j][i], bf[j][jj], acc[i][jj]);
+      }
+    }
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -650,7 +678,7 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dG
   const int u = m >> 2, gate = m & 3;
   if (u >= H) return;
   float s = 0.0f;
-  for (int k = lane; k < K; k += 64) s += (float)dGT[(size_t)m * KC + k];
+  for (int k = lane; k < K; k += 64) s += (float)dGT[ft_offset<T>(m, k, KC / (4 * Mma<T>::VEC))];
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
   if (lane == 0) {
