@@ -139,3 +139,88 @@ def test_config2_full_size():
     m = 50) in the launch configuration the benchmark times, against the full float64 oracle."""
     out, ref, inp, errs = run_case(wl.CONFIGS["cfg2"])
     print("cfg2 relative errors:", errs)
+
+
+def test_config3_full_size():
+    """Configuration 3 at full size (H = 2048, B = 128, t = 1000, ISM with m = 100 internal-state
+    slots) against the full float64 oracle."""
+    out, ref, inp, errs = run_case(wl.CONFIGS["cfg3"])
+    print("cfg3 relative errors:", errs)
+
+
+def test_config5_full_size_budget_sweep():
+    """Configuration 5 (H = 4096, B = 32, t = 1000, mixed policy): every budget of the sweep
+    m in {t, t/4, t/20, floor(sqrt t), 2} units against one float64 oracle run; all budgets must
+    also agree with each other bit for bit, and the byte cap must not bind."""
+    w = wl.CONFIGS["cfg5"]
+    inp = wl.make_inputs(w)
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, 1)
+    desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype, w.loss, 1)
+    cap_units = mb.mebptt_units_for_bytes(desc, mb.MSM, wl.CFG5_BYTE_CAP)
+    assert cap_units == wl.CFG5_BYTE_CAP // (2 * w.B * w.H * 4)
+    tabs = dp.msm_tables(w.t, max(wl.CFG5_BUDGET_SWEEP), w.alpha, w.beta)
+    first = None
+    for m in wl.CFG5_BUDGET_SWEEP:
+        assert m <= cap_units
+        from paper_1606_03401_amd.session import Session
+        s = Session(w, inp, kind=wl.KIND_MSM, m=m)
+        out = s.run_and_fetch()
+        assert out.stats.forward_ops == int(tabs[0][w.t, m])
+        assert out.stats.peak <= m and out.stats.peak_slot_bytes <= wl.CFG5_BYTE_CAP
+        errs = check_against_oracle(w, inp, out, ref, TOL[w.gemm_dtype], label=f"cfg5 m={m}: ")
+        print(f"cfg5 m={m}: forward ops {out.stats.forward_ops}, errors {errs}")
+        if first is None:
+            first = out
+        else:
+            for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+                assert np.array_equal(getattr(out, name), getattr(first, name)), (m, name)
+        del s
+
+
+def _oracle_forward_chunked(inp, t, chunk=500):
+    """Outputs h_1..h_t and the final (h, c) from the oracle's forward pass, in chunks."""
+    h, c = inp.h0.astype(np.float64), inp.c0.astype(np.float64)
+    ys, marks = [], {}
+    for s0 in range(0, t, chunk):
+        st = ob.lstm_forward_all(inp.W_ih, inp.W_hh, inp.b, inp.x[s0:s0 + chunk], h, c)
+        ys.append(st["h"].astype(np.float32))
+        h, c = st["h"][-1], st["c"][-1]
+        marks[s0 + st["h"].shape[0]] = (h.copy(), c.copy())
+    return np.concatenate(ys), marks
+
+
+def test_config4_reduced_length():
+    """Configuration 4's shape and loss placement (last 100 steps only) at t = 2000, where the
+    full float64 oracle is affordable."""
+    w = wl.CONFIGS["cfg4"].scaled(t=2000, dy_first_step=1901)
+    run_case(w)
+
+
+def test_config4_full_size():
+    """Configuration 4 at full size (t = 10000, m = 100 = 1 % of t).  The float64 oracle checks
+    (a) every output h_s (forward only, chunked);
+    (b) the gradients, by store-everything BPTT over the last 2000 steps started from the
+        oracle's own state at step 8000.  The loss sits on the last 100 steps, and the oracle's
+        gradient w.r.t. that start state is asserted to have vanished (below 1e-12 of its peak),
+        so the steps before the window contribute nothing at the tolerance.
+    (c) forward-operation count and peak occupancy as for every other case."""
+    w = wl.CONFIGS["cfg4"]
+    inp = wl.make_inputs(w)
+    from paper_1606_03401_amd.session import Session
+    s = Session(w, inp)
+    out = s.run_and_fetch()
+    assert out.stats.forward_ops == oracle_cost(w.kind, w.t, w.m) and out.stats.backward_ops == w.t
+    assert out.stats.peak <= w.m
+    y_ref, marks = _oracle_forward_chunked(inp, w.t)
+    assert rel_err(out.y, y_ref) <= TOL[w.gemm_dtype]
+    t0 = 8000
+    h8, c8 = marks[t0]
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[t0:], h8, c8, inp.dy, w.dy_first_step - t0)
+    peak = max(np.abs(ref.dx).max(), 1e-300)
+    assert np.abs(ref.dh0).max() <= 1e-12 * peak and np.abs(ref.dc0).max() <= 1e-12 * peak
+    for name in ("dW_ih", "dW_hh", "db"):
+        e = rel_err(getattr(out, name), getattr(ref, name))
+        assert e <= TOL[w.gemm_dtype], (name, e)
+    assert rel_err(out.dx[t0:], ref.dx) <= TOL[w.gemm_dtype]
+    assert np.abs(out.dx[:t0]).max() <= 1e-6 * np.abs(out.dx).max()
+    assert np.abs(out.dh0).max() <= 1e-6 and np.abs(out.dc0).max() <= 1e-6
