@@ -38,9 +38,13 @@ def time_runs(sess, steps, warmup):
         sess.run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    enq = 0.0
     for _ in range(steps):
+        e0 = time.perf_counter()
         sess.run()
+        enq += time.perf_counter() - e0
     torch.cuda.synchronize()
+    time_runs.last_enqueue_ms = enq / steps * 1e3      # host time spent inside mebptt_run (enqueue only)
     return (time.perf_counter() - t0) / steps
 
 
@@ -118,11 +122,20 @@ def main() -> int:
         return 1
     w = wl.CONFIGS[args.workload]
     log(f"[bench] {mb.mebptt_version()} workload {w}")
+    # A plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick
+    # that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters into bytes (see profiles/).
+    cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     inp = wl.make_inputs(w)
     sess = Session(w, inp, want_dx=True, want_y=False)
     ms = time_runs(sess, args.steps, args.warmup) * 1e3
     C = sess.plan.forward_ops
-    log(f"[bench] {KIND_NAMES[sess.kind]} m={sess.m}: {ms:.3f} ms/step, forward ops {C}, peak {sess.plan.peak}")
+    enqueue_ms = time_runs.last_enqueue_ms
+    log(f"[bench] {KIND_NAMES[sess.kind]} m={sess.m}: {ms:.3f} ms/step (host enqueue {enqueue_ms:.3f} ms), "
+        f"forward ops {C}, peak {sess.plan.peak}")
 
     # dominant kernel: event-bracketed samples on the run's stream, in extra profiled steps
     mb.mebptt_profile_enable(8)
@@ -172,7 +185,7 @@ def main() -> int:
     flops_useful = 3 * w.t * forward_flops(w)
     result = {
         "metric": METRIC, "value": w.t / (ms * 1e-3), "unit": "time-steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "host_enqueue_ms": enqueue_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_dtype else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: single-layer LSTM I={w.I} H={w.H} B={w.B} t={w.t}, "
                                f"BPTT-{KIND_NAMES[sess.kind]} budget m={sess.m}, seed {w.seed}",

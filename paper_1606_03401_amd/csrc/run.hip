@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -105,6 +106,38 @@ hipError_t timed(int cls, hipStream_t st, F&& launch) {
   e = hipEventRecord(s.stop, st);
   p.pending.push_back(s);
   return e;
+}
+
+// ---- side stream for the time-batched GEMMs ------------------------------------------------------
+// The weight-gradient and dx GEMMs of a finished chunk do not feed the sequential chain, so they
+// run on a second stream (default priority) while the main stream carries on with the next
+// steps.  Fork/join is by events only, so a caller may capture the whole run in a HIP graph.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t full[2] = {nullptr, nullptr};   // main -> side: chunk buffer is complete
+  hipEvent_t done[2] = {nullptr, nullptr};   // side -> main: chunk buffer may be overwritten
+};
+SideStream g_side[16];
+std::mutex g_run_mutex;
+
+hipError_t get_side_stream(SideStream** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  SideStream& s = g_side[dev];
+  if (!s.stream) {
+    e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+    for (int i = 0; i < 2; ++i) {
+      e = hipEventCreateWithFlags(&s.full[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+      e = hipEventCreateWithFlags(&s.done[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+  }
+  *out = &s;
+  return hipSuccess;
 }
 
 #define HIP_TRY(expr)                                                                                 \
@@ -243,6 +276,13 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     return launch_init_state(d, h0, c0, plan->kind == MEBPTT_ISM ? loc(MEBPTT_LOC_INIT) : loc(0), st);
   }));
 
+  std::lock_guard<std::mutex> lock(g_run_mutex);   // the side stream and its events are shared
+  SideStream* side = nullptr;
+  HIP_TRY(get_side_stream(&side));
+  hipStream_t st2 = side->stream;
+  bool pending[2] = {false, false};   // side-stream work on chunk buffer i not yet joined
+  int cur_chunk = -1;
+
   int64_t fwd = 0, bwd = 0;
   bool first_chunk = true;
   const int t = desc->t, CH = d.CH;
@@ -264,6 +304,13 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     } else if (op.op == MEBPTT_OP_BWD) {
       const int s = op.step;
       const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
+      if (chunk != cur_chunk) {   // first write into this chunk buffer: its previous user must be done
+        if (pending[buf]) {
+          HIP_TRY(hipStreamWaitEvent(st, side->done[buf], 0));
+          pending[buf] = false;
+        }
+        cur_chunk = chunk;
+      }
       BackwardArgs a{};
       a.WTh = WTh;
       a.dG_next = (s == t) ? nullptr : ws + w.dG[(s / CH) & 1] + (size_t)(s % CH) * dG_step;
@@ -282,15 +329,19 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
       if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
         const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
         const size_t x_off = (size_t)chunk * CH * d.B * d.I;
-        HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {
-          hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st);
+        HIP_TRY(hipEventRecord(side->full[buf], st));
+        HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
+        HIP_TRY(timed(MEBPTT_K_WGRAD, st2, [&] {
+          hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
           if (e != hipSuccess) return e;
-          return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st);
+          return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st2);
         }));
         if (dx)
-          HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] {
-            return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st);
+          HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
+            return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
           }));
+        HIP_TRY(hipEventRecord(side->done[buf], st2));
+        pending[buf] = true;
         first_chunk = false;
       }
     } else {
@@ -300,6 +351,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   // dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
   HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));
   HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, st); }));
+  for (int i = 0; i < 2; ++i)   // join: everything is ordered before whatever follows on `st`
+    if (pending[i]) HIP_TRY(hipStreamWaitEvent(st, side->done[i], 0));
 
   if (stats) {
     stats->forward_ops = fwd;
