@@ -182,7 +182,8 @@ enum {
   MEBPTT_K_WGRAD = 2,    /* time-batched dW/db accumulation (with the x transpose feeding it) */
   MEBPTT_K_DGRAD = 3,    /* time-batched dx GEMM and the final dh0 GEMM                       */
   MEBPTT_K_SETUP = 4,    /* operand copies of the weights, zero fills, start-state copy       */
-  MEBPTT_K_CLASSES = 5
+  MEBPTT_K_PAIR = 5,     /* one launch carrying a backward step and an independent forward op */
+  MEBPTT_K_CLASSES = 6
 };
 typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */

@@ -42,8 +42,8 @@ class mebptt_stats(C.Structure):
                 ("reserved", C.c_int32), ("peak_slot_bytes", C.c_size_t)]
 
 
-K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_CLASSES = 0, 1, 2, 3, 4, 5
-K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup")
+K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_PAIR, K_CLASSES = 0, 1, 2, 3, 4, 5, 6
+K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward")
 
 
 class mebptt_profile(C.Structure):

@@ -71,6 +71,15 @@ struct BackwardArgs {
 // LSTM backward producing dG_s and dc_{s-1}.
 hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st);
 
+// True when the shape runs the large-K kernel configurations, for which a backward step and an
+// independent forward step can share one launch.
+bool can_fuse_pair(const Dims& d);
+// One launch carrying the backward step `a` and one forward operation (arguments as
+// launch_forward).  The caller guarantees the forward step writes nothing the backward step reads.
+hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, const void* Wp, const float* bp,
+                                        const float* x_s, const float* src_unit, float* dst_unit, float* gates_units,
+                                        hipStream_t st);
+
 // out[b][n] = sum_k dG[b][k] * WT[n][k] for b < rows(valid), n < N; ld_out = row stride of out.
 // `rows_per_step`/`BP` describe the padded row layout of dG: logical row r = step_slot*B + b
 // lives at dG row step_slot*BP + b.

@@ -246,20 +246,22 @@ __device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int
   return r;
 }
 
-// Workgroup = one batch tile (16 sequences) x NG unit groups (4 hidden units = 16 gate rows
-// each); its KS waves split the K axis, every wave issuing all loads of U macro steps before
-// the first MFMA so that several KiB per wave are in flight.  Partial sums meet in LDS and are
-// added in a fixed order; wave g then runs the LSTM pointwise step of unit group g.
+// One workgroup of 64*KS threads = one batch tile (16 sequences) x NG unit groups (4 hidden units =
+// 16 gate rows each); its KS waves split the K axis, every wave issuing all loads of U macro steps
+// before the first MFMA so that several KiB per wave are in flight.  Partial sums meet in LDS
+// (`red`, KS*NG*256 floats) and are added in a fixed order; wave g then runs the LSTM pointwise
+// step of unit group g.  (bx, by) = (unit-group tile, batch tile).
 template <class T, int NG, int KS, int U>
-__global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
+__device__ inline void forward_body(const FwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
   static_assert(NG <= KS, "one epilogue wave per unit group");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
-  const int group0 = blockIdx.x * NG;
+  const int group0 = bx * NG;
   const int ngroups = p.HP >> 2;
-  const int b0 = blockIdx.y * 16;
+  const int b0 = by * 16;
   const int b_ld = min(b0 + lrow, p.B - 1);
   const float* xrow = p.x_s + (size_t)b_ld * p.I;
   const float* hrow = p.src_h + (size_t)b_ld * p.H;
@@ -275,28 +277,40 @@ __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
 #pragma unroll
   for (int g = 0; g < NG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // The epilogue waves fetch their pointwise operands now, so that their latency hides behind
+  // the K loop instead of following it.
+  const int b = b0 + lrow;
+  const int u = (group0 + wave) * 4 + lq;
+  const bool epi = wave < NG && b < p.B && u < p.H;
+  const size_t e = (size_t)b * p.H + u;
+  float4 bias = float4{0.f, 0.f, 0.f, 0.f};
+  float c_prev = 0.0f;
+  if (epi) {
+    bias = *reinterpret_cast<const float4*>(p.bp + 4 * u);
+    c_prev = p.src_c[e];
+  }
+
   for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
     RawAct<VEC> rb[U];
     typename M::Frag af[U][NG];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int s = min(s0 + u * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
+    for (int uu = 0; uu < U; ++uu) {
+      const int s = min(s0 + uu * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
       const int k = s * KSTEP + VEC * lq;
-      rb[u] = (k < p.KX) ? load_raw<VEC>(xrow, k, p.I, x_vec) : load_raw<VEC>(hrow, k - p.KX, p.H, h_vec);
+      rb[uu] = (k < p.KX) ? load_raw<VEC>(xrow, k, p.I, x_vec) : load_raw<VEC>(hrow, k - p.KX, p.H, h_vec);
 #pragma unroll
-      for (int g = 0; g < NG; ++g) af[u][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
+      for (int g = 0; g < NG; ++g) af[uu][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (s0 + u * KS < nsteps) {
-        typename M::Frag bf = M::from_f32(rb[u].v);
+    for (int uu = 0; uu < U; ++uu) {
+      if (s0 + uu * KS < nsteps) {
+        typename M::Frag bf = M::from_f32(rb[uu].v);
 #pragma unroll
-        for (int g = 0; g < NG; ++g) acc[g] = M::mma(af[u][g], bf, acc[g]);
+        for (int g = 0; g < NG; ++g) acc[g] = M::mma(af[uu][g], bf, acc[g]);
       }
     }
   }
 
-  __shared__ float red[KS * NG * 4 * 64];
 #pragma unroll
   for (int g = 0; g < NG; ++g)
 #pragma unroll
@@ -308,17 +322,12 @@ __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
   for (int q = 0; q < KS; ++q)   // fixed order: results do not depend on scheduling
 #pragma unroll
     for (int r = 0; r < 4; ++r) G[r] += red[((q * NG + g) * 4 + r) * 64 + lane];
-
-  const int b = b0 + lrow;
-  const int u = (group0 + g) * 4 + lq;
-  if (b >= p.B || u >= p.H) return;
-  const float4 bias = *reinterpret_cast<const float4*>(p.bp + 4 * u);
-  const size_t e = (size_t)b * p.H + u;
+  if (!epi) return;
   const float gi = sigmoidf_(G[0] + bias.x);
   const float gf = sigmoidf_(G[1] + bias.y);
   const float gg = tanhf(G[2] + bias.z);
   const float go = sigmoidf_(G[3] + bias.w);
-  const float c = gf * p.src_c[e] + gi * gg;
+  const float c = gf * c_prev + gi * gg;
   const float h = go * tanhf(c);
   p.dst_h[e] = h;
   p.dst_c[e] = c;
@@ -331,45 +340,9 @@ __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
 }
 
 template <class T, int NG, int KS, int U>
-static hipError_t launch_forward_cfg(const Dims& d, const FwdParams& p, hipStream_t st) {
-  dim3 grid((d.HP / 4 + NG - 1) / NG, d.BP / 16), block(64 * KS);
-  forward_kernel<T, NG, KS, U><<<grid, block, 0, st>>>(p);
-  return hipGetLastError();
-}
-
-template <class T>
-static hipError_t launch_forward_t(const Dims& d, const FwdParams& p, hipStream_t st) {
-  constexpr int KSTEP = 4 * Mma<T>::VEC;
-  const int nsteps = d.KP / KSTEP;
-  if (nsteps <= 8) return launch_forward_cfg<T, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
-  if (nsteps <= 20) return launch_forward_cfg<T, 4, 4, 5>(d, p, st);
-  return launch_forward_cfg<T, 4, 8, 5>(d, p, st);
-}
-
-hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const float* x_s, const float* src_unit,
-                          float* dst_unit, float* gates_units, hipStream_t st) {
-  const size_t plane = (size_t)d.B * d.H;
-  FwdParams p{};
-  p.Wp = Wp;
-  p.bp = bp;
-  p.x_s = x_s;
-  p.src_h = src_unit;
-  p.src_c = src_unit + plane;
-  p.dst_h = dst_unit;
-  p.dst_c = dst_unit + plane;
-  if (gates_units) {
-    p.g_i = gates_units;
-    p.g_f = gates_units + plane;
-    p.g_g = gates_units + 2 * plane;
-    p.g_o = gates_units + 3 * plane;
-  }
-  p.B = d.B;
-  p.I = d.I;
-  p.H = d.H;
-  p.HP = d.HP;
-  p.KX = d.KX;
-  p.KP = d.KP;
-  return d.dtype ? launch_forward_t<__bf16>(d, p, st) : launch_forward_t<float>(d, p, st);
+__global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
+  __shared__ float red[KS * NG * 4 * 64];
+  forward_body<T, NG, KS, U>(p, blockIdx.x, blockIdx.y, red);
 }
 
 // ---- backward step: dh GEMM + loss-gradient injection + LSTM pointwise backward --------------
@@ -388,24 +361,43 @@ struct BwdParams {
   int B, H, HP, G4, NX, KC, BP;
 };
 
-// Workgroup = one output tile (16 hidden units x 16 sequences); its KS waves split K = 4*HP,
-// each issuing the loads of U macro steps before the first MFMA.  Partial sums meet in LDS; waves
-// 0..3 then each take one of the four hidden units a lane owns and run the pointwise backward.
+// One workgroup of 64*KS threads = one output tile (16 hidden units x 16 sequences); its KS waves
+// split K = 4*HP, each issuing the loads of U macro steps before the first MFMA.  Partial sums meet
+// in LDS (`red`, KS*256 floats); waves 0..3 then each take one of the four hidden units a lane owns
+// and run the pointwise backward.  (bx, by) = (hidden-unit tile, batch tile).
 template <class T, int KS, int U>
-__global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
+__device__ inline void backward_body(const BwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
   static_assert(KS >= 4, "four epilogue waves");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
-  const int n0 = blockIdx.x * 16;
-  const int b0 = blockIdx.y * 16;
-  __shared__ float red[KS * 4 * 64];
+  const int n0 = bx * 16;
+  const int b0 = by * 16;
+  // Epilogue waves (0..3, one hidden unit of the lane's four each) fetch their pointwise operands
+  // before the K loop so that the latency overlaps with it.
+  const int b = b0 + lrow;
+  const int n = n0 + 4 * lq + wave;
+  const bool epi = wave < 4 && b < p.B && n < p.H;
+  const size_t e = (size_t)b * p.H + n;
+  float h = 0.f, dy = 0.f, gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, c_s = 0.f, c_prev = 0.f, dc_in = 0.f, h_prev = 0.f;
+  if (epi) {
+    if (p.dy_is_h || p.y_out_s) h = p.h[e];
+    if (!p.dy_is_h && p.dy_s) dy = p.dy_s[e];
+    gi = p.g_i[e];
+    gf = p.g_f[e];
+    gg = p.g_g[e];
+    go = p.g_o[e];
+    c_s = p.c[e];
+    c_prev = p.c_prev[e];
+    dc_in = p.dc[e];
+    h_prev = p.h_prev[e];
+  }
   if (p.dG_next) {
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     const int nsteps = p.G4 / KSTEP;
-    const T* abase = reinterpret_cast<const T*>(p.WTh) + ((size_t)blockIdx.x * nsteps * 64 + lane) * VEC;
-    const T* bbase = reinterpret_cast<const T*>(p.dG_next) + ((size_t)blockIdx.y * nsteps * 64 + lane) * VEC;
+    const T* abase = reinterpret_cast<const T*>(p.WTh) + ((size_t)bx * nsteps * 64 + lane) * VEC;
+    const T* bbase = reinterpret_cast<const T*>(p.dG_next) + ((size_t)by * nsteps * 64 + lane) * VEC;
     for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
       typename M::Frag af[U], bf[U];
 #pragma unroll
@@ -427,21 +419,12 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
   float dh = 0.0f;
   if (p.dG_next)
     for (int q = 0; q < KS; ++q) dh += red[(q * 4 + r) * 64 + lane];   // fixed order
-  const int b = b0 + lrow;
-  const int n = n0 + 4 * lq + r;
-  if (b >= p.B || n >= p.H) return;
-  const size_t e = (size_t)b * p.H + n;
-  const float h = (p.dy_is_h || p.y_out_s) ? p.h[e] : 0.0f;
-  if (p.dy_is_h)
-    dh += h;
-  else if (p.dy_s)
-    dh += p.dy_s[e];
+  if (!epi) return;
+  dh += p.dy_is_h ? h : dy;
   if (p.y_out_s) p.y_out_s[e] = h;
-  const float gi = p.g_i[e], gf = p.g_f[e], gg = p.g_g[e], go = p.g_o[e];
-  const float tc = tanhf(p.c[e]);
-  const float c_prev = p.c_prev[e];
+  const float tc = tanhf(c_s);
   const float d_o = dh * tc;
-  const float dct = p.dc[e] + dh * go * (1.0f - tc * tc);
+  const float dct = dc_in + dh * go * (1.0f - tc * tc);
   const float dGi = dct * gg * gi * (1.0f - gi);
   const float dGf = dct * c_prev * gf * (1.0f - gf);
   const float dGg = dct * gi * (1.0f - gg * gg);
@@ -461,20 +444,104 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
   dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
   dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
   dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
-  reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)p.h_prev[e];
+  reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)h_prev;
+}
+
+template <class T, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
+  __shared__ float red[KS * 4 * 64];
+  backward_body<T, KS, U>(p, blockIdx.x, blockIdx.y, red);
+}
+
+// ---- fused launch: a backward step and an independent forward step ---------------------------
+// The recomputation chain (forward operations) never depends on the backward chain, so the
+// forward operation that follows a backward step in the schedule can share its launch whenever
+// it does not overwrite a state that backward step still reads.  Workgroups [0, nf) play the
+// forward role, the rest the backward role; 512 threads and about 100 registers each, so one
+// workgroup of each role fits on a compute unit at the same time.  Each role splits K over the
+// same number of waves as its stand-alone kernel, so sums are formed in the same order and results
+// do not depend on whether a step was fused.
+constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 3, PAIR_BKS = 8, PAIR_BU = 8;
+
+template <class T>
+__global__ __launch_bounds__(64 * PAIR_BKS) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
+  __shared__ float red[PAIR_FKS * PAIR_NG * 4 * 64];
+  static_assert(PAIR_FKS * PAIR_NG >= PAIR_BKS && PAIR_FKS == PAIR_BKS, "shared buffer and block size cover both roles");
+  const int id = blockIdx.x;
+  if (id < nf)
+    forward_body<T, PAIR_NG, PAIR_FKS, PAIR_FU>(f, id % nfx, id / nfx, red);
+  else
+    backward_body<T, PAIR_BKS, PAIR_BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
+}
+
+template <class T>
+static bool uses_main_forward_config(const Dims& d) {
+  return d.KP / (4 * Mma<T>::VEC) > 20;
+}
+template <class T>
+static bool uses_main_backward_config(const Dims& d) {
+  return d.G4 / (4 * Mma<T>::VEC) > 16;
+}
+
+template <class T, int NG, int KS, int U>
+static hipError_t launch_forward_cfg(const Dims& d, const FwdParams& p, hipStream_t st) {
+  dim3 grid((d.HP / 4 + NG - 1) / NG, d.BP / 16), block(64 * KS);
+  forward_kernel<T, NG, KS, U><<<grid, block, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+template <class T>
+static hipError_t launch_forward_t(const Dims& d, const FwdParams& p, hipStream_t st) {
+  constexpr int KSTEP = 4 * Mma<T>::VEC;
+  const int nsteps = d.KP / KSTEP;
+  if (nsteps <= 8) return launch_forward_cfg<T, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
+  if (nsteps <= 20) return launch_forward_cfg<T, 4, 4, 5>(d, p, st);
+  return launch_forward_cfg<T, 4, 8, 5>(d, p, st);
+}
+
+static FwdParams make_fwd_params(const Dims& d, const void* Wp, const float* bp, const float* x_s,
+                                 const float* src_unit, float* dst_unit, float* gates_units) {
+  const size_t plane = (size_t)d.B * d.H;
+  FwdParams p{};
+  p.Wp = Wp;
+  p.bp = bp;
+  p.x_s = x_s;
+  p.src_h = src_unit;
+  p.src_c = src_unit + plane;
+  p.dst_h = dst_unit;
+  p.dst_c = dst_unit + plane;
+  if (gates_units) {
+    p.g_i = gates_units;
+    p.g_f = gates_units + plane;
+    p.g_g = gates_units + 2 * plane;
+    p.g_o = gates_units + 3 * plane;
+  }
+  p.B = d.B;
+  p.I = d.I;
+  p.H = d.H;
+  p.HP = d.HP;
+  p.KX = d.KX;
+  p.KP = d.KP;
+  return p;
+}
+
+hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const float* x_s, const float* src_unit,
+                          float* dst_unit, float* gates_units, hipStream_t st) {
+  FwdParams p = make_fwd_params(d, Wp, bp, x_s, src_unit, dst_unit, gates_units);
+  return d.dtype ? launch_forward_t<__bf16>(d, p, st) : launch_forward_t<float>(d, p, st);
 }
 
 template <class T>
 static hipError_t launch_backward_t(const Dims& d, const BwdParams& p, hipStream_t st) {
   dim3 grid(d.HP / 16, d.BP / 16);
-  if (d.G4 / (4 * Mma<T>::VEC) <= 16)
+  if (!uses_main_backward_config<T>(d))
     backward_kernel<T, 4, 4><<<grid, dim3(256), 0, st>>>(p);
   else
-    backward_kernel<T, 16, 4><<<grid, dim3(1024), 0, st>>>(p);
+    backward_kernel<T, PAIR_BKS, PAIR_BU><<<grid, dim3(64 * PAIR_BKS), 0, st>>>(p);
   return hipGetLastError();
 }
 
-hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st) {
+static BwdParams make_bwd_params(const Dims& d, const BackwardArgs& a) {
   const size_t plane = (size_t)d.B * d.H;
   BwdParams p{};
   p.WTh = a.WTh;
@@ -502,7 +569,32 @@ hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st)
   p.NX = d.NX;
   p.KC = d.KC;
   p.BP = d.BP;
+  return p;
+}
+
+hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st) {
+  BwdParams p = make_bwd_params(d, a);
   return d.dtype ? launch_backward_t<__bf16>(d, p, st) : launch_backward_t<float>(d, p, st);
+}
+
+bool can_fuse_pair(const Dims& d) {
+  return d.dtype ? (uses_main_forward_config<__bf16>(d) && uses_main_backward_config<__bf16>(d))
+                 : (uses_main_forward_config<float>(d) && uses_main_backward_config<float>(d));
+}
+
+hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, const void* Wp, const float* bp,
+                                        const float* x_s, const float* src_unit, float* dst_unit, float* gates_units,
+                                        hipStream_t st) {
+  BwdParams b = make_bwd_params(d, a);
+  FwdParams f = make_fwd_params(d, Wp, bp, x_s, src_unit, dst_unit, gates_units);
+  const int nfx = (d.HP / 4 + PAIR_NG - 1) / PAIR_NG, nfy = d.BP / 16;
+  const int nbx = d.HP / 16, nby = d.BP / 16;
+  dim3 grid(nfx * nfy + nbx * nby), block(64 * PAIR_BKS);
+  if (d.dtype)
+    pair_kernel<__bf16><<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+  else
+    pair_kernel<float><<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+  return hipGetLastError();
 }
 
 // ---- data-gradient GEMM: out[row][n] = sum_k dG[row][k] * WT[n][k] ---------------------------

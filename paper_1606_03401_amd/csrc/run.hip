@@ -3,8 +3,10 @@
 //
 // Memory outside the slot budget (the "single RNN core available for intermediate
 // calculations" of Section 3.1, plus bounded staging) lives in the caller's workspace:
-//   operand copies of the weights | transient states T0, T1 | working core (3 units) |
-//   copy of (h0, c0) | running dc | two chunk buffers each of dG, dG^T and [x ; h_prev]^T.
+//   operand copies of the weights | transient states T0, T1 | working core (3 units, held twice so
+//   that the forward step of the next backward operation can be computed while the previous one
+//   is still being back-propagated) | copy of (h0, c0) | running dc | two chunk buffers each of
+//   dG, dG^T and [x ; h_prev]^T.
 // The weight gradient is accumulated once per chunk of CH consecutive time steps.  Chunks are
 // aligned to absolute step numbers, so the summation order of dW depends only on t -- never on
 // the budget or the policy -- and gradients are bit-identical for every budget.
@@ -42,7 +44,7 @@ Workspace layout(const Dims& d) {
   w.bp = take((size_t)d.G4 * sizeof(float));
   w.WTh = take((size_t)d.HP * d.G4 * op);
   w.WTx = take((size_t)d.NX * d.G4 * op);
-  w.state = take(6 * unit);
+  w.state = take(9 * unit);   // T0 | T1 | core A (3 units) | copy of (h0,c0) | core B (3 units)
   w.dc = take(unit / 2);
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
@@ -238,12 +240,13 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   const size_t unit = 2 * plane;   // floats
   float* state = reinterpret_cast<float*>(ws + w.state);
   float* slot0 = reinterpret_cast<float*>(slots);
+  int core_flip = 0;   // which of the two working-core buffers MEBPTT_LOC_CORE currently names
   auto loc = [&](int32_t l) -> float* {
     if (l >= 0) return slot0 + (size_t)l * unit;
     switch (l) {
       case MEBPTT_LOC_T0: return state;
       case MEBPTT_LOC_T1: return state + unit;
-      case MEBPTT_LOC_CORE: return state + 2 * unit;
+      case MEBPTT_LOC_CORE: return state + (core_flip ? 6 : 2) * unit;
       case MEBPTT_LOC_INIT: return state + 5 * unit;
       default: return nullptr;
     }
@@ -287,21 +290,84 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   bool first_chunk = true;
   const int t = desc->t, CH = d.CH;
   const size_t dG_step = (size_t)d.BP * d.G4 * op_b;   // bytes of one step inside a dG chunk buffer
+  const bool fuse = can_fuse_pair(d);
+
+  // A backward step is held back until the next schedule entry is known: if that is a forward run
+  // whose first step overwrites nothing the backward step reads, both go out in one launch.
+  bool have_pending = false;
+  BackwardArgs pend{};
+  int pend_step = 0;
+
+  // Launches the held-back backward step, alone or fused with one forward operation, then the
+  // time-batched work of its chunk if the step completed one.
+  auto flush_backward = [&](const float* x_s, const float* f_src, float* f_dst, float* f_gates) -> int {
+    if (x_s) {
+      HIP_TRY(timed(MEBPTT_K_PAIR, st, [&] {
+        return launch_backward_forward_pair(d, pend, Wp, bp, x_s, f_src, f_dst, f_gates, st);
+      }));
+      ++fwd;
+    } else {
+      HIP_TRY(timed(MEBPTT_K_BACKWARD, st, [&] { return launch_backward(d, pend, st); }));
+    }
+    ++bwd;
+    have_pending = false;
+    const int s = pend_step;
+    const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
+    if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx on the side stream
+      const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
+      const size_t x_off = (size_t)chunk * CH * d.B * d.I;
+      HIP_TRY(hipEventRecord(side->full[buf], st));
+      HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
+      HIP_TRY(timed(MEBPTT_K_WGRAD, st2, [&] {
+        hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
+        if (e != hipSuccess) return e;
+        return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st2);
+      }));
+      if (dx)
+        HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
+          return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
+        }));
+      HIP_TRY(hipEventRecord(side->done[buf], st2));
+      pending[buf] = true;
+      first_chunk = false;
+    }
+    return MEBPTT_OK;
+  };
+
   for (const mebptt_op& op : plan->ops) {
     if (op.op == MEBPTT_OP_FWD_RUN) {
+      if (op.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
       const float* cur = loc(op.src);
       for (int j = 1; j <= op.count; ++j) {
         const int step = op.step + j - 1;
         float* dst = (j == op.count) ? loc(op.dst)
                                      : (j == op.count - 1 ? loc(op.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
         float* gates = (j == op.count && op.keep) ? dst + unit : nullptr;
-        HIP_TRY(timed(MEBPTT_K_FORWARD, st, [&] {
-          return launch_forward(d, Wp, bp, x + (size_t)(step - 1) * d.B * d.I, cur, dst, gates, st);
-        }));
+        const float* x_s = x + (size_t)(step - 1) * d.B * d.I;
+        if (have_pending) {
+          // units written by this forward step vs units read by the held-back backward step
+          const float* w_lo = dst;
+          const float* w_hi = dst + (gates ? 3 : 1) * unit;
+          const bool clash = (w_lo < pend.state + 3 * unit && pend.state < w_hi) ||
+                             (w_lo < pend.prev + unit && pend.prev < w_hi);
+          if (fuse && !clash) {
+            rc = flush_backward(x_s, cur, dst, gates);
+            if (rc) return rc;
+            cur = dst;
+            continue;
+          }
+          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+          if (rc) return rc;
+        }
+        HIP_TRY(timed(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_s, cur, dst, gates, st); }));
         cur = dst;
         ++fwd;
       }
     } else if (op.op == MEBPTT_OP_BWD) {
+      if (have_pending) {
+        rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+        if (rc) return rc;
+      }
       const int s = op.step;
       const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
       if (chunk != cur_chunk) {   // first write into this chunk buffer: its previous user must be done
@@ -311,42 +377,28 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
         }
         cur_chunk = chunk;
       }
-      BackwardArgs a{};
-      a.WTh = WTh;
-      a.dG_next = (s == t) ? nullptr : ws + w.dG[(s / CH) & 1] + (size_t)(s % CH) * dG_step;
-      a.state = loc(op.dst);
-      a.prev = loc(op.src);
-      a.dy_s = (desc->loss == 0 && s >= desc->dy_first_step) ? dy + (size_t)(s - desc->dy_first_step) * plane : nullptr;
-      a.dy_is_h = desc->loss == 1;
-      a.dc = dc;
-      a.dG_cur = ws + w.dG[buf] + (size_t)slot * dG_step;
-      a.dGT = ws + w.dGT[buf];
-      a.aT = ws + w.aT[buf];
-      a.col0 = slot * d.B;
-      a.y_out_s = y_out ? y_out + (size_t)(s - 1) * plane : nullptr;
-      HIP_TRY(timed(MEBPTT_K_BACKWARD, st, [&] { return launch_backward(d, a, st); }));
-      ++bwd;
-      if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
-        const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
-        const size_t x_off = (size_t)chunk * CH * d.B * d.I;
-        HIP_TRY(hipEventRecord(side->full[buf], st));
-        HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
-        HIP_TRY(timed(MEBPTT_K_WGRAD, st2, [&] {
-          hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
-          if (e != hipSuccess) return e;
-          return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st2);
-        }));
-        if (dx)
-          HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
-            return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
-          }));
-        HIP_TRY(hipEventRecord(side->done[buf], st2));
-        pending[buf] = true;
-        first_chunk = false;
-      }
+      pend = BackwardArgs{};
+      pend.WTh = WTh;
+      pend.dG_next = (s == t) ? nullptr : ws + w.dG[(s / CH) & 1] + (size_t)(s % CH) * dG_step;
+      pend.state = loc(op.dst);
+      pend.prev = loc(op.src);
+      pend.dy_s = (desc->loss == 0 && s >= desc->dy_first_step) ? dy + (size_t)(s - desc->dy_first_step) * plane : nullptr;
+      pend.dy_is_h = desc->loss == 1;
+      pend.dc = dc;
+      pend.dG_cur = ws + w.dG[buf] + (size_t)slot * dG_step;
+      pend.dGT = ws + w.dGT[buf];
+      pend.aT = ws + w.aT[buf];
+      pend.col0 = slot * d.B;
+      pend.y_out_s = y_out ? y_out + (size_t)(s - 1) * plane : nullptr;
+      pend_step = s;
+      have_pending = true;
     } else {
       return set_error(MEBPTT_EINVAL, "unknown schedule entry %d", op.op);
     }
+  }
+  if (have_pending) {
+    rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
   }
   // dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
   HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));

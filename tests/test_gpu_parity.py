@@ -224,3 +224,23 @@ def test_config4_full_size():
     assert rel_err(out.dx[t0:], ref.dx) <= TOL[w.gemm_dtype]
     assert np.abs(out.dx[:t0]).max() <= 1e-6 * np.abs(out.dx).max()
     assert np.abs(out.dh0).max() <= 1e-6 and np.abs(out.dc0).max() <= 1e-6
+
+
+@pytest.mark.parametrize("dtype", [wl.GEMM_FP32, wl.GEMM_BF16])
+def test_large_k_shapes_every_budget_bit_identical(dtype):
+    """A shape large enough for the kernels' large-K configurations (where a backward step and
+    the next forward operation share one launch whenever the schedule allows): every strategy and
+    many budgets against the oracle, and bit-identical to each other -- whether a step was fused
+    or not must not change a single bit."""
+    w = wl.Workload("largek", B=20, I=500, H=200, t=14, kind=wl.KIND_HSM, m=3, gemm_dtype=dtype,
+                    loss=wl.LOSS_EXTERNAL_DY, dy_first_step=3, seed=77)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+    first = None
+    for kind, budgets in ((wl.KIND_HSM, [1, 2, 3, 5, 14]), (wl.KIND_ISM, [1, 2, 4, 14]), (wl.KIND_MSM, [1, 2, 4, 5, 9, 23, 56])):
+        for m in budgets:
+            out, _, _, _ = run_case(w, kind=kind, m=m, ref=ref, inp=inp)
+            if first is None:
+                first = out
+            for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+                assert np.array_equal(getattr(out, name), getattr(first, name)), (kind, m, name)
