@@ -89,9 +89,12 @@ hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* d
 // x of `nslots` consecutive steps -> rows [0,NX) of aT.
 hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, void* aT, hipStream_t st);
 
-// dW_ih / dW_hh (+)= dGT * aT^T over K = nslots*B columns; db (+)= row sums of dGT.
-hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dW_ih,
-                        float* dW_hh, float* db, hipStream_t st);
+// Tile-ordered running sum of dW (+)= dGT * aT^T over K = nslots*B columns; db (+)= row sums of
+// dGT.  launch_wgrad_finish writes the caller's row-major dW_ih / dW_hh from it.
+size_t wgrad_accumulator_bytes(const Dims& d);
+hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dWacc,
+                        float* db, hipStream_t st);
+hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, hipStream_t st);
 
 hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, hipStream_t st);
 

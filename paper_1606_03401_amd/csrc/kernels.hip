@@ -682,82 +682,131 @@ hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, v
 
 // ---- weight-gradient GEMM: dW[row(m)][n] (+)= sum_k dGT[m][k] * aT[n][k] ------------------------
 
-// Each wave owns a 64 x 64 block (4 x 4 MFMA tiles); a workgroup is 2 x 2 waves.  Operand
-// fragments are fetched PD-1 macro steps ahead through a ring of register buffers, so several KiB
-// per wave are in flight while the MFMAs of the current step issue.
+// A workgroup of 2 x 2 waves owns a 128 x 128 block of dW; each wave a 64 x 64 quarter (4 x 4 MFMA
+// tiles).  Per macro step the workgroup copies the 8 + 8 operand fragments of its block (1 KiB
+// each, already in fragment order) from HBM/L2 into LDS with fully coalesced 16-byte loads --
+// fetched PD macro steps ahead through a ring of registers -- and every wave reads the 4 + 4
+// fragments it needs from LDS, so each operand byte crosses the L2 fabric once per workgroup
+// instead of once per wave.
 template <class T>
 __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, const T* __restrict__ aT, int K, int KC,
-                                                    int G4, int NTOT, int NX, int I, int H, int accumulate,
-                                                    float* __restrict__ dW_ih, float* __restrict__ dW_hh) {
+                                                    int G4, int NTOT, int accumulate, float* __restrict__ dWacc) {
   using M = Mma<T>;
-  constexpr int VEC = M::VEC, KSTEP = 4 * VEC, PD = 4;
+  constexpr int VEC = M::VEC, KSTEP = 4 * VEC, PD = 3;
+  constexpr int FRAG = 64 * VEC;                  // elements of one fragment block (1 KiB)
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  __shared__ __attribute__((aligned(16))) T lds[2][16 * FRAG];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
-  const int mt0 = (blockIdx.x * 2 + (wave & 1)) * 4;    // first 16-row tile of this wave
-  const int nt0 = (blockIdx.y * 2 + (wave >> 1)) * 4;
+  const int wm = wave & 1, wn = wave >> 1;
   const int MT = G4 / 16, NT = NTOT / 16;
-  if (mt0 >= MT || nt0 >= NT) return;
+  const int mt_wg = blockIdx.x * 8, nt_wg = blockIdx.y * 8;
   const int ncs = KC / KSTEP;    // macro steps per row tile in the fragment-tiled operands
   const int nk = K / KSTEP;      // macro steps that hold data
-  const T* ap[4];
-  const T* bp[4];
+  // this thread copies blocks q*4 + wave, q = 0..3: blocks 0..7 are dGT row tiles, 8..15 aT row tiles
+  const T* src[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int mt = min(mt0 + i, MT - 1), nt = min(nt0 + i, NT - 1);
-    ap[i] = dGT + ((size_t)mt * ncs * 64 + lane) * VEC;
-    bp[i] = aT + ((size_t)nt * ncs * 64 + lane) * VEC;
+  for (int q = 0; q < 4; ++q) {
+    const int blk = q * 4 + wave;
+    if (blk < 8)
+      src[q] = dGT + ((size_t)min(mt_wg + blk, MT - 1) * ncs * 64 + lane) * VEC;
+    else
+      src[q] = aT + ((size_t)min(nt_wg + blk - 8, NT - 1) * ncs * 64 + lane) * VEC;
   }
+  u32x4 ring[PD][4];
+  auto fetch = [&](int stage, int ks) {
+    const size_t off = (size_t)min(ks, nk - 1) * FRAG;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) ring[stage][q] = *reinterpret_cast<const u32x4*>(src[q] + off);
+  };
+  auto stash = [&](int stage, int buf) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<u32x4*>(&lds[buf][(q * 4 + wave) * FRAG + lane * VEC]) = ring[stage][q];
+  };
   f32x4 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  typename M::Frag af[PD][4], bf[PD][4];
-  auto fetch = [&](int stage, int ks) {
-    const size_t off = (size_t)min(ks, nk - 1) * 64 * VEC;
+
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      af[stage][i] = M::load(ap[i] + off);
-      bf[stage][i] = M::load(bp[i] + off);
-    }
-  };
-#pragma unroll
-  for (int st = 0; st < PD - 1; ++st) fetch(st, st);
+  for (int st = 0; st < PD; ++st) fetch(st, st);
+  stash(0, 0);
+  __syncthreads();
   for (int k0 = 0; k0 < nk; k0 += PD) {
 #pragma unroll
     for (int j = 0; j < PD; ++j) {
-      fetch((j + PD - 1) % PD, k0 + j + PD - 1);
-      if (k0 + j < nk) {
+      const int ks = k0 + j;           // macro step computed now (held in lds[ks & 1])
+      if (ks < nk) {
+        fetch(j, ks + PD);             // ring slot j was stashed for step ks; refill it PD steps ahead
+        typename M::Frag af[4], bf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          af[i] = M::load(&lds[ks & 1][(wm * 4 + i) * FRAG + lane * VEC]);
+          bf[i] = M::load(&lds[ks & 1][(8 + wn * 4 + i) * FRAG + lane * VEC]);
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) acc[i][jj] = M::mma(af[j][i], bf[j][jj], acc[i][jj]);
+          for (int jj = 0; jj < 4; ++jj) acc[i][jj] = M::mma(af[i], bf[jj], acc[i][jj]);
+        if (ks + 1 < nk) stash((j + 1) % PD, (ks + 1) & 1);
       }
+      __syncthreads();
+    }
+  }
+
+  // Epilogue: the running sum lives in a tile-ordered accumulator (each wave's 64 x 64 quarter is
+  // one contiguous 16 KiB run, a lane's four accumulator rows one float4), so the
+  // read-modify-write of every chunk is fully coalesced; wgrad_finish_kernel converts it to the
+  // caller's row-major dW once at the end of the run.
+  float4* accp = reinterpret_cast<float4*>(dWacc) +
+                 ((size_t)(blockIdx.x * gridDim.y + blockIdx.y) * 4 + wave) * 16 * 64 + lane;
+  if (accumulate) {
+    float4 old[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) old[q] = accp[q * 64];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      acc[q >> 2][q & 3][0] += old[q].x;
+      acc[q >> 2][q & 3][1] += old[q].y;
+      acc[q >> 2][q & 3][2] += old[q].z;
+      acc[q >> 2][q & 3][3] += old[q].w;
     }
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (mt0 + i >= MT) continue;
-    const int u = (mt0 + i) * 4 + lq;   // permuted row 4u + gate, gate = r
-    if (u >= H) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (nt0 + j >= NT) continue;
-      const int n = (nt0 + j) * 16 + lrow;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const size_t row = (size_t)r * H + u;
-        float* dst;
-        if (n < NX) {
-          if (n >= I) continue;
-          dst = dW_ih + row * I + n;
-        } else {
-          if (n - NX >= H) continue;
-          dst = dW_hh + row * H + (n - NX);
-        }
-        *dst = accumulate ? (*dst + acc[i][j][r]) : acc[i][j][r];
-      }
+  for (int q = 0; q < 16; ++q)
+    accp[q * 64] = float4{acc[q >> 2][q & 3][0], acc[q >> 2][q & 3][1], acc[q >> 2][q & 3][2], acc[q >> 2][q & 3][3]};
+}
+
+// dW_ih[row][n] / dW_hh[row][n] <- the tile-ordered accumulator (see wgrad_kernel's epilogue).
+__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int grid_y, int NX, int I, int H,
+                                    float* __restrict__ dW_ih, float* __restrict__ dW_hh) {
+  const size_t total = (size_t)4 * H * (I + H);
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+    int row, n, np;
+    float* dst;
+    if (idx < (size_t)4 * H * I) {
+      row = (int)(idx / I);
+      n = (int)(idx % I);
+      np = n;
+      dst = dW_ih + idx;
+    } else {
+      const size_t j = idx - (size_t)4 * H * I;
+      row = (int)(j / H);
+      n = (int)(j % H);
+      np = NX + n;
+      dst = dW_hh + j;
     }
+    const int gate = row / H, u = row % H;
+    const int mp = 4 * u + gate;                       // permuted row
+    const int mt = mp >> 4, lq = (mp & 15) >> 2, r = mp & 3;
+    const int nt = np >> 4, lrow = np & 15;
+    const int wgx = mt >> 3, wm = (mt & 7) >> 2, i = mt & 3;
+    const int wgy = nt >> 3, wn = (nt & 7) >> 2, jj = nt & 3;
+    const size_t off = ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * 16 + (i * 4 + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+    *dst = dWacc[off];
   }
 }
 
@@ -779,22 +828,33 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dG
   }
 }
 
-hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dW_ih,
-                        float* dW_hh, float* db, hipStream_t st) {
+size_t wgrad_accumulator_bytes(const Dims& d) {
+  const size_t gx = (d.G4 / 16 + 7) / 8, gy = ((d.NX + d.HP) / 16 + 7) / 8;
+  return gx * gy * 4 * 16 * 64 * sizeof(float4);
+}
+
+hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dWacc,
+                        float* db, hipStream_t st) {
   const int kstep = d.dtype ? 32 : 16;
   const int K = round_up(nslots * d.B, kstep);   // columns past nslots*B are zero
   const int NTOT = d.NX + d.HP;
   dim3 grid((d.G4 / 16 + 7) / 8, (NTOT / 16 + 7) / 8), block(256);
   dim3 bgrid((d.G4 + 3) / 4);
   if (d.dtype) {
-    wgrad_kernel<__bf16><<<grid, block, 0, st>>>((const __bf16*)dGT, (const __bf16*)aT, K, d.KC, d.G4, NTOT, d.NX, d.I,
-                                                 d.H, accumulate, dW_ih, dW_hh);
+    wgrad_kernel<__bf16><<<grid, block, 0, st>>>((const __bf16*)dGT, (const __bf16*)aT, K, d.KC, d.G4, NTOT, accumulate,
+                                                 dWacc);
     bias_grad_kernel<__bf16><<<bgrid, block, 0, st>>>((const __bf16*)dGT, nslots * d.B, d.KC, d.G4, d.H, accumulate, db);
   } else {
-    wgrad_kernel<float><<<grid, block, 0, st>>>((const float*)dGT, (const float*)aT, K, d.KC, d.G4, NTOT, d.NX, d.I, d.H,
-                                                accumulate, dW_ih, dW_hh);
+    wgrad_kernel<float><<<grid, block, 0, st>>>((const float*)dGT, (const float*)aT, K, d.KC, d.G4, NTOT, accumulate,
+                                                dWacc);
     bias_grad_kernel<float><<<bgrid, block, 0, st>>>((const float*)dGT, nslots * d.B, d.KC, d.G4, d.H, accumulate, db);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, hipStream_t st) {
+  const int grid_y = ((d.NX + d.HP) / 16 + 7) / 8;
+  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, grid_y, d.NX, d.I, d.H, dW_ih, dW_hh);
   return hipGetLastError();
 }
 

@@ -27,7 +27,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Workspace {
-  size_t Wp, bp, WTh, WTx, state, dc, dG[2], dGT[2], aT[2], total;
+  size_t Wp, bp, WTh, WTx, state, dWacc, dc, dG[2], dGT[2], aT[2], total;
 };
 
 Workspace layout(const Dims& d) {
@@ -45,6 +45,7 @@ Workspace layout(const Dims& d) {
   w.WTh = take((size_t)d.HP * d.G4 * op);
   w.WTx = take((size_t)d.NX * d.G4 * op);
   w.state = take(9 * unit);   // T0 | T1 | core A (3 units) | copy of (h0,c0) | core B (3 units)
+  w.dWacc = take(wgrad_accumulator_bytes(d));
   w.dc = take(unit / 2);
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
@@ -321,7 +322,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
       HIP_TRY(timed(MEBPTT_K_WGRAD, st2, [&] {
         hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
         if (e != hipSuccess) return e;
-        return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1, dW_ih, dW_hh, db, st2);
+        return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1,
+                            reinterpret_cast<float*>(ws + w.dWacc), db, st2);
       }));
       if (dx)
         HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
@@ -405,6 +407,9 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, st); }));
   for (int i = 0; i < 2; ++i)   // join: everything is ordered before whatever follows on `st`
     if (pending[i]) HIP_TRY(hipStreamWaitEvent(st, side->done[i], 0));
+  HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {
+    return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, st);
+  }));
 
   if (stats) {
     stats->forward_ops = fwd;
