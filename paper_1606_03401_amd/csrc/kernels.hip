@@ -35,8 +35,11 @@ Dims make_dims(int B, int I, int H, int dtype) {
   d.NX = round_up(I, 16);
   d.BP = round_up(B, 16);
   d.G4 = 4 * d.HP;
-  int ch = 512 / B;   // aim at K ~ 512 for the weight-gradient GEMM
-  d.CH = ch < 1 ? 1 : (ch > 32 ? 32 : ch);
+  // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 8 MiB (the
+  // staging is t-independent workspace), at least 2 and at most 32.
+  const size_t step_bytes = (size_t)d.BP * d.G4 * (dtype ? 2 : 4);
+  size_t ch = ((size_t)8 << 20) / step_bytes;
+  d.CH = ch < 2 ? 2 : (ch > 32 ? 32 : (int)ch);
   d.KC = round_up(d.CH * B, 32);
   return d;
 }

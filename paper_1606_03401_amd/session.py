@@ -66,6 +66,26 @@ class Session:
                              self.slots, self.workspace, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
                              self.dx, self.y, stream)
 
+    def capture(self) -> None:
+        """Records one gradient step into a HIP graph (the schedule and every pointer are fixed, so
+        the run is a static sequence of kernel launches); `replay` then re-issues it without the
+        per-launch host cost.  One eager run comes first so that nothing is created under capture."""
+        self.run()
+        torch.cuda.synchronize(self.dev)
+        self._graph_stream = torch.cuda.Stream(device=self.dev)
+        self._graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self._graph, stream=self._graph_stream):
+            self._graph_stats = self.run(stream=self._graph_stream.cuda_stream)
+
+    def replay(self) -> None:
+        self._graph.replay()
+
+    def fetch(self, stats=None) -> Outputs:
+        torch.cuda.synchronize(self.dev)
+        dn = lambda t: None if t is None else t.cpu().numpy()
+        return Outputs(dn(self.dW_ih), dn(self.dW_hh), dn(self.db), dn(self.dh0), dn(self.dc0), dn(self.dx),
+                       dn(self.y), stats)
+
     def run_and_fetch(self) -> Outputs:
         stats = self.run()
         torch.cuda.synchronize(self.dev)
