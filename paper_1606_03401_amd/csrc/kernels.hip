@@ -249,67 +249,90 @@ __device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int
   return r;
 }
 
-// One workgroup of 64*KS threads = one batch tile (16 sequences) x NG unit groups (4 hidden units =
-// 16 gate rows each); its KS waves split the K axis, every wave issuing all loads of U macro steps
-// before the first MFMA so that several KiB per wave are in flight.  Partial sums meet in LDS
-// (`red`, KS*NG*256 floats) and are added in a fixed order; wave g then runs the LSTM pointwise
-// step of unit group g.  (bx, by) = (unit-group tile, batch tile).
-template <class T, int NG, int KS, int U>
+// One workgroup of 64*KS threads = BT batch tiles (16 sequences each) x NG unit groups (4 hidden
+// units = 16 gate rows each).  Its KS waves split the K axis; every wave covers all NG x BT output
+// tiles (each weight fragment is reused for BT batch tiles, each activation fragment for NG unit
+// groups) and issues all loads of U macro steps before the first MFMA, so that several KiB per
+// wave are in flight.  Partial sums meet in LDS (`red`, KS*NG*BT*256 floats) and are added in a
+// fixed order; the NG*BT tiles are then dealt round-robin to the waves for the LSTM pointwise
+// step.  (bx, by) = (unit-group tile, batch-tile group).
+template <class T, int NG, int BT, int KS, int U>
 __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
-  static_assert(NG <= KS, "one epilogue wave per unit group");
+  constexpr int NTILE = NG * BT, TPW = (NTILE + KS - 1) / KS;   // tiles, epilogue tiles per wave
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
   const int group0 = bx * NG;
   const int ngroups = p.HP >> 2;
-  const int b0 = by * 16;
-  const int b_ld = min(b0 + lrow, p.B - 1);
-  const float* xrow = p.x_s + (size_t)b_ld * p.I;
-  const float* hrow = p.src_h + (size_t)b_ld * p.H;
+  const int b0 = by * BT * 16;
   const bool x_vec = (p.I & 3) == 0, h_vec = (p.H & 3) == 0;
   const int nsteps = p.KP / KSTEP;
+  const float* xrow[BT];
+  const float* hrow[BT];
+#pragma unroll
+  for (int t = 0; t < BT; ++t) {
+    const int b_ld = min(b0 + t * 16 + lrow, p.B - 1);
+    xrow[t] = p.x_s + (size_t)b_ld * p.I;
+    hrow[t] = p.src_h + (size_t)b_ld * p.H;
+  }
   const T* wbase[NG];   // fragment-tiled: tile (group) stride = nsteps * 64 * VEC
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     int grp = min(group0 + g, ngroups - 1);
     wbase[g] = reinterpret_cast<const T*>(p.Wp) + ((size_t)grp * nsteps * 64 + lane) * VEC;
   }
-  f32x4 acc[NG];
+  f32x4 acc[NG][BT];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < NG; ++g)
+#pragma unroll
+    for (int t = 0; t < BT; ++t) acc[g][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // The epilogue waves fetch their pointwise operands now, so that their latency hides behind
-  // the K loop instead of following it.
-  const int b = b0 + lrow;
-  const int u = (group0 + wave) * 4 + lq;
-  const bool epi = wave < NG && b < p.B && u < p.H;
-  const size_t e = (size_t)b * p.H + u;
-  float4 bias = float4{0.f, 0.f, 0.f, 0.f};
-  float c_prev = 0.0f;
-  if (epi) {
-    bias = *reinterpret_cast<const float4*>(p.bp + 4 * u);
-    c_prev = p.src_c[e];
+  // The epilogue operands of this wave's tiles are fetched now, so that their latency hides
+  // behind the K loop instead of following it.  Tile id = g * BT + t.
+  bool epi[TPW];
+  size_t eidx[TPW];
+  float4 bias[TPW];
+  float c_prev[TPW];
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const int tile = wave + q * KS;
+    const int g = tile / BT, t = tile % BT;
+    const int b = b0 + t * 16 + lrow;
+    const int u = (group0 + g) * 4 + lq;
+    epi[q] = tile < NTILE && b < p.B && u < p.H;
+    eidx[q] = (size_t)b * p.H + u;
+    bias[q] = float4{0.f, 0.f, 0.f, 0.f};
+    c_prev[q] = 0.0f;
+    if (epi[q]) {
+      bias[q] = *reinterpret_cast<const float4*>(p.bp + 4 * u);
+      c_prev[q] = p.src_c[eidx[q]];
+    }
   }
 
   for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-    RawAct<VEC> rb[U];
+    RawAct<VEC> rb[U][BT];
     typename M::Frag af[U][NG];
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
       const int s = min(s0 + uu * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
       const int k = s * KSTEP + VEC * lq;
-      rb[uu] = (k < p.KX) ? load_raw<VEC>(xrow, k, p.I, x_vec) : load_raw<VEC>(hrow, k - p.KX, p.H, h_vec);
+#pragma unroll
+      for (int t = 0; t < BT; ++t)
+        rb[uu][t] = (k < p.KX) ? load_raw<VEC>(xrow[t], k, p.I, x_vec) : load_raw<VEC>(hrow[t], k - p.KX, p.H, h_vec);
 #pragma unroll
       for (int g = 0; g < NG; ++g) af[uu][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
     }
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
       if (s0 + uu * KS < nsteps) {
-        typename M::Frag bf = M::from_f32(rb[uu].v);
 #pragma unroll
-        for (int g = 0; g < NG; ++g) acc[g] = M::mma(af[uu][g], bf, acc[g]);
+        for (int t = 0; t < BT; ++t) {
+          typename M::Frag bf = M::from_f32(rb[uu][t].v);
+#pragma unroll
+          for (int g = 0; g < NG; ++g) acc[g][t] = M::mma(af[uu][g], bf, acc[g][t]);
+        }
       }
     }
   }
@@ -317,35 +340,41 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
 #pragma unroll
   for (int g = 0; g < NG; ++g)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[((wave * NG + g) * 4 + r) * 64 + lane] = acc[g][r];
-  __syncthreads();
-  if (wave >= NG) return;
-  const int g = wave;
-  float G[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int q = 0; q < KS; ++q)   // fixed order: results do not depend on scheduling
+    for (int t = 0; t < BT; ++t)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) G[r] += red[((q * NG + g) * 4 + r) * 64 + lane];
-  if (!epi) return;
-  const float gi = sigmoidf_(G[0] + bias.x);
-  const float gf = sigmoidf_(G[1] + bias.y);
-  const float gg = tanhf(G[2] + bias.z);
-  const float go = sigmoidf_(G[3] + bias.w);
-  const float c = gf * c_prev + gi * gg;
-  const float h = go * tanhf(c);
-  p.dst_h[e] = h;
-  p.dst_c[e] = c;
-  if (p.g_i) {
-    p.g_i[e] = gi;
-    p.g_f[e] = gf;
-    p.g_g[e] = gg;
-    p.g_o[e] = go;
+      for (int r = 0; r < 4; ++r) red[((wave * NTILE + g * BT + t) * 4 + r) * 64 + lane] = acc[g][t][r];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const int tile = wave + q * KS;
+    if (tile >= NTILE) break;
+    float G[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int w = 0; w < KS; ++w)   // fixed order: results do not depend on scheduling
+#pragma unroll
+      for (int r = 0; r < 4; ++r) G[r] += red[((w * NTILE + tile) * 4 + r) * 64 + lane];
+    if (!epi[q]) continue;
+    const size_t e = eidx[q];
+    const float gi = sigmoidf_(G[0] + bias[q].x);
+    const float gf = sigmoidf_(G[1] + bias[q].y);
+    const float gg = tanhf(G[2] + bias[q].z);
+    const float go = sigmoidf_(G[3] + bias[q].w);
+    const float c = gf * c_prev[q] + gi * gg;
+    const float h = go * tanhf(c);
+    p.dst_h[e] = h;
+    p.dst_c[e] = c;
+    if (p.g_i) {
+      p.g_i[e] = gi;
+      p.g_f[e] = gf;
+      p.g_g[e] = gg;
+      p.g_o[e] = go;
+    }
   }
 }
 
-template <class T, int NG, int KS, int U>
+template <class T, int NG, int BT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
-  __shared__ float red[KS * NG * 4 * 64];
-  forward_body<T, NG, KS, U>(p, blockIdx.x, blockIdx.y, red);
+  __shared__ float red[KS * NG * BT * 4 * 64];
+  forward_body<T, NG, BT, KS, U>(p, blockIdx.x, blockIdx.y, red);
 }
 
 // ---- backward step: dh GEMM + loss-gradient injection + LSTM pointwise backward --------------
@@ -364,96 +393,135 @@ struct BwdParams {
   int B, H, HP, G4, NX, KC, BP;
 };
 
-// One workgroup of 64*KS threads = one output tile (16 hidden units x 16 sequences); its KS waves
-// split K = 4*HP, each issuing the loads of U macro steps before the first MFMA.  Partial sums meet
-// in LDS (`red`, KS*256 floats); waves 0..3 then each take one of the four hidden units a lane owns
-// and run the pointwise backward.  (bx, by) = (hidden-unit tile, batch tile).
-template <class T, int KS, int U>
+// One workgroup of 64*KS threads = NT hidden-unit tiles x BT batch tiles (16 x 16 outputs each);
+// its KS waves split K = 4*HP, every wave covering all NT x BT tiles and issuing the loads of U
+// macro steps before the first MFMA.  Partial sums meet in LDS (`red`, KS*NT*BT*256 floats).  The
+// pointwise backward has NT*BT*4 pieces of work (tile x which of the lane's four hidden units),
+// dealt round-robin to the waves.  (bx, by) = (hidden-unit tile group, batch-tile group).
+template <class T, int NT, int BT, int KS, int U>
 __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
-  static_assert(KS >= 4, "four epilogue waves");
+  constexpr int NTILE = NT * BT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
-  const int n0 = bx * 16;
-  const int b0 = by * 16;
-  // Epilogue waves (0..3, one hidden unit of the lane's four each) fetch their pointwise operands
-  // before the K loop so that the latency overlaps with it.
-  const int b = b0 + lrow;
-  const int n = n0 + 4 * lq + wave;
-  const bool epi = wave < 4 && b < p.B && n < p.H;
-  const size_t e = (size_t)b * p.H + n;
-  float h = 0.f, dy = 0.f, gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, c_s = 0.f, c_prev = 0.f, dc_in = 0.f, h_prev = 0.f;
-  if (epi) {
-    if (p.dy_is_h || p.y_out_s) h = p.h[e];
-    if (!p.dy_is_h && p.dy_s) dy = p.dy_s[e];
-    gi = p.g_i[e];
-    gf = p.g_f[e];
-    gg = p.g_g[e];
-    go = p.g_o[e];
-    c_s = p.c[e];
-    c_prev = p.c_prev[e];
-    dc_in = p.dc[e];
-    h_prev = p.h_prev[e];
+  const int ntiles_n = p.HP / 16, ntiles_b = p.BP / 16;
+  // Epilogue pieces of this wave: piece id = tile * 4 + r, tile = tn * BT + tb.  Their pointwise
+  // operands are fetched before the K loop so that the latency overlaps with it.
+  bool epi[PPW];
+  size_t eidx[PPW];
+  int en[PPW], eb[PPW];
+  float h[PPW], dy[PPW], gi[PPW], gf[PPW], gg[PPW], go[PPW], c_s[PPW], c_prev[PPW], dc_in[PPW], h_prev[PPW];
+#pragma unroll
+  for (int q = 0; q < PPW; ++q) {
+    const int piece = wave + q * KS;
+    const int tile = piece >> 2, r = piece & 3;
+    const int tn = tile / BT, tb = tile % BT;
+    const int b = (by * BT + tb) * 16 + lrow;
+    const int n = (bx * NT + tn) * 16 + 4 * lq + r;
+    epi[q] = piece < NPIECE && b < p.B && n < p.H;
+    eidx[q] = (size_t)b * p.H + n;
+    en[q] = n;
+    eb[q] = b;
+    h[q] = dy[q] = gi[q] = gf[q] = gg[q] = go[q] = c_s[q] = c_prev[q] = dc_in[q] = h_prev[q] = 0.f;
+    if (epi[q]) {
+      const size_t e = eidx[q];
+      if (p.dy_is_h || p.y_out_s) h[q] = p.h[e];
+      if (!p.dy_is_h && p.dy_s) dy[q] = p.dy_s[e];
+      gi[q] = p.g_i[e];
+      gf[q] = p.g_f[e];
+      gg[q] = p.g_g[e];
+      go[q] = p.g_o[e];
+      c_s[q] = p.c[e];
+      c_prev[q] = p.c_prev[e];
+      dc_in[q] = p.dc[e];
+      h_prev[q] = p.h_prev[e];
+    }
   }
   if (p.dG_next) {
-    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[NT][BT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int j = 0; j < BT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int nsteps = p.G4 / KSTEP;
-    const T* abase = reinterpret_cast<const T*>(p.WTh) + ((size_t)bx * nsteps * 64 + lane) * VEC;
-    const T* bbase = reinterpret_cast<const T*>(p.dG_next) + ((size_t)by * nsteps * 64 + lane) * VEC;
+    const T* abase[NT];
+    const T* bbase[BT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      abase[i] = reinterpret_cast<const T*>(p.WTh) + ((size_t)min(bx * NT + i, ntiles_n - 1) * nsteps * 64 + lane) * VEC;
+#pragma unroll
+    for (int j = 0; j < BT; ++j)
+      bbase[j] = reinterpret_cast<const T*>(p.dG_next) + ((size_t)min(by * BT + j, ntiles_b - 1) * nsteps * 64 + lane) * VEC;
     for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-      typename M::Frag af[U], bf[U];
+      typename M::Frag af[U][NT], bf[U][BT];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int s = min(s0 + u * KS, nsteps - 1);
-        af[u] = M::load(abase + (size_t)s * 64 * VEC);
-        bf[u] = M::load(bbase + (size_t)s * 64 * VEC);
+        const size_t off = (size_t)min(s0 + u * KS, nsteps - 1) * 64 * VEC;
+#pragma unroll
+        for (int i = 0; i < NT; ++i) af[u][i] = M::load(abase[i] + off);
+#pragma unroll
+        for (int j = 0; j < BT; ++j) bf[u][j] = M::load(bbase[j] + off);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (s0 + u * KS < nsteps) acc = M::mma(af[u], bf[u], acc);
+        if (s0 + u * KS < nsteps) {
+#pragma unroll
+          for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < BT; ++j) acc[i][j] = M::mma(af[u][i], bf[u][j], acc[i][j]);
+        }
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int j = 0; j < BT; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((wave * NTILE + i * BT + j) * 4 + r) * 64 + lane] = acc[i][j][r];
     __syncthreads();
   }
-  if (wave >= 4) return;
-  const int r = wave;
-  float dh = 0.0f;
-  if (p.dG_next)
-    for (int q = 0; q < KS; ++q) dh += red[(q * 4 + r) * 64 + lane];   // fixed order
-  if (!epi) return;
-  dh += p.dy_is_h ? h : dy;
-  if (p.y_out_s) p.y_out_s[e] = h;
-  const float tc = tanhf(c_s);
-  const float d_o = dh * tc;
-  const float dct = dc_in + dh * go * (1.0f - tc * tc);
-  const float dGi = dct * gg * gi * (1.0f - gi);
-  const float dGf = dct * c_prev * gf * (1.0f - gf);
-  const float dGg = dct * gi * (1.0f - gg * gg);
-  const float dGo = d_o * go * (1.0f - go);
-  p.dc[e] = dct * gf;
-  const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
-  // dG of this step, fragment-tiled [b][4n + gate]: the four gates are consecutive in one lane slot
-  T* dG4 = reinterpret_cast<T*>(p.dG_cur) + ft_offset<T>(b, 4 * n, p.G4 / KSTEP);
-  dG4[0] = q0;
-  dG4[1] = q1;
-  dG4[2] = q2;
-  dG4[3] = q3;
-  // transposed copies for the weight gradient, fragment-tiled [4n + gate][col] and [NX + n][col]
-  const int col = p.col0 + b, ncs = p.KC / KSTEP;
-  T* dGT = reinterpret_cast<T*>(p.dGT);
-  dGT[ft_offset<T>(4 * n + 0, col, ncs)] = q0;
-  dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
-  dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
-  dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
-  reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)h_prev;
+#pragma unroll
+  for (int q = 0; q < PPW; ++q) {
+    const int piece = wave + q * KS;
+    if (piece >= NPIECE) break;
+    float dh = 0.0f;
+    if (p.dG_next)
+      for (int w = 0; w < KS; ++w) dh += red[(w * NPIECE + piece) * 64 + lane];   // fixed order
+    if (!epi[q]) continue;
+    const size_t e = eidx[q];
+    const int n = en[q], b = eb[q];
+    dh += p.dy_is_h ? h[q] : dy[q];
+    if (p.y_out_s) p.y_out_s[e] = h[q];
+    const float tc = tanhf(c_s[q]);
+    const float d_o = dh * tc;
+    const float dct = dc_in[q] + dh * go[q] * (1.0f - tc * tc);
+    const float dGi = dct * gg[q] * gi[q] * (1.0f - gi[q]);
+    const float dGf = dct * c_prev[q] * gf[q] * (1.0f - gf[q]);
+    const float dGg = dct * gi[q] * (1.0f - gg[q] * gg[q]);
+    const float dGo = d_o * go[q] * (1.0f - go[q]);
+    p.dc[e] = dct * gf[q];
+    const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
+    // dG of this step, fragment-tiled [b][4n + gate]: the four gates are consecutive in one lane slot
+    T* dG4 = reinterpret_cast<T*>(p.dG_cur) + ft_offset<T>(b, 4 * n, p.G4 / KSTEP);
+    dG4[0] = q0;
+    dG4[1] = q1;
+    dG4[2] = q2;
+    dG4[3] = q3;
+    // transposed copies for the weight gradient, fragment-tiled [4n + gate][col] and [NX + n][col]
+    const int col = p.col0 + b, ncs = p.KC / KSTEP;
+    T* dGT = reinterpret_cast<T*>(p.dGT);
+    dGT[ft_offset<T>(4 * n + 0, col, ncs)] = q0;
+    dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
+    dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
+    dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
+    reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)h_prev[q];
+  }
 }
 
-template <class T, int KS, int U>
+template <class T, int NT, int BT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
-  __shared__ float red[KS * 4 * 64];
-  backward_body<T, KS, U>(p, blockIdx.x, blockIdx.y, red);
+  __shared__ float red[KS * NT * BT * 4 * 64];
+  backward_body<T, NT, BT, KS, U>(p, blockIdx.x, blockIdx.y, red);
 }
 
 // ---- fused launch: a backward step and an independent forward step ---------------------------
@@ -472,34 +540,55 @@ __global__ __launch_bounds__(64 * PAIR_BKS) void pair_kernel(FwdParams f, BwdPar
   static_assert(PAIR_FKS * PAIR_NG >= PAIR_BKS && PAIR_FKS == PAIR_BKS, "shared buffer and block size cover both roles");
   const int id = blockIdx.x;
   if (id < nf)
-    forward_body<T, PAIR_NG, PAIR_FKS, PAIR_FU>(f, id % nfx, id / nfx, red);
+    forward_body<T, PAIR_NG, 1, PAIR_FKS, PAIR_FU>(f, id % nfx, id / nfx, red);
   else
-    backward_body<T, PAIR_BKS, PAIR_BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
+    backward_body<T, 1, 1, PAIR_BKS, PAIR_BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
+}
+
+// Kernel configurations by shape.  Tiles per workgroup grow with the problem so that the grid
+// stays near one workgroup per compute unit while every operand byte is reused as often as
+// possible; the choice depends on the shape only, never on the schedule.
+enum FwdConfig { FWD_TINY, FWD_SMALLK, FWD_B1, FWD_42, FWD_82 };
+enum BwdConfig { BWD_SMALLK, BWD_11, BWD_12, BWD_22 };
+constexpr int TARGET_WGS = 256;
+
+template <class T>
+static FwdConfig forward_config(const Dims& d) {
+  const int nsteps = d.KP / (4 * Mma<T>::VEC);
+  if (nsteps <= 8) return FWD_TINY;
+  if (nsteps <= 20) return FWD_SMALLK;
+  const int ngroups = d.HP / 4, bt = d.BP / 16;
+  if (bt >= 2 && ((ngroups + 7) / 8) * ((bt + 1) / 2) >= TARGET_WGS) return FWD_82;
+  if (bt >= 2 && ((ngroups + 3) / 4) * ((bt + 1) / 2) >= TARGET_WGS) return FWD_42;
+  return FWD_B1;
 }
 
 template <class T>
-static bool uses_main_forward_config(const Dims& d) {
-  return d.KP / (4 * Mma<T>::VEC) > 20;
-}
-template <class T>
-static bool uses_main_backward_config(const Dims& d) {
-  return d.G4 / (4 * Mma<T>::VEC) > 16;
+static BwdConfig backward_config(const Dims& d) {
+  const int nsteps = d.G4 / (4 * Mma<T>::VEC);
+  if (nsteps <= 16) return BWD_SMALLK;
+  const int nt = d.HP / 16, bt = d.BP / 16;
+  if (nt >= 2 && bt >= 2 && ((nt + 1) / 2) * ((bt + 1) / 2) >= TARGET_WGS) return BWD_22;
+  if (bt >= 2 && nt * ((bt + 1) / 2) >= TARGET_WGS) return BWD_12;
+  return BWD_11;
 }
 
-template <class T, int NG, int KS, int U>
+template <class T, int NG, int BT, int KS, int U>
 static hipError_t launch_forward_cfg(const Dims& d, const FwdParams& p, hipStream_t st) {
-  dim3 grid((d.HP / 4 + NG - 1) / NG, d.BP / 16), block(64 * KS);
-  forward_kernel<T, NG, KS, U><<<grid, block, 0, st>>>(p);
+  dim3 grid((d.HP / 4 + NG - 1) / NG, (d.BP / 16 + BT - 1) / BT), block(64 * KS);
+  forward_kernel<T, NG, BT, KS, U><<<grid, block, 0, st>>>(p);
   return hipGetLastError();
 }
 
 template <class T>
 static hipError_t launch_forward_t(const Dims& d, const FwdParams& p, hipStream_t st) {
-  constexpr int KSTEP = 4 * Mma<T>::VEC;
-  const int nsteps = d.KP / KSTEP;
-  if (nsteps <= 8) return launch_forward_cfg<T, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
-  if (nsteps <= 20) return launch_forward_cfg<T, 4, 4, 5>(d, p, st);
-  return launch_forward_cfg<T, 4, 8, 5>(d, p, st);
+  switch (forward_config<T>(d)) {
+    case FWD_TINY: return launch_forward_cfg<T, 1, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
+    case FWD_SMALLK: return launch_forward_cfg<T, 4, 1, 4, 5>(d, p, st);
+    case FWD_82: return launch_forward_cfg<T, 8, 2, 8, 2>(d, p, st);
+    case FWD_42: return launch_forward_cfg<T, 4, 2, 8, 3>(d, p, st);
+    default: return launch_forward_cfg<T, PAIR_NG, 1, PAIR_FKS, 5>(d, p, st);
+  }
 }
 
 static FwdParams make_fwd_params(const Dims& d, const void* Wp, const float* bp, const float* x_s,
@@ -534,14 +623,21 @@ hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const 
   return d.dtype ? launch_forward_t<__bf16>(d, p, st) : launch_forward_t<float>(d, p, st);
 }
 
+template <class T, int NT, int BT, int KS, int U>
+static hipError_t launch_backward_cfg(const Dims& d, const BwdParams& p, hipStream_t st) {
+  dim3 grid((d.HP / 16 + NT - 1) / NT, (d.BP / 16 + BT - 1) / BT), block(64 * KS);
+  backward_kernel<T, NT, BT, KS, U><<<grid, block, 0, st>>>(p);
+  return hipGetLastError();
+}
+
 template <class T>
 static hipError_t launch_backward_t(const Dims& d, const BwdParams& p, hipStream_t st) {
-  dim3 grid(d.HP / 16, d.BP / 16);
-  if (!uses_main_backward_config<T>(d))
-    backward_kernel<T, 4, 4><<<grid, dim3(256), 0, st>>>(p);
-  else
-    backward_kernel<T, PAIR_BKS, PAIR_BU><<<grid, dim3(64 * PAIR_BKS), 0, st>>>(p);
-  return hipGetLastError();
+  switch (backward_config<T>(d)) {
+    case BWD_SMALLK: return launch_backward_cfg<T, 1, 1, 4, 4>(d, p, st);
+    case BWD_22: return launch_backward_cfg<T, 2, 2, 8, 4>(d, p, st);
+    case BWD_12: return launch_backward_cfg<T, 1, 2, 8, 6>(d, p, st);
+    default: return launch_backward_cfg<T, 1, 1, PAIR_BKS, PAIR_BU>(d, p, st);
+  }
 }
 
 static BwdParams make_bwd_params(const Dims& d, const BackwardArgs& a) {
@@ -581,8 +677,8 @@ hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st)
 }
 
 bool can_fuse_pair(const Dims& d) {
-  return d.dtype ? (uses_main_forward_config<__bf16>(d) && uses_main_backward_config<__bf16>(d))
-                 : (uses_main_forward_config<float>(d) && uses_main_backward_config<float>(d));
+  return d.dtype ? (forward_config<__bf16>(d) == FWD_B1 && backward_config<__bf16>(d) == BWD_11)
+                 : (forward_config<float>(d) == FWD_B1 && backward_config<float>(d) == BWD_11);
 }
 
 hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, const void* Wp, const float* bp,
@@ -700,7 +796,6 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
   typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
   __shared__ __attribute__((aligned(16))) T lds[2][16 * FRAG];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int lrow = lane & 15, lq = lane >> 4;
   const int wm = wave & 1, wn = wave >> 1;
   const int MT = G4 / 16, NT = NTOT / 16;
   const int mt_wg = blockIdx.x * 8, nt_wg = blockIdx.y * 8;

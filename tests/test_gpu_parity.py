@@ -85,6 +85,8 @@ def test_config1_every_budget_every_strategy():
     (64, 40, 200, 12, wl.KIND_MSM, 9),     # several k-steps, ragged tail in K
     (130, 96, 136, 7, wl.KIND_HSM, 4),     # more than two batch tiles per workgroup row
     (1, 1, 1, 3, wl.KIND_HSM, 2),          # degenerate
+    (130, 100, 1000, 5, wl.KIND_MSM, 6),   # multi-tile workgroups (4 groups x 2 batch tiles; 1 x 2 backward), ragged
+    (120, 72, 2040, 4, wl.KIND_HSM, 2),    # largest workgroup tiles (8 x 2 forward, 2 x 2 backward), ragged
 ])
 def test_ragged_shapes(B, I, H, t, kind, m, dtype):
     if H == 1 and dtype == wl.GEMM_BF16:
