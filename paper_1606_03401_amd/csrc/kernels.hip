@@ -781,52 +781,54 @@ hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, v
 
 // ---- weight-gradient GEMM: dW[row(m)][n] (+)= sum_k dGT[m][k] * aT[n][k] ------------------------
 
-// A workgroup of 2 x 2 waves owns a 128 x 128 block of dW; each wave a 64 x 64 quarter (4 x 4 MFMA
-// tiles).  Per macro step the workgroup copies the 8 + 8 operand fragments of its block (1 KiB
-// each, already in fragment order) from HBM/L2 into LDS with fully coalesced 16-byte loads --
-// fetched PD macro steps ahead through a ring of registers -- and every wave reads the 4 + 4
-// fragments it needs from LDS, so each operand byte crosses the L2 fabric once per workgroup
-// instead of once per wave.
-template <class T>
+// A workgroup of 2 x 2 waves owns a block of 2*WT x 2*WT MFMA tiles of dW (128 x 128 elements for
+// WT = 4, 64 x 64 for WT = 2, used when the larger block would leave most compute units idle);
+// each wave a WT x WT quarter.  Per macro step the workgroup copies the 2*WT + 2*WT operand
+// fragments of its block (1 KiB each, already in fragment order) from HBM/L2 into LDS with fully
+// coalesced 16-byte loads -- fetched PD macro steps ahead through a ring of registers -- and every
+// wave reads the WT + WT fragments it needs from LDS, so each operand byte crosses the L2 fabric
+// once per workgroup instead of once per wave.
+template <class T, int WT>
 __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, const T* __restrict__ aT, int K, int KC,
                                                     int G4, int NTOT, int accumulate, float* __restrict__ dWacc) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC, PD = 3;
   constexpr int FRAG = 64 * VEC;                  // elements of one fragment block (1 KiB)
   typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-  __shared__ __attribute__((aligned(16))) T lds[2][16 * FRAG];
+  __shared__ __attribute__((aligned(16))) T lds[2][4 * WT * FRAG];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave & 1, wn = wave >> 1;
   const int MT = G4 / 16, NT = NTOT / 16;
-  const int mt_wg = blockIdx.x * 8, nt_wg = blockIdx.y * 8;
+  const int mt_wg = blockIdx.x * 2 * WT, nt_wg = blockIdx.y * 2 * WT;
   const int ncs = KC / KSTEP;    // macro steps per row tile in the fragment-tiled operands
   const int nk = K / KSTEP;      // macro steps that hold data
-  // this thread copies blocks q*4 + wave, q = 0..3: blocks 0..7 are dGT row tiles, 8..15 aT row tiles
-  const T* src[4];
+  // this thread copies blocks q*4 + wave, q = 0..WT-1: the first 2*WT blocks are dGT row tiles,
+  // the other 2*WT are aT row tiles
+  const T* src[WT];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < WT; ++q) {
     const int blk = q * 4 + wave;
-    if (blk < 8)
+    if (blk < 2 * WT)
       src[q] = dGT + ((size_t)min(mt_wg + blk, MT - 1) * ncs * 64 + lane) * VEC;
     else
-      src[q] = aT + ((size_t)min(nt_wg + blk - 8, NT - 1) * ncs * 64 + lane) * VEC;
+      src[q] = aT + ((size_t)min(nt_wg + blk - 2 * WT, NT - 1) * ncs * 64 + lane) * VEC;
   }
-  u32x4 ring[PD][4];
+  u32x4 ring[PD][WT];
   auto fetch = [&](int stage, int ks) {
     const size_t off = (size_t)min(ks, nk - 1) * FRAG;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) ring[stage][q] = *reinterpret_cast<const u32x4*>(src[q] + off);
+    for (int q = 0; q < WT; ++q) ring[stage][q] = *reinterpret_cast<const u32x4*>(src[q] + off);
   };
   auto stash = [&](int stage, int buf) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < WT; ++q)
       *reinterpret_cast<u32x4*>(&lds[buf][(q * 4 + wave) * FRAG + lane * VEC]) = ring[stage][q];
   };
-  f32x4 acc[4][4];
+  f32x4 acc[WT][WT];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < WT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
   for (int st = 0; st < PD; ++st) fetch(st, st);
@@ -838,47 +840,47 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
       const int ks = k0 + j;           // macro step computed now (held in lds[ks & 1])
       if (ks < nk) {
         fetch(j, ks + PD);             // ring slot j was stashed for step ks; refill it PD steps ahead
-        typename M::Frag af[4], bf[4];
+        typename M::Frag af[WT], bf[WT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          af[i] = M::load(&lds[ks & 1][(wm * 4 + i) * FRAG + lane * VEC]);
-          bf[i] = M::load(&lds[ks & 1][(8 + wn * 4 + i) * FRAG + lane * VEC]);
+        for (int i = 0; i < WT; ++i) {
+          af[i] = M::load(&lds[ks & 1][(wm * WT + i) * FRAG + lane * VEC]);
+          bf[i] = M::load(&lds[ks & 1][(2 * WT + wn * WT + i) * FRAG + lane * VEC]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < WT; ++i)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) acc[i][jj] = M::mma(af[i], bf[jj], acc[i][jj]);
+          for (int jj = 0; jj < WT; ++jj) acc[i][jj] = M::mma(af[i], bf[jj], acc[i][jj]);
         if (ks + 1 < nk) stash((j + 1) % PD, (ks + 1) & 1);
       }
       __syncthreads();
     }
   }
 
-  // Epilogue: the running sum lives in a tile-ordered accumulator (each wave's 64 x 64 quarter is
-  // one contiguous 16 KiB run, a lane's four accumulator rows one float4), so the
+  // Epilogue: the running sum lives in a tile-ordered accumulator (each wave's quarter is one
+  // contiguous run, a lane's four accumulator rows one float4), so the
   // read-modify-write of every chunk is fully coalesced; wgrad_finish_kernel converts it to the
   // caller's row-major dW once at the end of the run.
   float4* accp = reinterpret_cast<float4*>(dWacc) +
-                 ((size_t)(blockIdx.x * gridDim.y + blockIdx.y) * 4 + wave) * 16 * 64 + lane;
+                 ((size_t)(blockIdx.x * gridDim.y + blockIdx.y) * 4 + wave) * (WT * WT) * 64 + lane;
   if (accumulate) {
-    float4 old[16];
+    float4 old[WT * WT];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) old[q] = accp[q * 64];
+    for (int q = 0; q < WT * WT; ++q) old[q] = accp[q * 64];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      acc[q >> 2][q & 3][0] += old[q].x;
-      acc[q >> 2][q & 3][1] += old[q].y;
-      acc[q >> 2][q & 3][2] += old[q].z;
-      acc[q >> 2][q & 3][3] += old[q].w;
+    for (int q = 0; q < WT * WT; ++q) {
+      acc[q / WT][q % WT][0] += old[q].x;
+      acc[q / WT][q % WT][1] += old[q].y;
+      acc[q / WT][q % WT][2] += old[q].z;
+      acc[q / WT][q % WT][3] += old[q].w;
     }
   }
 #pragma unroll
-  for (int q = 0; q < 16; ++q)
-    accp[q * 64] = float4{acc[q >> 2][q & 3][0], acc[q >> 2][q & 3][1], acc[q >> 2][q & 3][2], acc[q >> 2][q & 3][3]};
+  for (int q = 0; q < WT * WT; ++q)
+    accp[q * 64] = float4{acc[q / WT][q % WT][0], acc[q / WT][q % WT][1], acc[q / WT][q % WT][2], acc[q / WT][q % WT][3]};
 }
 
 // dW_ih[row][n] / dW_hh[row][n] <- the tile-ordered accumulator (see wgrad_kernel's epilogue).
-__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int grid_y, int NX, int I, int H,
+__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int NX, int I, int H,
                                     float* __restrict__ dW_ih, float* __restrict__ dW_hh) {
   const size_t total = (size_t)4 * H * (I + H);
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -901,9 +903,10 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int grid_y,
     const int mp = 4 * u + gate;                       // permuted row
     const int mt = mp >> 4, lq = (mp & 15) >> 2, r = mp & 3;
     const int nt = np >> 4, lrow = np & 15;
-    const int wgx = mt >> 3, wm = (mt & 7) >> 2, i = mt & 3;
-    const int wgy = nt >> 3, wn = (nt & 7) >> 2, jj = nt & 3;
-    const size_t off = ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * 16 + (i * 4 + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+    const int wgx = mt / (2 * WT), wm = (mt % (2 * WT)) / WT, i = mt % WT;
+    const int wgy = nt / (2 * WT), wn = (nt % (2 * WT)) / WT, jj = nt % WT;
+    const size_t off =
+        ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * (WT * WT) + (i * WT + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
     *dst = dWacc[off];
   }
 }
@@ -926,33 +929,46 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dG
   }
 }
 
+// Wave tile of the weight-gradient GEMM: 4 x 4 MFMA tiles when that still gives the chip enough
+// workgroups, else 2 x 2.
+static int wgrad_wave_tile(const Dims& d) {
+  const int MT = d.G4 / 16, NT = (d.NX + d.HP) / 16;
+  return ((MT + 7) / 8) * ((NT + 7) / 8) >= 200 ? 4 : 2;
+}
+
 size_t wgrad_accumulator_bytes(const Dims& d) {
-  const size_t gx = (d.G4 / 16 + 7) / 8, gy = ((d.NX + d.HP) / 16 + 7) / 8;
-  return gx * gy * 4 * 16 * 64 * sizeof(float4);
+  const int WT = wgrad_wave_tile(d);
+  const size_t gx = (d.G4 / 16 + 2 * WT - 1) / (2 * WT), gy = ((d.NX + d.HP) / 16 + 2 * WT - 1) / (2 * WT);
+  return gx * gy * 4 * WT * WT * 64 * sizeof(float4);
+}
+
+template <class T>
+static void launch_wgrad_t(const Dims& d, const void* dGT, const void* aT, int K, int nvalid, int accumulate,
+                           float* dWacc, float* db, hipStream_t st) {
+  const int NTOT = d.NX + d.HP, WT = wgrad_wave_tile(d);
+  dim3 grid((d.G4 / 16 + 2 * WT - 1) / (2 * WT), (NTOT / 16 + 2 * WT - 1) / (2 * WT)), block(256);
+  if (WT == 4)
+    wgrad_kernel<T, 4><<<grid, block, 0, st>>>((const T*)dGT, (const T*)aT, K, d.KC, d.G4, NTOT, accumulate, dWacc);
+  else
+    wgrad_kernel<T, 2><<<grid, block, 0, st>>>((const T*)dGT, (const T*)aT, K, d.KC, d.G4, NTOT, accumulate, dWacc);
+  bias_grad_kernel<T><<<dim3((d.G4 + 3) / 4), block, 0, st>>>((const T*)dGT, nvalid, d.KC, d.G4, d.H, accumulate, db);
 }
 
 hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dWacc,
                         float* db, hipStream_t st) {
   const int kstep = d.dtype ? 32 : 16;
   const int K = round_up(nslots * d.B, kstep);   // columns past nslots*B are zero
-  const int NTOT = d.NX + d.HP;
-  dim3 grid((d.G4 / 16 + 7) / 8, (NTOT / 16 + 7) / 8), block(256);
-  dim3 bgrid((d.G4 + 3) / 4);
-  if (d.dtype) {
-    wgrad_kernel<__bf16><<<grid, block, 0, st>>>((const __bf16*)dGT, (const __bf16*)aT, K, d.KC, d.G4, NTOT, accumulate,
-                                                 dWacc);
-    bias_grad_kernel<__bf16><<<bgrid, block, 0, st>>>((const __bf16*)dGT, nslots * d.B, d.KC, d.G4, d.H, accumulate, db);
-  } else {
-    wgrad_kernel<float><<<grid, block, 0, st>>>((const float*)dGT, (const float*)aT, K, d.KC, d.G4, NTOT, accumulate,
-                                                dWacc);
-    bias_grad_kernel<float><<<bgrid, block, 0, st>>>((const float*)dGT, nslots * d.B, d.KC, d.G4, d.H, accumulate, db);
-  }
+  if (d.dtype)
+    launch_wgrad_t<__bf16>(d, dGT, aT, K, nslots * d.B, accumulate, dWacc, db, st);
+  else
+    launch_wgrad_t<float>(d, dGT, aT, K, nslots * d.B, accumulate, dWacc, db, st);
   return hipGetLastError();
 }
 
 hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, hipStream_t st) {
-  const int grid_y = ((d.NX + d.HP) / 16 + 7) / 8;
-  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, grid_y, d.NX, d.I, d.H, dW_ih, dW_hh);
+  const int WT = wgrad_wave_tile(d);
+  const int grid_y = ((d.NX + d.HP) / 16 + 2 * WT - 1) / (2 * WT);
+  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.I, d.H, dW_ih, dW_hh);
   return hipGetLastError();
 }
 
