@@ -189,6 +189,11 @@ typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
   int64_t sampled[MEBPTT_K_CLASSES];  /* launches that were bracketed by an event pair   */
   double sampled_ms[MEBPTT_K_CLASSES]; /* sum of the bracketed launches' elapsed times    */
+  /* Forward runs of nine or more consecutive operations are also bracketed as a whole (all but
+   * their first launch): one event pair around many back-to-back launches, so the cost of the
+   * events themselves disappears from the per-launch average. */
+  int64_t forward_run_launches;
+  double forward_run_ms;
 } mebptt_profile;
 /* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
  * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;

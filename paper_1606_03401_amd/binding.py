@@ -48,7 +48,8 @@ K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward")
 
 class mebptt_profile(C.Structure):
     _fields_ = [("launches", C.c_int64 * K_CLASSES), ("sampled", C.c_int64 * K_CLASSES),
-                ("sampled_ms", C.c_double * K_CLASSES)]
+                ("sampled_ms", C.c_double * K_CLASSES), ("forward_run_launches", C.c_int64),
+                ("forward_run_ms", C.c_double)]
 
 
 # name -> (restype, argtypes): every symbol the header declares

@@ -74,11 +74,14 @@ inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 struct Sample {
   int cls;
   hipEvent_t start, stop;
+  int64_t launches;   // kernel launches between the two events
 };
 struct Profiler {
   int every_n = 0;
+  bool in_run = false;   // inside a bracketed forward run: no per-launch brackets
   int64_t launches[MEBPTT_K_CLASSES] = {};
   std::vector<Sample> pending;
+  std::vector<Sample> runs;   // whole forward runs, one event pair around many launches
   std::vector<hipEvent_t> pool;
   hipEvent_t get() {
     if (!pool.empty()) {
@@ -98,9 +101,9 @@ template <class F>
 hipError_t timed(int cls, hipStream_t st, F&& launch) {
   Profiler& p = g_prof;
   if (p.every_n <= 0) return launch();
-  const bool sample = (p.launches[cls]++ % p.every_n) == 0 && p.pending.size() < 200000;
+  const bool sample = (p.launches[cls]++ % p.every_n) == 0 && p.pending.size() < 200000 && !p.in_run;
   if (!sample) return launch();
-  Sample s{cls, p.get(), p.get()};
+  Sample s{cls, p.get(), p.get(), 1};
   if (!s.start || !s.stop) return hipErrorOutOfMemory;
   hipError_t e = hipEventRecord(s.start, st);
   if (e != hipSuccess) return e;
@@ -168,6 +171,20 @@ int mebptt_profile_collect(mebptt_profile* out) {
     p.launches[c] = 0;
   }
   int rc = MEBPTT_OK;
+  for (Sample& s : p.runs) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(s.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, s.start, s.stop);
+    if (e != hipSuccess) {
+      rc = set_error(MEBPTT_EHIP, "event timing failed: %s", hipGetErrorString(e));
+    } else {
+      out->forward_run_launches += s.launches;
+      out->forward_run_ms += ms;
+    }
+    p.pool.push_back(s.start);
+    p.pool.push_back(s.stop);
+  }
+  p.runs.clear();
   for (Sample& s : p.pending) {
     float ms = 0.0f;
     hipError_t e = hipEventSynchronize(s.stop);
@@ -340,7 +357,18 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     if (op.op == MEBPTT_OP_FWD_RUN) {
       if (op.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
       const float* cur = loc(op.src);
+      // Measurement hook: one event pair around the back-to-back launches of a long run (all but
+      // its first step, which may share a launch with a backward step).
+      const bool bracket = g_prof.every_n > 0 && op.count >= 9 && g_prof.runs.size() < 100000;
+      Sample run_sample{MEBPTT_K_FORWARD, nullptr, nullptr, op.count - 1};
       for (int j = 1; j <= op.count; ++j) {
+        if (bracket && j == 2) {
+          run_sample.start = g_prof.get();
+          run_sample.stop = g_prof.get();
+          if (!run_sample.start || !run_sample.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+          HIP_TRY(hipEventRecord(run_sample.start, st));
+          g_prof.in_run = true;
+        }
         const int step = op.step + j - 1;
         float* dst = (j == op.count) ? loc(op.dst)
                                      : (j == op.count - 1 ? loc(op.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
@@ -364,6 +392,11 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
         HIP_TRY(timed(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_s, cur, dst, gates, st); }));
         cur = dst;
         ++fwd;
+      }
+      if (bracket) {
+        g_prof.in_run = false;
+        HIP_TRY(hipEventRecord(run_sample.stop, st));
+        g_prof.runs.push_back(run_sample);
       }
     } else if (op.op == MEBPTT_OP_BWD) {
       if (have_pending) {
