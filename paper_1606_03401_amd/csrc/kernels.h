@@ -13,7 +13,8 @@
 //                        columns in the permuted order 4u + gate; chunk slot = (step-1) % CH.
 //   dGT [G4][KC]         the same values transposed, KC = CH*B rounded up to 32, column
 //                        slot*B + b: operand of the weight-gradient GEMM.
-//   aT  [NX+HP][KC]      rows [0,NX): x_s transposed; rows [NX,NX+HP): h_{s-1} transposed.
+//   aT  [NA][KC]         NA = NX+HP+16.  Rows [0,NX): x_s transposed; rows [NX,NX+HP): h_{s-1}
+//                        transposed; row NX+HP: ones (its dW column is db); the rest zero.
 // OpT is float (gemm_dtype 0) or bf16 (gemm_dtype 1); accumulation is always fp32.
 #pragma once
 
@@ -26,7 +27,7 @@ namespace mebptt {
 
 struct Dims {
   int B, I, H;
-  int HP, KX, KH, KP, NX, BP, G4;
+  int HP, KX, KH, KP, NX, BP, G4, NA;
   int CH, KC;   // steps per weight-gradient chunk, padded K of that GEMM
   int dtype;    // 0 fp32, 1 bf16
   size_t op_bytes() const { return dtype ? 2 : 4; }
@@ -35,12 +36,6 @@ struct Dims {
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 Dims make_dims(int B, int I, int H, int dtype);
-
-// One unit = (h, c): two consecutive [B,H] fp32 planes.
-struct UnitPtr {
-  float* p;
-  float* plane(const Dims& d, int k) const { return p + (size_t)k * d.B * d.H; }
-};
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_prep_weights(const Dims& d, const float* W_ih, const float* W_hh, const float* b, void* Wp,
@@ -86,15 +81,16 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,
                              int ld_out, hipStream_t st);
 
-// x of `nslots` consecutive steps -> rows [0,NX) of aT.
+// x of `nslots` consecutive steps -> rows [0,NX) of aT, and ones into row NX+HP for the same columns.
 hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, void* aT, hipStream_t st);
 
-// Tile-ordered running sum of dW (+)= dGT * aT^T over K = nslots*B columns; db (+)= row sums of
-// dGT.  launch_wgrad_finish writes the caller's row-major dW_ih / dW_hh from it.
+// Tile-ordered running sum of [dW | db] (+)= dGT * aT^T over K = nslots*B columns.
+// launch_wgrad_finish writes the caller's row-major dW_ih, dW_hh and db from it.
 size_t wgrad_accumulator_bytes(const Dims& d);
 hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dWacc,
-                        float* db, hipStream_t st);
-hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, hipStream_t st);
+                        hipStream_t st);
+hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, float* db,
+                               hipStream_t st);
 
 hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, hipStream_t st);
 

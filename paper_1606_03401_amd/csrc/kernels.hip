@@ -35,6 +35,7 @@ Dims make_dims(int B, int I, int H, int dtype) {
   d.NX = round_up(I, 16);
   d.BP = round_up(B, 16);
   d.G4 = 4 * d.HP;
+  d.NA = d.NX + d.HP + 16;
   // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 8 MiB (the
   // staging is t-independent workspace), at least 2 and at most 32.
   const size_t step_bytes = (size_t)d.BP * d.G4 * (dtype ? 2 : 4);
@@ -698,63 +699,106 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
 
 // ---- data-gradient GEMM: out[row][n] = sum_k dG[row][k] * WT[n][k] ---------------------------
 
-template <class T, int KS, int U>
+// One workgroup = NT column tiles (16 outputs n each) x RT row tiles (16 (step, sequence) rows each);
+// its KS waves split K = 4*HP, every wave covering all NT x RT tiles.  Partial sums meet in LDS;
+// the NT*RT*4 output quarter-tiles are dealt round-robin to the waves for the store.
+template <class T, int NT, int RT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT, int N, const T* __restrict__ dG,
-                                                        int B, int BP, int G4, float* __restrict__ out, int ld_out) {
+                                                        int nrow_tiles, int B, int BP, int G4,
+                                                        float* __restrict__ out, int ld_out) {
   using M = Mma<T>;
-  constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
+  constexpr int VEC = M::VEC, KSTEP = 4 * VEC, NTILE = NT * RT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
+  __shared__ float red[KS * NTILE * 4 * 64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
-  const int n0 = blockIdx.x * 16;
-  const int r0 = blockIdx.y * 16;   // padded row (slot*BP + b); grid.y covers exactly nslots*BP/16 tiles
+  const int ncol_tiles = (N + 15) / 16;
   const int nsteps = G4 / KSTEP;
-  const T* abase = WT + ((size_t)blockIdx.x * nsteps * 64 + lane) * VEC;
-  const T* bbase = dG + ((size_t)blockIdx.y * nsteps * 64 + lane) * VEC;
-  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  const T* abase[NT];
+  const T* bbase[RT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+    abase[i] = WT + ((size_t)min((int)blockIdx.x * NT + i, ncol_tiles - 1) * nsteps * 64 + lane) * VEC;
+#pragma unroll
+  for (int j = 0; j < RT; ++j)
+    bbase[j] = dG + ((size_t)min((int)blockIdx.y * RT + j, nrow_tiles - 1) * nsteps * 64 + lane) * VEC;
+  f32x4 acc[NT][RT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int j = 0; j < RT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-    typename M::Frag af[U], bf[U];
+    typename M::Frag af[U][NT], bf[U][RT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int s = min(s0 + u * KS, nsteps - 1);
-      af[u] = M::load(abase + (size_t)s * 64 * VEC);
-      bf[u] = M::load(bbase + (size_t)s * 64 * VEC);
+      const size_t off = (size_t)min(s0 + u * KS, nsteps - 1) * 64 * VEC;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) af[u][i] = M::load(abase[i] + off);
+#pragma unroll
+      for (int j = 0; j < RT; ++j) bf[u][j] = M::load(bbase[j] + off);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (s0 + u * KS < nsteps) acc = M::mma(af[u], bf[u], acc);
-  }
-  __shared__ float red[KS * 4 * 64];
+      if (s0 + u * KS < nsteps) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+          for (int j = 0; j < RT; ++j) acc[i][j] = M::mma(af[u][i], bf[u][j], acc[i][j]);
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int j = 0; j < RT; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[((wave * NTILE + i * RT + j) * 4 + r) * 64 + lane] = acc[i][j][r];
   __syncthreads();
-  if (wave >= 4) return;
-  const int r = wave;
-  float v = 0.0f;
-  for (int q = 0; q < KS; ++q) v += red[(q * 4 + r) * 64 + lane];
-  const int row = r0 + lrow;
-  const int slot = row / BP, b = row % BP;
-  const int n = n0 + 4 * lq + r;
-  if (b >= B || n >= N) return;
-  out[((size_t)slot * B + b) * ld_out + n] = v;
+#pragma unroll
+  for (int q = 0; q < PPW; ++q) {
+    const int piece = wave + q * KS;
+    if (piece >= NPIECE) break;
+    float v = 0.0f;
+    for (int w = 0; w < KS; ++w) v += red[(w * NPIECE + piece) * 64 + lane];   // fixed order
+    const int tile = piece >> 2, r = piece & 3;
+    const int tn = tile / RT, tr = tile % RT;
+    const int row = ((int)blockIdx.y * RT + tr) * 16 + lrow;   // padded row: slot * BP + b
+    const int n = ((int)blockIdx.x * NT + tn) * 16 + 4 * lq + r;
+    const int slot = row / BP, b = row % BP;
+    if (row >= nrow_tiles * 16 || b >= B || n >= N) continue;
+    out[((size_t)slot * B + b) * ld_out + n] = v;
+  }
+}
+
+template <class T>
+static void launch_dgrad_t(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
+                           hipStream_t st) {
+  const int ncol_tiles = round_up(N, 16) / 16, nrow_tiles = nslots * d.BP / 16;
+  if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 1) / 2) >= TARGET_WGS) {
+    dim3 grid((ncol_tiles + 1) / 2, (nrow_tiles + 1) / 2);
+    dgrad_kernel<T, 2, 2, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
+                                                            ld_out);
+  } else {
+    dim3 grid(ncol_tiles, nrow_tiles);
+    dgrad_kernel<T, 1, 1, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
+                                                            ld_out);
+  }
 }
 
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
                              hipStream_t st) {
-  dim3 grid(round_up(N, 16) / 16, nslots * d.BP / 16);
   if (d.dtype)
-    dgrad_kernel<__bf16, 8, 4><<<grid, dim3(512), 0, st>>>((const __bf16*)WT, N, (const __bf16*)dG, d.B, d.BP, d.G4, out,
-                                                           ld_out);
+    launch_dgrad_t<__bf16>(d, WT, N, dG, nslots, out, ld_out, st);
   else
-    dgrad_kernel<float, 8, 4><<<grid, dim3(512), 0, st>>>((const float*)WT, N, (const float*)dG, d.B, d.BP, d.G4, out,
-                                                          ld_out);
+    launch_dgrad_t<float>(d, WT, N, dG, nslots, out, ld_out, st);
   return hipGetLastError();
 }
 
 // ---- x transposed into the weight-gradient operand ----------------------------------------------
 
 template <class T>
-__global__ void transpose_x_kernel(const float* __restrict__ x, int rows, int I, int KC, T* __restrict__ aT) {
-  // x: [rows][I] (rows = nslots*B consecutive (step, b) pairs) -> aT[i][row]
+__global__ void transpose_x_kernel(const float* __restrict__ x, int rows, int I, int KC, int ones_row,
+                                   T* __restrict__ aT) {
+  // x: [rows][I] (rows = nslots*B consecutive (step, b) pairs) -> aT[i][row]; the first column of
+  // blocks also sets aT[ones_row][row] = 1, the operand row that turns db into a column of dW.
   __shared__ float tile[32][33];
   const int r0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
@@ -767,15 +811,16 @@ __global__ void transpose_x_kernel(const float* __restrict__ x, int rows, int I,
     int i = i0 + ii, r = r0 + tx;
     if (i < I && r < rows) aT[ft_offset<T>(i, r, KC / (4 * Mma<T>::VEC))] = (T)tile[tx][ii];
   }
+  if (blockIdx.y == 0 && ty == 0 && r0 + tx < rows) aT[ft_offset<T>(ones_row, r0 + tx, KC / (4 * Mma<T>::VEC))] = (T)1.0f;
 }
 
 hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, void* aT, hipStream_t st) {
   const int rows = nslots * d.B;
   dim3 grid((rows + 31) / 32, (d.I + 31) / 32), block(256);
   if (d.dtype)
-    transpose_x_kernel<__bf16><<<grid, block, 0, st>>>(x_first, rows, d.I, d.KC, (__bf16*)aT);
+    transpose_x_kernel<__bf16><<<grid, block, 0, st>>>(x_first, rows, d.I, d.KC, d.NX + d.HP, (__bf16*)aT);
   else
-    transpose_x_kernel<float><<<grid, block, 0, st>>>(x_first, rows, d.I, d.KC, (float*)aT);
+    transpose_x_kernel<float><<<grid, block, 0, st>>>(x_first, rows, d.I, d.KC, d.NX + d.HP, (float*)aT);
   return hipGetLastError();
 }
 
@@ -880,9 +925,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
 }
 
 // dW_ih[row][n] / dW_hh[row][n] <- the tile-ordered accumulator (see wgrad_kernel's epilogue).
-__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int NX, int I, int H,
-                                    float* __restrict__ dW_ih, float* __restrict__ dW_hh) {
-  const size_t total = (size_t)4 * H * (I + H);
+// The accumulator's column NX + HP (operand row of ones) holds db.
+__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int NX, int HP, int I, int H,
+                                    float* __restrict__ dW_ih, float* __restrict__ dW_hh, float* __restrict__ db) {
+  const size_t total = (size_t)4 * H * (I + H + 1);
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
     int row, n, np;
@@ -892,12 +938,16 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int
       n = (int)(idx % I);
       np = n;
       dst = dW_ih + idx;
-    } else {
+    } else if (idx < (size_t)4 * H * (I + H)) {
       const size_t j = idx - (size_t)4 * H * I;
       row = (int)(j / H);
       n = (int)(j % H);
       np = NX + n;
       dst = dW_hh + j;
+    } else {
+      row = (int)(idx - (size_t)4 * H * (I + H));
+      np = NX + HP;
+      dst = db + row;
     }
     const int gate = row / H, u = row % H;
     const int mp = 4 * u + gate;                       // permuted row
@@ -911,64 +961,46 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int
   }
 }
 
-template <class T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dGT, int K, int KC, int G4, int H,
-                                                        int accumulate, float* __restrict__ db) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + wave;
-  if (m >= G4) return;
-  const int u = m >> 2, gate = m & 3;
-  if (u >= H) return;
-  float s = 0.0f;
-  for (int k = lane; k < K; k += 64) s += (float)dGT[ft_offset<T>(m, k, KC / (4 * Mma<T>::VEC))];
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-  if (lane == 0) {
-    float* dst = db + (size_t)gate * H + u;
-    *dst = accumulate ? (*dst + s) : s;
-  }
-}
-
 // Wave tile of the weight-gradient GEMM: 4 x 4 MFMA tiles when that still gives the chip enough
 // workgroups, else 2 x 2.
 static int wgrad_wave_tile(const Dims& d) {
-  const int MT = d.G4 / 16, NT = (d.NX + d.HP) / 16;
+  const int MT = d.G4 / 16, NT = d.NA / 16;
   return ((MT + 7) / 8) * ((NT + 7) / 8) >= 200 ? 4 : 2;
 }
 
 size_t wgrad_accumulator_bytes(const Dims& d) {
   const int WT = wgrad_wave_tile(d);
-  const size_t gx = (d.G4 / 16 + 2 * WT - 1) / (2 * WT), gy = ((d.NX + d.HP) / 16 + 2 * WT - 1) / (2 * WT);
+  const size_t gx = (d.G4 / 16 + 2 * WT - 1) / (2 * WT), gy = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
   return gx * gy * 4 * WT * WT * 64 * sizeof(float4);
 }
 
 template <class T>
-static void launch_wgrad_t(const Dims& d, const void* dGT, const void* aT, int K, int nvalid, int accumulate,
-                           float* dWacc, float* db, hipStream_t st) {
-  const int NTOT = d.NX + d.HP, WT = wgrad_wave_tile(d);
+static void launch_wgrad_t(const Dims& d, const void* dGT, const void* aT, int K, int accumulate, float* dWacc,
+                           hipStream_t st) {
+  const int NTOT = d.NA, WT = wgrad_wave_tile(d);
   dim3 grid((d.G4 / 16 + 2 * WT - 1) / (2 * WT), (NTOT / 16 + 2 * WT - 1) / (2 * WT)), block(256);
   if (WT == 4)
     wgrad_kernel<T, 4><<<grid, block, 0, st>>>((const T*)dGT, (const T*)aT, K, d.KC, d.G4, NTOT, accumulate, dWacc);
   else
     wgrad_kernel<T, 2><<<grid, block, 0, st>>>((const T*)dGT, (const T*)aT, K, d.KC, d.G4, NTOT, accumulate, dWacc);
-  bias_grad_kernel<T><<<dim3((d.G4 + 3) / 4), block, 0, st>>>((const T*)dGT, nvalid, d.KC, d.G4, d.H, accumulate, db);
 }
 
 hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslots, int accumulate, float* dWacc,
-                        float* db, hipStream_t st) {
+                        hipStream_t st) {
   const int kstep = d.dtype ? 32 : 16;
   const int K = round_up(nslots * d.B, kstep);   // columns past nslots*B are zero
   if (d.dtype)
-    launch_wgrad_t<__bf16>(d, dGT, aT, K, nslots * d.B, accumulate, dWacc, db, st);
+    launch_wgrad_t<__bf16>(d, dGT, aT, K, accumulate, dWacc, st);
   else
-    launch_wgrad_t<float>(d, dGT, aT, K, nslots * d.B, accumulate, dWacc, db, st);
+    launch_wgrad_t<float>(d, dGT, aT, K, accumulate, dWacc, st);
   return hipGetLastError();
 }
 
-hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, hipStream_t st) {
+hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, float* db,
+                               hipStream_t st) {
   const int WT = wgrad_wave_tile(d);
-  const int grid_y = ((d.NX + d.HP) / 16 + 2 * WT - 1) / (2 * WT);
-  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.I, d.H, dW_ih, dW_hh);
+  const int grid_y = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
+  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.HP, d.I, d.H, dW_ih, dW_hh, db);
   return hipGetLastError();
 }
 

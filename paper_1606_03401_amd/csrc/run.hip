@@ -49,7 +49,7 @@ Workspace layout(const Dims& d) {
   w.dc = take(unit / 2);
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
-  for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)(d.NX + d.HP) * d.KC * op);
+  for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)d.NA * d.KC * op);
   w.total = off;
   return w;
 }
@@ -340,7 +340,7 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
         hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
         if (e != hipSuccess) return e;
         return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1,
-                            reinterpret_cast<float*>(ws + w.dWacc), db, st2);
+                            reinterpret_cast<float*>(ws + w.dWacc), st2);
       }));
       if (dx)
         HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
@@ -441,7 +441,7 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   for (int i = 0; i < 2; ++i)   // join: everything is ordered before whatever follows on `st`
     if (pending[i]) HIP_TRY(hipStreamWaitEvent(st, side->done[i], 0));
   HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {
-    return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, st);
+    return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, db, st);
   }));
 
   if (stats) {
