@@ -63,6 +63,36 @@ inline void first_argmin(const int64_t* a, int a_shift, const int64_t* b_rev, in
   }
 }
 
+// The O(t*m) route the appendix alludes to ("exploiting convexity in t").  If C(., m) is convex on
+// the part already filled and C(., m-1) is convex, then Q(t, m, y) is convex in y (a sum of convex
+// sequences), so a local minimum is the global one and the minimisers form an interval: the
+// leftmost one is found by walking from the previous cell's split, in O(1) steps amortised.
+// Convexity is not assumed: every column's second differences are checked as it is filled, and
+// the first violation sends the rest of the table back to the full scan, so the result is always
+// exactly the triple loop's (same cost, same leftmost split).
+template <class QF>
+inline void convex_first_argmin(QF Q, int lo, int hi, int start, int64_t& best, int& arg) {
+  int y = start < lo ? lo : (start > hi ? hi : start);
+  int64_t q = Q(y);
+  while (y > lo) {   // ties go left
+    int64_t ql = Q(y - 1);
+    if (ql > q) break;
+    --y;
+    q = ql;
+  }
+  while (y < hi) {
+    int64_t qr = Q(y + 1);
+    if (qr >= q) break;
+    ++y;
+    q = qr;
+  }
+  best = q;
+  arg = y;
+}
+
+// Second difference of a column at index i (needs i >= lo + 2).
+inline bool convex_at(const std::vector<int64_t>& c, int i) { return c[i] - 2 * c[i - 1] + c[i - 2] >= 0; }
+
 using Col64 = std::vector<std::vector<int64_t>>;
 using Col32 = std::vector<std::vector<int32_t>>;
 
@@ -84,18 +114,27 @@ void solve_hsm(int t, int m, Tables& T) {
   for (int mm = 0; mm <= m; ++mm) C[mm][0] = 0;
   for (int tt = 1; tt <= t; ++tt) C[1][tt] = (int64_t)tt * (tt + 1) / 2;
   D[1][1] = 1;
+  bool convex = true;   // every column so far (and the current one as far as filled) is convex on [0, .]
   for (int mm = 2; mm <= m; ++mm) {
     int plentiful = std::min(t, mm);
     for (int tt = 1; tt <= plentiful; ++tt) {
       C[mm][tt] = 2 * (int64_t)tt - 1;
       D[mm][tt] = 1;
     }
+    const int64_t* cm = C[mm].data();
+    const int64_t* cm1 = C[mm - 1].data();
     for (int tt = mm + 1; tt <= t; ++tt) {
       int64_t best;
       int arg;
-      first_argmin(C[mm].data(), 0, C[mm - 1].data() + tt, 1, tt - 1, best, arg);
+      if (convex && tt > mm + 1) {
+        auto Q = [&](int y) { return (int64_t)y + cm[y] + cm1[tt - y]; };
+        convex_first_argmin(Q, 1, tt - 1, D[mm][tt - 1], best, arg);
+      } else {
+        first_argmin(cm, 0, cm1 + tt, 1, tt - 1, best, arg);
+      }
       C[mm][tt] = best;
       D[mm][tt] = arg;
+      if (convex && tt >= 2 && !convex_at(C[mm], tt)) convex = false;
     }
   }
   to_row_major(C, t, m, T.C);
@@ -108,13 +147,23 @@ void solve_ism(int t, int m, Tables& T) {
   alloc_cols(C, t, m, INF);
   alloc_cols(D, t, m);
   for (int mm = 0; mm <= m; ++mm) C[mm][0] = 0;
+  bool convex = true;
   for (int mm = 1; mm <= m; ++mm) {
+    const int64_t* cm = C[mm].data();
+    const int64_t* cm1 = C[mm - 1].data();
     for (int tt = 1; tt <= t; ++tt) {
       int64_t best;
       int arg;
-      first_argmin(C[mm].data(), 1, C[mm - 1].data() + tt, 1, tt, best, arg);
+      // column 0 is infinite for t > 0, so the convexity argument starts with column 2
+      if (convex && mm >= 2 && tt >= 2) {
+        auto Q = [&](int y) { return (int64_t)y + cm[y - 1] + cm1[tt - y]; };
+        convex_first_argmin(Q, 1, tt, D[mm][tt - 1], best, arg);
+      } else {
+        first_argmin(cm, 1, cm1 + tt, 1, tt, best, arg);
+      }
       C[mm][tt] = best;
       D[mm][tt] = arg;
+      if (convex && tt >= 2 && !convex_at(C[mm], tt)) convex = false;
     }
   }
   to_row_major(C, t, m, T.C);

@@ -165,6 +165,16 @@ def test_full_size_tables_config4_and_config5():
         assert p.peak <= m
 
 
+@pytest.mark.parametrize("kind", [mb.HSM, mb.ISM])
+def test_long_sequence_tables_match_the_plain_recurrence(kind):
+    """The library fills HSM/ISM tables by walking from the previous split (convexity, checked as
+    it goes); the oracle scans every y.  They must agree cell for cell, ties included."""
+    t, m = 3000, 64
+    plan = mb.mebptt_plan(t, m, kind)
+    tabs = dp.hsm_tables(t, m) if kind == mb.HSM else dp.ism_tables(t, m)
+    _assert_tables_equal(plan, kind, tabs)
+
+
 def test_constant_memory_is_run_length_encoded():
     plan = mb.mebptt_plan(2000, 1, mb.HSM)
     assert plan.forward_ops == 2000 * 2001 // 2
