@@ -120,6 +120,34 @@ def cpu_baseline(w, inp, budget_s=20.0):
             "sample": f"first {n} of {w.t} steps of {w.name} (float64 store-everything BPTT, numpy), {dt:.1f} s"}
 
 
+def fig2b(args) -> int:
+    """Section 4 / Fig. 2b: time per time step of one gradient step as a function of the sequence
+    length, for budgets of 10, 50, 100, 500, 1000 hidden states, beside the cost model's forward
+    operations per step (Fig. 2a).  Synthetic inputs; the paper states no hardware or precision."""
+    import torch
+    from paper_1606_03401_amd import workloads as wl
+    from paper_1606_03401_amd.session import Session
+    rows = []
+    for t in (100, 200, 400, 600, 800, 1000):
+        base = wl.Workload("fig2b", B=64, I=256, H=256, t=t, kind=wl.KIND_HSM, m=t, gemm_dtype=wl.GEMM_BF16,
+                           loss=wl.LOSS_EXTERNAL_DY, seed=t)
+        inp = wl.make_inputs(base)
+        line = {"t": t}
+        for m in (10, 50, 100, 500, 1000):
+            s = Session(base, inp, kind=wl.KIND_HSM, m=min(m, t), want_dx=True, want_y=False)
+            ms = time_runs(s, args.steps, args.warmup) * 1e3
+            line[m] = (ms / t * 1e3, s.plan.forward_ops / t)
+            del s
+        sa = Session(base, inp, kind=wl.KIND_ISM, m=t, want_dx=True, want_y=False)
+        line["store_all"] = (time_runs(sa, args.steps, args.warmup) * 1e3 / t * 1e3, 1.0)
+        del sa
+        rows.append(line)
+        log(f"[fig2b] t={t}: " + "  ".join(
+            f"m={k}: {v[0]:.1f} us/step ({v[1]:.2f} fwd/step)" for k, v in line.items() if k != "t"))
+    print(json.dumps({"experiment": "fig2b", "unit": "us per time step (forward ops per step)", "rows": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +157,9 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="also time the budget sweep m = t .. 5%% of t (stderr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time stream launches only")
+    ap.add_argument("--fig2b", action="store_true",
+                    help="the shape of the paper's timing experiment: LSTM 256->256, batch 64, ms per time step "
+                         "vs sequence length at budgets of 10/50/100/500/1000 hidden states (table on stderr)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: the path is single-device by design (see DESIGN.md); --gpus must be 1")
@@ -142,6 +173,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         log("no GPU visible: the HIP path cannot run")
         return 1
+    if args.fig2b:
+        return fig2b(args)
     w = wl.CONFIGS[args.workload]
     log(f"[bench] {mb.mebptt_version()} workload {w}")
     # A plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick
