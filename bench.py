@@ -162,7 +162,7 @@ def main() -> int:
                          "vs sequence length at budgets of 10/50/100/500/1000 hidden states (table on stderr)")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py measures one GPU: the path is single-device by design (see DESIGN.md); --gpus must be 1")
+        log("bench.py measures one GPU: this build runs the path on a single device; --gpus must be 1")
         return 2
 
     import torch

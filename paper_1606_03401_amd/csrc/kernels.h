@@ -4,17 +4,20 @@
 // 16-byte aligned and in bounds; padding is zero):
 //   HP = H rounded up to 16,  KX = I rounded up to 32,  KH = H rounded up to 32,  KP = KX + KH,
 //   NX = I rounded up to 16,  BP = B rounded up to 16,  G4 = 4 * HP.
-//   Wp  [HP/4][16][KP]   forward operand: row 4*u_local + gate of group u/4 is row gate*H + u of
-//                        [W_ih | W_hh]; columns [0,KX) hold W_ih, [KX,KP) hold W_hh.
-//   bp  [G4] fp32        bias in the same permuted order: bp[4u + gate] = b[gate*H + u].
+// The logical matrices below are all stored fragment-tiled (16-row tiles, one contiguous 1 KiB
+// block per tile and macro step; the exact index map is next to ft_offset in kernels.hip):
+//   Wp  [G4][KP]         forward operand: row 4*u + gate is row gate*H + u of [W_ih | W_hh];
+//                        columns [0,KX) hold W_ih, [KX,KP) hold W_hh.
 //   WTh [HP][G4]         WTh[n][4u+gate] = W_hh[gate*H+u][n]  (operand of dh_{s-1} = dG_s W_hh)
 //   WTx [NX][G4]         WTx[n][4u+gate] = W_ih[gate*H+u][n]  (operand of dx_s   = dG_s W_ih)
-//   dG  [CH][BP][G4]     gate pre-activation gradients of one chunk of CH consecutive steps,
-//                        columns in the permuted order 4u + gate; chunk slot = (step-1) % CH.
+//   dG  [CH*BP][G4]      gate pre-activation gradients of one chunk of CH consecutive steps, row
+//                        slot*BP + b, columns in the permuted order 4u + gate; slot = (step-1) % CH.
 //   dGT [G4][KC]         the same values transposed, KC = CH*B rounded up to 32, column
 //                        slot*B + b: operand of the weight-gradient GEMM.
 //   aT  [NA][KC]         NA = NX+HP+16.  Rows [0,NX): x_s transposed; rows [NX,NX+HP): h_{s-1}
 //                        transposed; row NX+HP: ones (its dW column is db); the rest zero.
+// Plain arrays:
+//   bp  [G4] fp32        bias in the permuted order: bp[4u + gate] = b[gate*H + u].
 // OpT is float (gemm_dtype 0) or bf16 (gemm_dtype 1); accumulation is always fp32.
 #pragma once
 
@@ -50,13 +53,13 @@ hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const 
 
 struct BackwardArgs {
   const void* WTh;
-  const void* dG_next;    // [BP][G4] of step s+1, or NULL for s = t
+  const void* dG_next;    // dG rows of step s+1 (BP rows of the chunk buffer), or NULL for s = t
   const float* state;     // unit (h_s, c_s); the gates follow in the next two units
   const float* prev;      // unit (h_{s-1}, c_{s-1})
   const float* dy_s;      // [B,H] or NULL
   int dy_is_h;            // built-in loss: the injected gradient is h_s itself
   float* dc;              // [B,H] running gradient w.r.t. the cell state, updated in place
-  void* dG_cur;           // [BP][G4] of step s (written)
+  void* dG_cur;           // dG rows of step s (written)
   void* dGT;              // chunk-transposed copy (written at column col0 + b)
   void* aT;               // h_{s-1} transposed goes to rows [NX, NX+HP) at column col0 + b
   int col0;               // slot * B
@@ -75,9 +78,8 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
                                         const float* x_s, const float* src_unit, float* dst_unit, float* gates_units,
                                         hipStream_t st);
 
-// out[b][n] = sum_k dG[b][k] * WT[n][k] for b < rows(valid), n < N; ld_out = row stride of out.
-// `rows_per_step`/`BP` describe the padded row layout of dG: logical row r = step_slot*B + b
-// lives at dG row step_slot*BP + b.
+// out[slot*B + b][n] = sum_k dG[slot*BP + b][k] * WT[n][k] for slot < nslots, b < B, n < N;
+// ld_out = row stride of out.  Used for dx (WT = WTx, N = I) and for dh_0 (WT = WTh, N = H).
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,
                              int ld_out, hipStream_t st);
 

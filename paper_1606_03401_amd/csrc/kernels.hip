@@ -11,10 +11,10 @@
 // The weights always play A (rows = gate rows or hidden units) and the batch plays B (columns),
 // so a lane ends up with FOUR CONSECUTIVE ROWS of one batch column.  The forward operand is
 // row-permuted so that those four rows are the gates i, f, g, o of one hidden unit: the LSTM
-// pointwise step then runs entirely in registers (K1 + K2 of the hot path fused).  In the
-// backward step the four rows are four consecutive hidden units of dh, and the pointwise
-// backward (K3 + K4) again runs in registers on the GEMM result (K5's dh half fused with K4 of
-// the next step down).
+// pointwise step then runs on the GEMM result without leaving the workgroup (gate GEMM and
+// pointwise forward fused).  In the backward step the four rows are four consecutive hidden
+// units of dh, and loss-gradient injection and the pointwise backward again run on the GEMM
+// result (the dh = dG W_hh product of step s+1 fused with the pointwise backward of step s).
 #include "kernels.h"
 
 namespace mebptt {
