@@ -14,7 +14,7 @@ On top of the machine:
     admissible y -- and, for MSM, both kinds of push -- at every node), run each one on the
     machine, and return the cheapest cost found.  No cost table is consulted.
 
-Readings (also in the design notes):
+Readings:
   * HSM/MSM: the start state of the sequence (h_0) sits on the stack and uses one unit of the
     budget -- only then do C(t,1) = t(t+1)/2 and "C(t,m) = 2t-1 iff m >= t" hold.
   * ISM: h_0 is a given input outside the budget; all m slots hold internal states -- only then

@@ -20,7 +20,7 @@ sequence of length t with m memory slots; D(t, m) = position of the first state 
         Q2(t,m,y) = y + C(y-1, m) + C(t-y, m - (beta if y == 1 else alpha)),  1 <= y <= t
         C = min(C1, C2),  H = 1 (hidden) if C1 <= C2 else 2 (internal).
 
-Readings where the text is silent or inconsistent (every one is also listed in the design notes):
+Readings where the text is silent or inconsistent:
   * argmin ties go to the smallest y, which is what Algorithm 1's upward scan with a strict
     "<" comparison produces; H prefers the hidden branch on a tie (argmin over i = 1, 2 in order).
   * the appendix prints C(t,1) = t(t+2)/2 once; the body and Algorithm 1 say t(t+1)/2, which is
