@@ -79,7 +79,13 @@ struct Mma<float> {
   }
 };
 
-__device__ inline float sigmoidf_(float z) { return 1.0f / (1.0f + expf(-z)); }
+// Pointwise activations on the hardware exp2 / reciprocal units (a few ulp; the absolute error of
+// tanh stays below 1e-7, far inside the fp32 gradient tolerance).
+__device__ inline float sigmoidf_(float z) { return __frcp_rn(1.0f + __expf(-z)); }
+__device__ inline float tanhf_(float z) {
+  const float e = __expf(-2.0f * fabsf(z));            // in (0, 1]: no overflow
+  return copysignf((1.0f - e) * __frcp_rn(1.0f + e), z);
+}
 
 // ---- small utility kernels -------------------------------------------------------------------
 
@@ -357,10 +363,10 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     const size_t e = eidx[q];
     const float gi = sigmoidf_(G[0] + bias[q].x);
     const float gf = sigmoidf_(G[1] + bias[q].y);
-    const float gg = tanhf(G[2] + bias[q].z);
+    const float gg = tanhf_(G[2] + bias[q].z);
     const float go = sigmoidf_(G[3] + bias[q].w);
     const float c = gf * c_prev[q] + gi * gg;
-    const float h = go * tanhf(c);
+    const float h = go * tanhf_(c);
     p.dst_h[e] = h;
     p.dst_c[e] = c;
     if (p.g_i) {
@@ -493,7 +499,7 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
     const int n = en[q], b = eb[q];
     dh += p.dy_is_h ? h[q] : dy[q];
     if (p.y_out_s) p.y_out_s[e] = h[q];
-    const float tc = tanhf(c_s[q]);
+    const float tc = tanhf_(c_s[q]);
     const float d_o = dh * tc;
     const float dct = dc_in[q] + dh * go[q] * (1.0f - tc * tc);
     const float dGi = dct * gg[q] * gi[q] * (1.0f - gi[q]);
