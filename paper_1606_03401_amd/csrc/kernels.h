@@ -2,7 +2,8 @@
 //
 // Shapes and padded operand layouts (all chosen so that every vector load of a GEMM operand is
 // 16-byte aligned and in bounds; padding is zero):
-//   HP = H rounded up to 16,  KX = I rounded up to 32,  KH = H rounded up to 32,  KP = KX + KH,
+//   HP = H rounded up to 16 (32 for bf16 operands),  KX = I rounded up to 32,  KH = H rounded up to 32,
+//   KP = KX + KH,
 //   NX = I rounded up to 16,  BP = B rounded up to 16,  G4 = 4 * HP.
 // The logical matrices below are all stored fragment-tiled (16-row tiles, one contiguous 1 KiB
 // block per tile and macro step; the exact index map is next to ft_offset in kernels.hip):
@@ -18,6 +19,15 @@
 //                        transposed; row NX+HP: ones (its dW column is db); the rest zero.
 // Plain arrays:
 //   bp  [G4] fp32        bias in the permuted order: bp[4u + gate] = b[gate*H + u].
+//
+// State units.  A unit (the granule of the slot pool) holds a hidden state (h, c) or a pair of gate
+// planes; it is `unit` floats long (a multiple of 64).  Gate planes and c are plain [B][H] fp32.
+// The h plane comes first in its unit and is `hplane` floats long:
+//   fp32 operands: plain [B][H] fp32.
+//   bf16 operands: the SAME 4 bytes per element, split into two fragment-tiled 16-bit planes of
+//     the logical matrix [BP][KH]: `hi` = the value rounded to bf16 (half-up), ready to be fetched
+//     as a GEMM operand in 1 KiB blocks, then `lo` = the low 16 bits of the fp32 pattern.  The fp32
+//     value is recovered exactly as ((hi - (lo >> 15)) << 16) | lo.
 // OpT is float (gemm_dtype 0) or bf16 (gemm_dtype 1); accumulation is always fp32.
 #pragma once
 
@@ -33,6 +43,7 @@ struct Dims {
   int HP, KX, KH, KP, NX, BP, G4, NA;
   int CH, KC;   // steps per weight-gradient chunk, padded K of that GEMM
   int dtype;    // 0 fp32, 1 bf16
+  size_t hplane, unit;   // floats: the h part of a hidden-state unit, a whole unit
   size_t op_bytes() const { return dtype ? 2 : 4; }
 };
 

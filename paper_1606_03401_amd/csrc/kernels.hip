@@ -28,7 +28,7 @@ Dims make_dims(int B, int I, int H, int dtype) {
   d.I = I;
   d.H = H;
   d.dtype = dtype;
-  d.HP = round_up(H, 16);
+  d.HP = round_up(H, dtype ? 32 : 16);   // bf16: HP == KH, so every column of a split h plane belongs to a tile
   d.KX = round_up(I, 32);
   d.KH = round_up(H, 32);
   d.KP = d.KX + d.KH;
@@ -41,6 +41,8 @@ Dims make_dims(int B, int I, int H, int dtype) {
   const size_t step_bytes = (size_t)d.BP * d.G4 * (dtype ? 2 : 4);
   size_t ch = ((size_t)8 << 20) / step_bytes;
   d.CH = ch < 2 ? 2 : (ch > 32 ? 32 : (int)ch);
+  d.hplane = dtype ? (size_t)d.BP * d.KH : (size_t)B * H;
+  d.unit = (d.hplane + (size_t)B * H + 63) / 64 * 64;
   d.KC = round_up(d.CH * B, 32);
   return d;
 }
@@ -86,6 +88,48 @@ __device__ inline float tanhf_(float z) {
   const float e = __expf(-2.0f * fabsf(z));            // in (0, 1]: no overflow
   return copysignf((1.0f - e) * __frcp_rn(1.0f + e), z);
 }
+
+// ---- the h plane of a hidden-state unit ----------------------------------------------------------
+// (layout described in kernels.h).  HPlane<T>::store/load hide whether h is a plain fp32 plane or
+// the split, fragment-tiled pair of 16-bit planes.
+template <class T>
+struct HPlane;
+
+template <>
+struct HPlane<float> {
+  static constexpr bool SPLIT = false;
+  __device__ static void store(float* plane, int b, int u, float v, int, int H, size_t) { plane[(size_t)b * H + u] = v; }
+  __device__ static float load(const float* plane, int b, int u, int, int H, size_t) { return plane[(size_t)b * H + u]; }
+  __device__ static float as_operand(const float* plane, int b, int u, int, int H, size_t) {
+    return plane[(size_t)b * H + u];
+  }
+};
+
+template <class T>
+__device__ inline size_t ft_offset(int row, int k, int nsteps);
+
+template <>
+struct HPlane<__bf16> {
+  static constexpr bool SPLIT = true;
+  // nsh = KH / 32 macro steps per batch tile; half = BP * KH elements per 16-bit plane
+  __device__ static void store(float* plane, int b, int u, float v, int nsh, int, size_t half) {
+    unsigned short* hi = reinterpret_cast<unsigned short*>(plane);
+    const unsigned bits = __float_as_uint(v);
+    const size_t o = ft_offset<__bf16>(b, u, nsh);
+    hi[o] = (unsigned short)((bits + 0x8000u) >> 16);
+    hi[half + o] = (unsigned short)(bits & 0xffffu);
+  }
+  __device__ static float load(const float* plane, int b, int u, int nsh, int, size_t half) {
+    const unsigned short* hi = reinterpret_cast<const unsigned short*>(plane);
+    const size_t o = ft_offset<__bf16>(b, u, nsh);
+    const unsigned lo = hi[half + o];
+    return __uint_as_float((((unsigned)hi[o] - (lo >> 15)) << 16) | lo);
+  }
+  __device__ static __bf16 as_operand(const float* plane, int b, int u, int nsh, int, size_t) {
+    const __bf16* hi = reinterpret_cast<const __bf16*>(plane);
+    return hi[ft_offset<__bf16>(b, u, nsh)];
+  }
+};
 
 // ---- small utility kernels -------------------------------------------------------------------
 
@@ -185,20 +229,28 @@ hipError_t launch_prep_weights(const Dims& d, const float* W_ih, const float* W_
   return hipGetLastError();
 }
 
-__global__ void init_state_kernel(size_t n, const float* __restrict__ h0, const float* __restrict__ c0,
+template <class T>
+__global__ void init_state_kernel(Dims d, const float* __restrict__ h0, const float* __restrict__ c0,
                                   float* __restrict__ dst) {
-  size_t stride = (size_t)gridDim.x * blockDim.x;
+  const int W = HPlane<T>::SPLIT ? d.KH : d.H;   // split layout: padding columns are written as zero
+  const size_t n = (size_t)d.B * W;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    dst[i] = h0 ? h0[i] : 0.0f;
-    dst[n + i] = c0 ? c0[i] : 0.0f;
+    const int b = (int)(i / W), u = (int)(i % W);
+    const size_t e = (size_t)b * d.H + u;
+    HPlane<T>::store(dst, b, u, (u < d.H && h0) ? h0[e] : 0.0f, d.KH / 32, d.H, (size_t)d.BP * d.KH);
+    if (u < d.H) dst[d.hplane + e] = c0 ? c0[e] : 0.0f;
   }
 }
 
 hipError_t launch_init_state(const Dims& d, const float* h0, const float* c0, float* dst_unit, hipStream_t st) {
-  size_t n = (size_t)d.B * d.H;
+  size_t n = (size_t)d.B * d.KH;
   size_t blocks = (n + 255) / 256;
   if (blocks > 2048) blocks = 2048;
-  init_state_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(n, h0, c0, dst_unit);
+  if (d.dtype)
+    init_state_kernel<__bf16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(d, h0, c0, dst_unit);
+  else
+    init_state_kernel<float><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(d, h0, c0, dst_unit);
   return hipGetLastError();
 }
 
@@ -221,15 +273,15 @@ struct FwdParams {
   const void* Wp;
   const float* bp;
   const float* x_s;
-  const float* src_h;
+  const float* src_h;   // h plane of the input state (layout: HPlane)
   const float* src_c;
-  float* dst_h;
+  float* dst_h;         // h plane of the output state
   float* dst_c;
   float* g_i;   // NULL: do not keep the gates
   float* g_f;
   float* g_g;
   float* g_o;
-  int B, I, H, HP, KX, KP;
+  int B, I, H, HP, KX, KH, KP, BP;
 };
 
 // Raw (unconverted) activation fragment: VEC fp32 values, zero beyond `limit`.
@@ -274,15 +326,21 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
   const int group0 = bx * NG;
   const int ngroups = p.HP >> 2;
   const int b0 = by * BT * 16;
+  using HP_ = HPlane<T>;
   const bool x_vec = (p.I & 3) == 0, h_vec = (p.H & 3) == 0;
   const int nsteps = p.KP / KSTEP;
+  const int nsx = p.KX / KSTEP, nsh = p.KH / KSTEP;   // macro steps of the x and the h segment
+  const size_t hhalf = (size_t)p.BP * p.KH;           // elements of one 16-bit plane (split layout)
   const float* xrow[BT];
-  const float* hrow[BT];
+  const float* hrow[BT];   // plain layout: row pointer
+  const T* hfrag[BT];      // split layout: this lane's slot in the batch tile's first fragment
 #pragma unroll
   for (int t = 0; t < BT; ++t) {
     const int b_ld = min(b0 + t * 16 + lrow, p.B - 1);
     xrow[t] = p.x_s + (size_t)b_ld * p.I;
     hrow[t] = p.src_h + (size_t)b_ld * p.H;
+    const int btile = min(by * BT + t, p.BP / 16 - 1);
+    hfrag[t] = reinterpret_cast<const T*>(p.src_h) + ((size_t)btile * nsh * 64 + lane) * VEC;
   }
   const T* wbase[NG];   // fragment-tiled: tile (group) stride = nsteps * 64 * VEC
 #pragma unroll
@@ -300,6 +358,7 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
   // behind the K loop instead of following it.  Tile id = g * BT + t.
   bool epi[TPW];
   size_t eidx[TPW];
+  int eb[TPW], eu[TPW];
   float4 bias[TPW];
   float c_prev[TPW];
 #pragma unroll
@@ -310,6 +369,8 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     const int u = (group0 + g) * 4 + lq;
     epi[q] = tile < NTILE && b < p.B && u < p.H;
     eidx[q] = (size_t)b * p.H + u;
+    eb[q] = b;
+    eu[q] = u;
     bias[q] = float4{0.f, 0.f, 0.f, 0.f};
     c_prev[q] = 0.0f;
     if (epi[q]) {
@@ -319,24 +380,32 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
   }
 
   for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-    RawAct<VEC> rb[U][BT];
+    RawAct<VEC> rb[U][BT];          // fp32 activations still to be converted (x; h in the plain layout)
+    typename M::Frag hb[U][BT];     // ready-made h fragments (split layout)
     typename M::Frag af[U][NG];
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
       const int s = min(s0 + uu * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
       const int k = s * KSTEP + VEC * lq;
 #pragma unroll
-      for (int t = 0; t < BT; ++t)
-        rb[uu][t] = (k < p.KX) ? load_raw<VEC>(xrow[t], k, p.I, x_vec) : load_raw<VEC>(hrow[t], k - p.KX, p.H, h_vec);
+      for (int t = 0; t < BT; ++t) {
+        if (s < nsx)
+          rb[uu][t] = load_raw<VEC>(xrow[t], k, p.I, x_vec);
+        else if (HP_::SPLIT)
+          hb[uu][t] = M::load(hfrag[t] + (size_t)(s - nsx) * 64 * VEC);
+        else
+          rb[uu][t] = load_raw<VEC>(hrow[t], k - p.KX, p.H, h_vec);
+      }
 #pragma unroll
       for (int g = 0; g < NG; ++g) af[uu][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
     }
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
-      if (s0 + uu * KS < nsteps) {
+      const int s = s0 + uu * KS;
+      if (s < nsteps) {
 #pragma unroll
         for (int t = 0; t < BT; ++t) {
-          typename M::Frag bf = M::from_f32(rb[uu][t].v);
+          typename M::Frag bf = (HP_::SPLIT && s >= nsx) ? hb[uu][t] : M::from_f32(rb[uu][t].v);
 #pragma unroll
           for (int g = 0; g < NG; ++g) acc[g][t] = M::mma(af[uu][g], bf, acc[g][t]);
         }
@@ -359,7 +428,12 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     for (int w = 0; w < KS; ++w)   // fixed order: results do not depend on scheduling
 #pragma unroll
       for (int r = 0; r < 4; ++r) G[r] += red[((w * NTILE + tile) * 4 + r) * 64 + lane];
-    if (!epi[q]) continue;
+    if (!epi[q]) {
+      // split layout: the padding columns H..KH of a valid row are part of the operand other
+      // launches fetch, so they are (re)written as zero with every state
+      if (HP_::SPLIT && tile < NTILE && eb[q] < p.B && eu[q] < p.KH) HP_::store(p.dst_h, eb[q], eu[q], 0.0f, nsh, p.H, hhalf);
+      continue;
+    }
     const size_t e = eidx[q];
     const float gi = sigmoidf_(G[0] + bias[q].x);
     const float gf = sigmoidf_(G[1] + bias[q].y);
@@ -367,7 +441,7 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     const float go = sigmoidf_(G[3] + bias[q].w);
     const float c = gf * c_prev[q] + gi * gg;
     const float h = go * tanhf_(c);
-    p.dst_h[e] = h;
+    HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
     p.dst_c[e] = c;
     if (p.g_i) {
       p.g_i[e] = gi;
@@ -397,7 +471,7 @@ struct BwdParams {
   void* aT;
   int col0;
   float* y_out_s;
-  int B, H, HP, G4, NX, KC, BP;
+  int B, H, HP, KH, G4, NX, KC, BP;
 };
 
 // One workgroup of 64*KS threads = NT hidden-unit tiles x BT batch tiles (16 x 16 outputs each);
@@ -433,7 +507,7 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
     h[q] = dy[q] = gi[q] = gf[q] = gg[q] = go[q] = c_s[q] = c_prev[q] = dc_in[q] = h_prev[q] = 0.f;
     if (epi[q]) {
       const size_t e = eidx[q];
-      if (p.dy_is_h || p.y_out_s) h[q] = p.h[e];
+      if (p.dy_is_h || p.y_out_s) h[q] = HPlane<T>::load(p.h, b, n, p.KH / 32, p.H, (size_t)p.BP * p.KH);
       if (!p.dy_is_h && p.dy_s) dy[q] = p.dy_s[e];
       gi[q] = p.g_i[e];
       gf[q] = p.g_f[e];
@@ -442,7 +516,7 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
       c_s[q] = p.c[e];
       c_prev[q] = p.c_prev[e];
       dc_in[q] = p.dc[e];
-      h_prev[q] = p.h_prev[e];
+      h_prev[q] = (float)HPlane<T>::as_operand(p.h_prev, b, n, p.KH / 32, p.H, (size_t)p.BP * p.KH);
     }
   }
   if (p.dG_next) {
@@ -606,21 +680,23 @@ static FwdParams make_fwd_params(const Dims& d, const void* Wp, const float* bp,
   p.bp = bp;
   p.x_s = x_s;
   p.src_h = src_unit;
-  p.src_c = src_unit + plane;
+  p.src_c = src_unit + d.hplane;
   p.dst_h = dst_unit;
-  p.dst_c = dst_unit + plane;
-  if (gates_units) {
+  p.dst_c = dst_unit + d.hplane;
+  if (gates_units) {   // two units: (i, f) and (g, o)
     p.g_i = gates_units;
     p.g_f = gates_units + plane;
-    p.g_g = gates_units + 2 * plane;
-    p.g_o = gates_units + 3 * plane;
+    p.g_g = gates_units + d.unit;
+    p.g_o = gates_units + d.unit + plane;
   }
   p.B = d.B;
   p.I = d.I;
   p.H = d.H;
   p.HP = d.HP;
   p.KX = d.KX;
+  p.KH = d.KH;
   p.KP = d.KP;
+  p.BP = d.BP;
   return p;
 }
 
@@ -653,13 +729,13 @@ static BwdParams make_bwd_params(const Dims& d, const BackwardArgs& a) {
   p.WTh = a.WTh;
   p.dG_next = a.dG_next;
   p.h = a.state;
-  p.c = a.state + plane;
-  p.g_i = a.state + 2 * plane;
-  p.g_f = a.state + 3 * plane;
-  p.g_g = a.state + 4 * plane;
-  p.g_o = a.state + 5 * plane;
+  p.c = a.state + d.hplane;
+  p.g_i = a.state + d.unit;
+  p.g_f = a.state + d.unit + plane;
+  p.g_g = a.state + 2 * d.unit;
+  p.g_o = a.state + 2 * d.unit + plane;
   p.h_prev = a.prev;
-  p.c_prev = a.prev + plane;
+  p.c_prev = a.prev + d.hplane;
   p.dy_s = a.dy_s;
   p.dy_is_h = a.dy_is_h;
   p.dc = a.dc;
@@ -671,6 +747,7 @@ static BwdParams make_bwd_params(const Dims& d, const BackwardArgs& a) {
   p.B = d.B;
   p.H = d.H;
   p.HP = d.HP;
+  p.KH = d.KH;
   p.G4 = d.G4;
   p.NX = d.NX;
   p.KC = d.KC;

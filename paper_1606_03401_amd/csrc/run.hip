@@ -33,7 +33,7 @@ struct Workspace {
 Workspace layout(const Dims& d) {
   Workspace w{};
   const size_t op = d.op_bytes();
-  const size_t unit = 2 * (size_t)d.B * d.H * sizeof(float);
+  const size_t unit = d.unit * sizeof(float);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -46,7 +46,7 @@ Workspace layout(const Dims& d) {
   w.WTx = take((size_t)d.NX * d.G4 * op);
   w.state = take(9 * unit);   // T0 | T1 | core A (3 units) | copy of (h0,c0) | core B (3 units)
   w.dWacc = take(wgrad_accumulator_bytes(d));
-  w.dc = take(unit / 2);
+  w.dc = take((size_t)d.B * d.H * sizeof(float));
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
   for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)d.NA * d.KC * op);
@@ -204,7 +204,7 @@ int mebptt_profile_collect(mebptt_profile* out) {
 
 size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc) {
   if (!desc || desc->B < 1 || desc->H < 1) return 0;
-  return 2 * (size_t)desc->B * desc->H * sizeof(float);
+  return make_dims(desc->B, 1, desc->H, desc->gemm_dtype ? 1 : 0).unit * sizeof(float);
 }
 
 size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan) {
@@ -255,7 +255,7 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* ws = reinterpret_cast<char*>(workspace);
   const size_t plane = (size_t)d.B * d.H;
-  const size_t unit = 2 * plane;   // floats
+  const size_t unit = d.unit;   // floats
   float* state = reinterpret_cast<float*>(ws + w.state);
   float* slot0 = reinterpret_cast<float*>(slots);
   int core_flip = 0;   // which of the two working-core buffers MEBPTT_LOC_CORE currently names
