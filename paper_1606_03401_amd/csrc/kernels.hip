@@ -609,14 +609,15 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
 // The recomputation chain (forward operations) never depends on the backward chain, so the
 // forward operation that follows a backward step in the schedule can share its launch whenever
 // it does not overwrite a state that backward step still reads.  Workgroups [0, nf) play the
-// forward role, the rest the backward role; 512 threads and about 100 registers each, so one
-// workgroup of each role fits on a compute unit at the same time.  Each role splits K over the
+// forward role, the rest the backward role; 512 threads each, and the launch bounds hold the kernel
+// to 128 registers (4 waves per SIMD), so that two workgroups are resident on a compute unit at
+// the same time and the 2 x 256 workgroups of a launch run as one wave of work, not two.  Each role splits K over the
 // same number of waves as its stand-alone kernel, so sums are formed in the same order and results
 // do not depend on whether a step was fused.
-constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 3, PAIR_BKS = 8, PAIR_BU = 8;
+constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 2, PAIR_BKS = 8, PAIR_BU = 8;
 
 template <class T>
-__global__ __launch_bounds__(64 * PAIR_BKS) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
+__global__ __launch_bounds__(64 * PAIR_BKS, 4) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
   __shared__ float red[PAIR_FKS * PAIR_NG * 4 * 64];
   static_assert(PAIR_FKS * PAIR_NG >= PAIR_BKS && PAIR_FKS == PAIR_BKS, "shared buffer and block size cover both roles");
   const int id = blockIdx.x;
