@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: one LSTM gradient step under the DP checkpoint policy.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--sweep | --fig2b | --chen]
 
 A "step" is one call of ``mebptt_run``: every forward operation, every recomputation and every
 backward operation of the schedule for one batch of synthetic sequences.  Inputs are resident in
@@ -148,6 +148,45 @@ def fig2b(args) -> int:
     return 0
 
 
+def chen_comparison(args) -> int:
+    """Sections 4.2-4.3: Chen et al.'s sqrt(t) and recursive strategies run as policies through the
+    same executor on the benchmark workload, beside the optimal BPTT-MSM policy at the same memory,
+    and the two quantities of the paper's numerical comparison computed from the planner's tables
+    (memory needed for a cost of 2 forward operations per step relative to sqrt(t)(1+beta), and
+    cost per step at that memory; alpha = beta + 1)."""
+    import math
+    from paper_1606_03401_amd import binding as mb
+    from paper_1606_03401_amd import workloads as wl
+    from paper_1606_03401_amd.session import Session
+    w = wl.CONFIGS[args.workload]
+    inp = wl.make_inputs(w)
+    rows = []
+    cases = [("chen sqrt(t)", mb.mebptt_plan_chen_sqrt(w.t))]
+    cases += [(f"chen recursive k={k}", mb.mebptt_plan_chen_recursive(w.t, k)) for k in (1, 2, 4, 9)]
+    for name, plan in cases:
+        for label, pl in ((name, plan), (f"  BPTT-MSM at the same {plan.m} units", mb.mebptt_plan(w.t, plan.m, mb.MSM))):
+            sess = Session(w, inp, plan=pl, want_dx=True, want_y=False)
+            ms = time_runs(sess, args.steps, args.warmup) * 1e3
+            rows.append({"strategy": label.strip(), "units": pl.m, "slot_MiB": sess.slot_bytes / 2**20,
+                         "forward_ops": pl.forward_ops, "ms_per_step": ms})
+            log(f"[chen] {label:42s} {pl.m:5d} units ({sess.slot_bytes / 2**20:7.1f} MiB)  C = {pl.forward_ops:6d} "
+                f"({pl.forward_ops / w.t:.3f}/step)  {ms:8.3f} ms")
+            del sess
+    fig = []
+    for beta in (2, 5, 10):
+        for t in (100, 400, 1000):
+            ref = math.sqrt(t) * (1 + beta)
+            m_ref = int(ref)
+            tab = mb.mebptt_plan(t, m_ref, mb.MSM, beta + 1, beta)   # tables only (alpha may be below 4)
+            C = tab.cost(0)[t]
+            m_cost2 = next(m for m in range(1, m_ref + 1) if C[m] <= 2 * t)
+            fig.append({"beta": beta, "t": t, "memory_ratio_at_cost_2": m_cost2 / ref, "cost_per_step_at_chen_memory": C[m_ref] / t})
+            log(f"[chen] beta={beta:2d} t={t:4d}: memory at cost 2 = {m_cost2:4d} units = {m_cost2 / ref:.3f} x sqrt(t)(1+beta); "
+                f"cost at sqrt(t)(1+beta) = {C[m_ref] / t:.3f} per step")
+    print(json.dumps({"experiment": "chen", "workload": w.name, "rows": rows, "section_4_3": fig}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,6 +199,9 @@ def main() -> int:
     ap.add_argument("--fig2b", action="store_true",
                     help="the shape of the paper's timing experiment: LSTM 256->256, batch 64, ms per time step "
                          "vs sequence length at budgets of 10/50/100/500/1000 hidden states (table on stderr)")
+    ap.add_argument("--chen", action="store_true",
+                    help="Chen et al.'s sqrt(t) / recursive strategies as policies through the same executor, beside "
+                         "BPTT-MSM at the same memory, and the paper's numerical comparison (table on stderr)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build runs the path on a single device; --gpus must be 1")
@@ -175,6 +217,8 @@ def main() -> int:
         return 1
     if args.fig2b:
         return fig2b(args)
+    if args.chen:
+        return chen_comparison(args)
     w = wl.CONFIGS[args.workload]
     log(f"[bench] {mb.mebptt_version()} workload {w}")
     # A plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick

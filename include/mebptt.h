@@ -99,6 +99,35 @@ typedef struct {
 int mebptt_plan(int32_t t, int32_t m, int32_t kind, int32_t alpha, int32_t beta, mebptt_plan_t** out);
 void mebptt_plan_free(mebptt_plan_t* plan);
 
+/* Section 4.2: every strategy inside the model is a (possibly sub-optimal) policy of BPTT-MSM.
+ * A policy is handed over as the decisions the execution procedure of Section 3.3 asks for, in
+ * the order it asks: at a node (t', m') with t' >= 2 and m' >= 2 it takes the next decision --
+ * memorise the hidden state (store = 1, 1 <= y < t') or the internal state (store = 2,
+ * 1 <= y <= t') reached after y forward operations -- then treats the right part
+ * (t' - y, m' - units), then the left part (y or y - 1, m').  Nodes with t' <= 1, and nodes
+ * with m' = 1 (constant-memory procedure), take no decision.  Units: hidden 1, internal alpha,
+ * beta when y = 1; m counts the start state h_0, as in BPTT-MSM. */
+enum { MEBPTT_STORE_HIDDEN = 1, MEBPTT_STORE_INTERNAL = 2 };
+typedef struct {
+  int32_t store;
+  int32_t y;
+} mebptt_decision;
+/* Flattens the policy `decisions[0..n)` (host memory, read during the call only) for a sequence
+ * of length t within m units.  The plan has kind MEBPTT_MSM and no tables (the cost, split and
+ * choice accessors return NULL); forward_ops is the policy's cost.  alpha >= 4, 3 <= beta <=
+ * alpha.  Errors: EINVAL (malformed decision, too few or too many decisions), EINFEASIBLE (the
+ * policy does not fit into m), ENOMEM_HOST. */
+int mebptt_plan_from_policy(int32_t t, int32_t m, int32_t alpha, int32_t beta, const mebptt_decision* decisions,
+                            size_t n, mebptt_plan_t** out);
+/* Section 2, "Chen's sqrt(t) algorithm" as such a policy: ceil(sqrt(t)) parts of equal length,
+ * the hidden state memorised at every cut, every internal state (beta units each) memorised
+ * while a part is back-propagated.  The plan's budget is what the strategy needs. */
+int mebptt_plan_chen_sqrt(int32_t t, int32_t alpha, int32_t beta, mebptt_plan_t** out);
+/* Section 2, "Chen's recursive algorithm": k >= 1 hidden states memorised per level, cutting a
+ * sub-sequence into min(k + 1, length) equal parts, recursively down to single steps (k = 1:
+ * bisection, about log2(t) units).  The plan's budget is what the strategy needs. */
+int mebptt_plan_chen_recursive(int32_t t, int32_t k, int32_t alpha, int32_t beta, mebptt_plan_t** out);
+
 /* Borrowed read-only views, valid until mebptt_plan_free.  Tables are row-major
  * [(t+1) x (m+1)], entry [t'][m'].  Infeasible cost cells hold MEBPTT_COST_INF; undefined
  * split/choice cells hold 0.

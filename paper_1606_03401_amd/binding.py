@@ -33,6 +33,13 @@ class mebptt_op(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("op", "step", "count", "src", "dst", "keep", "prev")]
 
 
+class mebptt_decision(C.Structure):
+    _fields_ = [("store", C.c_int32), ("y", C.c_int32)]
+
+
+STORE_HIDDEN, STORE_INTERNAL = 1, 2
+
+
 class mebptt_lstm_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "I", "H", "t", "gemm_dtype", "loss", "dy_first_step")]
 
@@ -57,6 +64,10 @@ _P = C.c_void_p
 _DESC = C.POINTER(mebptt_lstm_desc)
 SIGNATURES = {
     "mebptt_plan": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
+    "mebptt_plan_from_policy": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(mebptt_decision),
+                                          C.c_size_t, C.POINTER(_P)]),
+    "mebptt_plan_chen_sqrt": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
+    "mebptt_plan_chen_recursive": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
     "mebptt_plan_free": (None, [_P]),
     "mebptt_plan_cost": (C.POINTER(C.c_int64), [_P, C.c_int32]),
     "mebptt_plan_split": (C.POINTER(C.c_int32), [_P, C.c_int32]),
@@ -172,6 +183,26 @@ class Plan:
 def mebptt_plan(t: int, m: int, kind: int, alpha: int = 4, beta: int = 3) -> Plan:
     out = _P()
     _check(lib().mebptt_plan(t, m, kind, alpha, beta, C.byref(out)))
+    return Plan(out.value)
+
+
+def mebptt_plan_from_policy(t: int, m: int, decisions, alpha: int = 4, beta: int = 3) -> Plan:
+    """`decisions`: sequence of (store, y) pairs, store = STORE_HIDDEN or STORE_INTERNAL."""
+    arr = (mebptt_decision * max(len(decisions), 1))(*[mebptt_decision(int(s), int(y)) for s, y in decisions])
+    out = _P()
+    _check(lib().mebptt_plan_from_policy(t, m, alpha, beta, arr, len(decisions), C.byref(out)))
+    return Plan(out.value)
+
+
+def mebptt_plan_chen_sqrt(t: int, alpha: int = 4, beta: int = 3) -> Plan:
+    out = _P()
+    _check(lib().mebptt_plan_chen_sqrt(t, alpha, beta, C.byref(out)))
+    return Plan(out.value)
+
+
+def mebptt_plan_chen_recursive(t: int, k: int, alpha: int = 4, beta: int = 3) -> Plan:
+    out = _P()
+    _check(lib().mebptt_plan_chen_recursive(t, k, alpha, beta, C.byref(out)))
     return Plan(out.value)
 
 

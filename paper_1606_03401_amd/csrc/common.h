@@ -31,4 +31,5 @@ struct mebptt_plan_s {
   int64_t forward_ops = 0;
   int64_t backward_ops = 0;
   int32_t peak = 0;   // in budget units of `kind`
+  bool from_policy = false;   // flattened from a caller-supplied decision list: no tables
 };

@@ -15,7 +15,14 @@
 // pushes, and the constant-memory procedure of Section 3 when a single unit is left.  An
 // internal state whose right-hand remainder is empty (y = t) is consumed by the next backward
 // operation, so it is kept in the working core and not pushed.
+//
+// A policy need not come from the tables: Section 4.2 observes that any strategy inside the model
+// -- Chen et al.'s two strategies of Section 2 in particular -- is a (possibly sub-optimal) policy
+// of BPTT-MSM.  Such a policy is given as the list of decisions the flattening asks for, in the
+// order it asks (a node, then its right sub-sequence, then its left one); the generators for the
+// sqrt(t) and the recursive strategy produce that list.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <string>
@@ -232,7 +239,7 @@ inline int32_t transient(int parity) { return parity ? MEBPTT_LOC_T1 : MEBPTT_LO
 
 class Flattener {
  public:
-  Flattener(mebptt_plan_t& p) : p_(p) {
+  Flattener(mebptt_plan_t& p, const std::vector<mebptt_decision>* list = nullptr) : p_(p), list_(list) {
     used_ = (p.kind == MEBPTT_ISM) ? 0 : 1;   // HSM/MSM: the start state h_0 occupies unit 0
     units_per_budget_ = (p.kind == MEBPTT_ISM) ? 4 : 1;
     capacity_ = (int64_t)p.m * units_per_budget_;
@@ -257,6 +264,8 @@ class Flattener {
       int rc = exec(w, st);
       if (rc) return rc;
     }
+    if (list_ && next_ != list_->size())
+      return set_error(MEBPTT_EINVAL, "policy has %zu decisions, the schedule asked for %zu", list_->size(), next_);
     p_.peak = (int32_t)((peak_ + units_per_budget_ - 1) / units_per_budget_);
     return MEBPTT_OK;
   }
@@ -279,7 +288,9 @@ class Flattener {
 
   int take(int32_t units) {
     used_ += units;
-    if (used_ > capacity_) return set_error(MEBPTT_EINVAL, "internal error: schedule exceeds the budget");
+    if (used_ > capacity_)
+      return list_ ? set_error(MEBPTT_EINFEASIBLE, "the policy needs more than the budget of %d units", p_.m)
+                   : set_error(MEBPTT_EINVAL, "internal error: schedule exceeds the budget");
     peak_ = std::max(peak_, used_);
     return MEBPTT_OK;
   }
@@ -303,7 +314,20 @@ class Flattener {
         for (int32_t k = t; k >= 1; --k) forward_into_core_and_backward(s, k, top);
         return MEBPTT_OK;
       }
-      if (p_.kind == MEBPTT_HSM) {
+      if (list_) {   // caller-supplied policy: one decision per node with t >= 2 and m >= 2
+        if (next_ >= list_->size())
+          return set_error(MEBPTT_EINVAL, "policy ends after %zu decisions; node (t=%d, m=%d) needs one", next_, t, m);
+        const mebptt_decision& d = (*list_)[next_++];
+        if (d.store != MEBPTT_STORE_HIDDEN && d.store != MEBPTT_STORE_INTERNAL)
+          return set_error(MEBPTT_EINVAL, "decision %zu: store must be 1 (hidden) or 2 (internal), got %d", next_ - 1, d.store);
+        internal = d.store == MEBPTT_STORE_INTERNAL;
+        y = d.y;
+        if (y < 1 || (internal ? y > t : y >= t))
+          return set_error(MEBPTT_EINVAL, "decision %zu: y=%d is outside the range of a sub-sequence of length %d", next_ - 1,
+                           y, t);
+        if (internal && y < t && m - (y == 1 ? p_.beta : p_.alpha) < 1)
+          return set_error(MEBPTT_EINFEASIBLE, "decision %zu: an internal state does not fit into %d units", next_ - 1, m);
+      } else if (p_.kind == MEBPTT_HSM) {
         internal = false;
         y = T.D[T.idx(t, m)];
       } else {
@@ -356,9 +380,87 @@ class Flattener {
   }
 
   mebptt_plan_t& p_;
+  const std::vector<mebptt_decision>* list_;
+  size_t next_ = 0;
   int64_t used_, peak_, capacity_;
   int32_t units_per_budget_;
 };
+
+// ---- Chen et al.'s strategies as decision lists (Section 2; Section 4.2) -----------------------
+
+inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+// A part that is run with every internal state memorised: each state is pushed right after the
+// step that made it (y = 1, beta units: its input state is the entry below).
+void chen_keep_all(int32_t n, std::vector<mebptt_decision>& out) {
+  for (int32_t i = 0; i + 1 < n; ++i) out.push_back(mebptt_decision{MEBPTT_STORE_INTERNAL, 1});
+}
+
+// sqrt(t): ceil(sqrt(t)) parts of equal length L, the hidden state memorised at every cut, each
+// part then (re)run keeping all of its internal states.  The cuts nest to the right, so their
+// decisions come first, then the last part, then one full part per cut while unwinding.
+void chen_sqrt_decisions(int32_t t, std::vector<mebptt_decision>& out) {
+  int32_t k = (int32_t)std::ceil(std::sqrt((double)t));
+  while ((int64_t)k * k < t) ++k;
+  while (k > 1 && (int64_t)(k - 1) * (k - 1) >= t) --k;
+  const int32_t L = ceil_div(t, k), ncut = ceil_div(t, L) - 1;
+  for (int32_t j = 0; j < ncut; ++j) out.push_back(mebptt_decision{MEBPTT_STORE_HIDDEN, L});
+  chen_keep_all(t - L * ncut, out);
+  for (int32_t j = 0; j < ncut; ++j) chen_keep_all(L, out);
+}
+
+// recursive, k memorised hidden states per level: a sub-sequence of length n is cut into
+// min(k+1, n) parts of equal length, each part treated the same way until its length is 1.
+void chen_recursive_decisions(int32_t n, int32_t k, std::vector<mebptt_decision>& out) {
+  if (n <= 1) return;
+  const int32_t parts = (int32_t)std::min<int64_t>((int64_t)k + 1, n);
+  const int32_t L = ceil_div(n, parts), ncut = ceil_div(n, L) - 1;
+  for (int32_t j = 0; j < ncut; ++j) out.push_back(mebptt_decision{MEBPTT_STORE_HIDDEN, L});
+  chen_recursive_decisions(n - L * ncut, k, out);
+  for (int32_t j = 0; j < ncut; ++j) chen_recursive_decisions(L, k, out);
+}
+
+int check_policy_args(int32_t t, int32_t alpha, int32_t beta, mebptt_plan_t** out) {
+  if (!out) return set_error(MEBPTT_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (t < 1) return set_error(MEBPTT_EINVAL, "t must be >= 1 (got %d)", t);
+  if (alpha < 4 || beta < 3 || beta > alpha)
+    return set_error(MEBPTT_EINVAL, "a schedule needs alpha >= 4 and 3 <= beta <= alpha (got %d, %d)", alpha, beta);
+  return MEBPTT_OK;
+}
+
+// Flattens `list` for (t, m) in the MSM protocol.  m <= 0: the budget becomes what the policy needs.
+int plan_from_list(int32_t t, int32_t m, int32_t alpha, int32_t beta, const std::vector<mebptt_decision>& list,
+                   mebptt_plan_t** out) {
+  for (int pass = (m > 0 ? 1 : 0); pass < 2; ++pass) {
+    mebptt_plan_t* p = new (std::nothrow) mebptt_plan_t;
+    if (!p) return set_error(MEBPTT_ENOMEM_HOST, "out of host memory");
+    p->t = t;
+    p->m = pass ? m : INT32_MAX / 8;   // sizing pass: no limit, the peak becomes the budget
+    p->kind = MEBPTT_MSM;
+    p->alpha = alpha;
+    p->beta = beta;
+    p->from_policy = true;
+    int rc;
+    try {
+      Flattener f(*p, &list);
+      rc = f.run();
+    } catch (const std::bad_alloc&) {
+      rc = set_error(MEBPTT_ENOMEM_HOST, "out of host memory");
+    }
+    if (rc) {
+      delete p;
+      return rc;
+    }
+    if (pass) {
+      *out = p;
+      return MEBPTT_OK;
+    }
+    m = p->peak;
+    delete p;
+  }
+  return MEBPTT_OK;
+}
 
 }  // namespace
 }  // namespace mebptt
@@ -420,10 +522,49 @@ int mebptt_plan(int32_t t, int32_t m, int32_t kind, int32_t alpha, int32_t beta,
   return MEBPTT_OK;
 }
 
+int mebptt_plan_from_policy(int32_t t, int32_t m, int32_t alpha, int32_t beta, const mebptt_decision* decisions,
+                            size_t n, mebptt_plan_t** out) {
+  int rc = check_policy_args(t, alpha, beta, out);
+  if (rc) return rc;
+  if (m < 1) return set_error(MEBPTT_EINVAL, "m must be >= 1 (got %d)", m);
+  if (n && !decisions) return set_error(MEBPTT_EINVAL, "decisions is NULL");
+  try {
+    std::vector<mebptt_decision> list(decisions, decisions + n);
+    return plan_from_list(t, m, alpha, beta, list, out);
+  } catch (const std::bad_alloc&) {
+    return set_error(MEBPTT_ENOMEM_HOST, "out of host memory");
+  }
+}
+
+int mebptt_plan_chen_sqrt(int32_t t, int32_t alpha, int32_t beta, mebptt_plan_t** out) {
+  int rc = check_policy_args(t, alpha, beta, out);
+  if (rc) return rc;
+  try {
+    std::vector<mebptt_decision> list;
+    chen_sqrt_decisions(t, list);
+    return plan_from_list(t, 0, alpha, beta, list, out);
+  } catch (const std::bad_alloc&) {
+    return set_error(MEBPTT_ENOMEM_HOST, "out of host memory");
+  }
+}
+
+int mebptt_plan_chen_recursive(int32_t t, int32_t k, int32_t alpha, int32_t beta, mebptt_plan_t** out) {
+  int rc = check_policy_args(t, alpha, beta, out);
+  if (rc) return rc;
+  if (k < 1) return set_error(MEBPTT_EINVAL, "k must be >= 1 (got %d)", k);
+  try {
+    std::vector<mebptt_decision> list;
+    chen_recursive_decisions(t, k, list);
+    return plan_from_list(t, 0, alpha, beta, list, out);
+  } catch (const std::bad_alloc&) {
+    return set_error(MEBPTT_ENOMEM_HOST, "out of host memory");
+  }
+}
+
 void mebptt_plan_free(mebptt_plan_t* plan) { delete plan; }
 
 const int64_t* mebptt_plan_cost(const mebptt_plan_t* p, int32_t which) {
-  if (!p) return nullptr;
+  if (!p || p->from_policy) return nullptr;
   if (which == 0) return p->tab.C.data();
   if (p->kind != MEBPTT_MSM) return nullptr;
   if (which == 1) return p->tab.C1.data();
@@ -432,7 +573,7 @@ const int64_t* mebptt_plan_cost(const mebptt_plan_t* p, int32_t which) {
 }
 
 const int32_t* mebptt_plan_split(const mebptt_plan_t* p, int32_t which) {
-  if (!p) return nullptr;
+  if (!p || p->from_policy) return nullptr;
   if (p->kind != MEBPTT_MSM) return which == 0 ? p->tab.D.data() : nullptr;
   if (which == 1) return p->tab.D1.data();
   if (which == 2) return p->tab.D2.data();
@@ -440,7 +581,7 @@ const int32_t* mebptt_plan_split(const mebptt_plan_t* p, int32_t which) {
 }
 
 const uint8_t* mebptt_plan_choice(const mebptt_plan_t* p) {
-  return (p && p->kind == MEBPTT_MSM) ? p->tab.Hc.data() : nullptr;
+  return (p && p->kind == MEBPTT_MSM && !p->from_policy) ? p->tab.Hc.data() : nullptr;
 }
 
 int32_t mebptt_plan_length(const mebptt_plan_t* p) { return p ? p->t : 0; }

@@ -78,6 +78,49 @@ def test_config1_every_budget_every_strategy():
                 assert np.array_equal(getattr(out, name), getattr(first, name)), (kind, m, name)
 
 
+def test_chen_strategies_and_caller_policies():
+    """Section 4.2: Chen et al.'s strategies run through the same executor as policies.  Their
+    cost and memory are the oracle's direct execution of the strategy; the gradients are those of
+    every other strategy, bit for bit, and within tolerance of the oracle's."""
+    from oracle import chen
+    from paper_1606_03401_amd import binding as mb
+    from paper_1606_03401_amd.session import Session
+    for w, nonzero in ((wl.CONFIGS["cfg1"], True),
+                       (wl.Workload("chen-bf16", B=40, I=48, H=1100, t=30, kind=wl.KIND_MSM, m=30,
+                                    gemm_dtype=wl.GEMM_BF16, loss=wl.LOSS_EXTERNAL_DY, dy_first_step=1, seed=77), False)):
+        inp = wl.make_inputs(w, nonzero_state=nonzero, nonzero_bias=nonzero)
+        ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+        base = Session(w, inp, kind=wl.KIND_HSM, m=5).run_and_fetch()
+        plans = [("sqrt", mb.mebptt_plan_chen_sqrt(w.t), chen.execute_chen_sqrt(w.t, 3))]
+        for k in (1, 2, 5):
+            plans.append((f"recursive k={k}", mb.mebptt_plan_chen_recursive(w.t, k), chen.execute_chen_recursive(w.t, k)))
+        # a caller's own policy: hidden state after 7 steps, the rest by Chen's bisection rule
+        tail = mb.mebptt_plan_chen_recursive(w.t - 7, 1)
+        plans.append(("from_policy", None, None))
+        for name, plan, tr in plans:
+            if plan is None:
+                dec = [(mb.STORE_HIDDEN, 7)] + [(mb.STORE_HIDDEN, (n + 1) // 2) for n in _bisection_nodes(w.t - 7)] \
+                      + [(mb.STORE_HIDDEN, (n + 1) // 2) for n in _bisection_nodes(7)]
+                plan = mb.mebptt_plan_from_policy(w.t, tail.m + 1, dec)
+            s = Session(w, inp, plan=plan)
+            out = s.run_and_fetch()
+            if tr is not None:
+                assert out.stats.forward_ops == tr.forwards and out.stats.peak == tr.peak, name
+            assert out.stats.backward_ops == w.t and out.stats.peak <= plan.m
+            check_against_oracle(w, inp, out, ref, TOL[w.gemm_dtype], label=f"{w.name} {name}: ")
+            for f in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+                assert np.array_equal(getattr(out, f), getattr(base, f)), (name, f)
+
+
+def _bisection_nodes(n):
+    """Lengths of the sub-sequences at which Chen's recursive strategy with k = 1 takes a decision,
+    in the order the execution procedure visits them (node, right part, left part)."""
+    if n <= 1:
+        return []
+    L = (n + 1) // 2
+    return [n] + _bisection_nodes(n - L) + _bisection_nodes(L)
+
+
 @pytest.mark.parametrize("dtype", [wl.GEMM_FP32, wl.GEMM_BF16])
 @pytest.mark.parametrize("B,I,H,t,kind,m", [
     (5, 7, 9, 6, wl.KIND_HSM, 3),          # nothing a multiple of anything
