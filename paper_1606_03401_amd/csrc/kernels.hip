@@ -312,14 +312,13 @@ __device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int
 // units = 16 gate rows each).  Its KS waves split the K axis; every wave covers all NG x BT output
 // tiles (each weight fragment is reused for BT batch tiles, each activation fragment for NG unit
 // groups) and issues all loads of U macro steps before the first MFMA, so that several KiB per
-// wave are in flight.  Partial sums meet in LDS (`red`, KS*NG*BT*256 floats) and are added in a
-// fixed order; the NG*BT tiles are then dealt round-robin to the waves for the LSTM pointwise
-// step.  (bx, by) = (unit-group tile, batch-tile group).
+// wave are in flight.  Partial sums meet in LDS (`red`, forward_red_floats(NG, BT, KS) floats) and
+// are added in a fixed order by the thread that then does the LSTM pointwise step of that
+// (sequence, unit).  (bx, by) = (unit-group tile, batch-tile group).
 template <class T, int NG, int BT, int KS, int U>
 __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
-  constexpr int NTILE = NG * BT, TPW = (NTILE + KS - 1) / KS;   // tiles, epilogue tiles per wave
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
@@ -354,22 +353,26 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
 #pragma unroll
     for (int t = 0; t < BT; ++t) acc[g][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // The epilogue operands of this wave's tiles are fetched now, so that their latency hides
-  // behind the K loop instead of following it.  Tile id = g * BT + t.
-  bool epi[TPW];
-  size_t eidx[TPW];
-  int eb[TPW], eu[TPW];
-  float4 bias[TPW];
-  float c_prev[TPW];
+  // Epilogue work is dealt out by memory layout, not by MFMA layout: item i of the workgroup's
+  // BT*16 rows x UW units is (row, unit) with the unit index fastest, so that consecutive lanes
+  // own consecutive units of one sequence and every pointwise load and store of a wave falls
+  // into runs of UW*4 bytes (plain planes) or 16 bytes (the 16-bit h planes) instead of one
+  // element per row.  The operands are fetched now, so that their latency hides behind the K loop.
+  constexpr int UW = NG * 4, RS = UW + 1;          // units per workgroup; padded row stride in `red`
+  constexpr int ITEMS = BT * 16 * UW, NTHR = 64 * KS, IPT = (ITEMS + NTHR - 1) / NTHR;
+  bool epi[IPT];
+  size_t eidx[IPT];
+  int eb[IPT], eu[IPT];
+  float4 bias[IPT];
+  float c_prev[IPT];
 #pragma unroll
-  for (int q = 0; q < TPW; ++q) {
-    const int tile = wave + q * KS;
-    const int g = tile / BT, t = tile % BT;
-    const int b = b0 + t * 16 + lrow;
-    const int u = (group0 + g) * 4 + lq;
-    epi[q] = tile < NTILE && b < p.B && u < p.H;
+  for (int q = 0; q < IPT; ++q) {
+    const int item = (int)threadIdx.x + q * NTHR;
+    const int b = b0 + (item / UW) % (BT * 16);     // rows of batch tile t follow those of t-1
+    const int u = group0 * 4 + item % UW;
+    epi[q] = item < ITEMS && b < p.B && u < p.H;
     eidx[q] = (size_t)b * p.H + u;
-    eb[q] = b;
+    eb[q] = item < ITEMS ? b : p.B;
     eu[q] = u;
     bias[q] = float4{0.f, 0.f, 0.f, 0.f};
     c_prev[q] = 0.0f;
@@ -413,25 +416,27 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     }
   }
 
+  // partial sums -> red[wave][gate r][row][unit] (row stride padded against bank conflicts)
 #pragma unroll
   for (int g = 0; g < NG; ++g)
 #pragma unroll
     for (int t = 0; t < BT; ++t)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[((wave * NTILE + g * BT + t) * 4 + r) * 64 + lane] = acc[g][t][r];
+      for (int r = 0; r < 4; ++r) red[((wave * 4 + r) * BT * 16 + t * 16 + lrow) * RS + g * 4 + lq] = acc[g][t][r];
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < TPW; ++q) {
-    const int tile = wave + q * KS;
-    if (tile >= NTILE) break;
+  for (int q = 0; q < IPT; ++q) {
+    const int item = (int)threadIdx.x + q * NTHR;
+    if (item >= ITEMS) break;
+    const int cell = ((item / UW) % (BT * 16)) * RS + item % UW;
     float G[4] = {0.f, 0.f, 0.f, 0.f};
     for (int w = 0; w < KS; ++w)   // fixed order: results do not depend on scheduling
 #pragma unroll
-      for (int r = 0; r < 4; ++r) G[r] += red[((w * NTILE + tile) * 4 + r) * 64 + lane];
+      for (int r = 0; r < 4; ++r) G[r] += red[(w * 4 + r) * BT * 16 * RS + cell];
     if (!epi[q]) {
       // split layout: the padding columns H..KH of a valid row are part of the operand other
       // launches fetch, so they are (re)written as zero with every state
-      if (HP_::SPLIT && tile < NTILE && eb[q] < p.B && eu[q] < p.KH) HP_::store(p.dst_h, eb[q], eu[q], 0.0f, nsh, p.H, hhalf);
+      if (HP_::SPLIT && eb[q] < p.B && eu[q] < p.KH) HP_::store(p.dst_h, eb[q], eu[q], 0.0f, nsh, p.H, hhalf);
       continue;
     }
     const size_t e = eidx[q];
@@ -452,9 +457,12 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
   }
 }
 
+// Floats of LDS a forward workgroup needs for its partial sums.
+constexpr int forward_red_floats(int NG, int BT, int KS) { return KS * 4 * BT * 16 * (NG * 4 + 1); }
+
 template <class T, int NG, int BT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
-  __shared__ float red[KS * NG * BT * 4 * 64];
+  __shared__ float red[forward_red_floats(NG, BT, KS)];
   forward_body<T, NG, BT, KS, U>(p, blockIdx.x, blockIdx.y, red);
 }
 
@@ -618,8 +626,9 @@ constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 2, PAIR_BKS = 8, PAIR_BU = 8;
 
 template <class T>
 __global__ __launch_bounds__(64 * PAIR_BKS, 4) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
-  __shared__ float red[PAIR_FKS * PAIR_NG * 4 * 64];
-  static_assert(PAIR_FKS * PAIR_NG >= PAIR_BKS && PAIR_FKS == PAIR_BKS, "shared buffer and block size cover both roles");
+  __shared__ float red[forward_red_floats(PAIR_NG, 1, PAIR_FKS)];
+  static_assert(forward_red_floats(PAIR_NG, 1, PAIR_FKS) >= PAIR_BKS * 4 * 64 && PAIR_FKS == PAIR_BKS,
+                "shared buffer and block size cover both roles");
   const int id = blockIdx.x;
   if (id < nf)
     forward_body<T, PAIR_NG, 1, PAIR_FKS, PAIR_FU>(f, id % nfx, id / nfx, red);
