@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 METRIC = "LSTM BPTT time-steps/s at budget m; cost ratio vs store-all BPTT"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+MFMA_PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # by gemm_dtype: fp32 operands, bf16 operands
 KIND_NAMES = {0: "HSM", 1: "ISM", 2: "MSM"}
 
 
@@ -249,13 +250,41 @@ def main() -> int:
     torch.cuda.synchronize()
     prof = mb.mebptt_profile_collect()
     mb.mebptt_profile_enable(0)
+    # What an event pair around a single launch adds: the same bracket around a launch that does
+    # nothing measurable (a 4-byte fill), minus nothing -- an upper bound of the bracket's own cost.
+    cal = torch.zeros(1, device=sess.dev)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    for a, b in pairs:
+        a.record()
+        cal.zero_()
+        b.record()
+    torch.cuda.synchronize()
+    bracket_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
+    null_us = 2.4   # a back-to-back empty launch on this stack: part of every kernel's own time
+    overhead_us = max(0.0, bracket_us - null_us)
+    log(f"[bench] event bracket around a minimal launch: {bracket_us:.2f} us -> {overhead_us:.2f} us subtracted from single-launch samples")
+    # flops of one launch of each class: forward op 8BH(I+H); backward step (dh GEMM) 8BH^2; the
+    # time-batched GEMMs carry t steps over their launches: dW 8BH(I+H), dx 8BHI per step
+    F_fwd, F_dh = forward_flops(w), 8.0 * w.B * w.H * w.H
+    F_dx = 8.0 * w.B * w.H * w.I
     classes = {}
     for k, name in enumerate(mb.K_NAMES):
         n_s = prof.sampled[k]
+        lps = prof.launches[k] / prof_steps
         avg_us = prof.sampled_ms[k] / n_s * 1e3 if n_s else None
-        classes[name] = {"launches_per_step": prof.launches[k] / prof_steps, "avg_us": avg_us}
-        log(f"[bench] kernel class {name}: {prof.launches[k] / prof_steps:.0f} launches/step, "
-            f"avg {avg_us if avg_us is None else round(avg_us, 2)} us (event-bracketed, {n_s} samples)")
+        classes[name] = {"launches_per_step": lps, "avg_us": avg_us}
+        if avg_us is not None and lps > 0:
+            net_us = max(avg_us - overhead_us, 1e-3)
+            flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_dh + F_fwd,
+                     "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps}.get(name)
+            classes[name]["net_us"] = net_us
+            if flops:
+                tf = flops / (net_us * 1e-6) / 1e12
+                classes[name].update({"gflop_per_launch": flops / 1e9, "tflops": tf, "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS[w.gemm_dtype]})
+        log(f"[bench] kernel class {name}: {lps:.0f} launches/step, "
+            f"avg {avg_us if avg_us is None else round(avg_us, 2)} us (event-bracketed, {n_s} samples)"
+            + (f", net {classes[name]['net_us']:.2f} us, {classes[name]['tflops']:.0f} TFLOP/s = "
+               f"{100 * classes[name]['frac_mfma_peak']:.1f}% of MFMA peak" if "tflops" in classes[name] else ""))
     # The dominant kernel's launch duration: whole forward runs bracketed by one event pair (the
     # figure rocprofv3's kernel trace reports); single-launch brackets carry ~4 us of event cost.
     if prof.forward_run_launches:
