@@ -36,10 +36,11 @@ Dims make_dims(int B, int I, int H, int dtype) {
   d.BP = round_up(B, 16);
   d.G4 = 4 * d.HP;
   d.NA = d.NX + d.HP + 16;
-  // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 8 MiB (the
-  // staging is t-independent workspace), at least 2 and at most 32.
+  // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 32 MiB (the
+  // staging is t-independent workspace), at least 2 and at most 32.  Every chunk costs one
+  // read-modify-write of the whole dW accumulator, so longer chunks are cheaper per step.
   const size_t step_bytes = (size_t)d.BP * d.G4 * (dtype ? 2 : 4);
-  size_t ch = ((size_t)8 << 20) / step_bytes;
+  size_t ch = ((size_t)32 << 20) / step_bytes;
   d.CH = ch < 2 ? 2 : (ch > 32 ? 32 : (int)ch);
   d.hplane = dtype ? (size_t)d.BP * d.KH : (size_t)B * H;
   d.unit = (d.hplane + (size_t)B * H + 63) / 64 * 64;
