@@ -799,22 +799,32 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
 template <class T, int NT, int RT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT, int N, const T* __restrict__ dG,
                                                         int nrow_tiles, int B, int BP, int G4,
-                                                        float* __restrict__ out, int ld_out) {
+                                                        float* __restrict__ out, int ld_out, int rows_per_xcd) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC, NTILE = NT * RT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
   __shared__ float red[KS * NTILE * 4 * 64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
+  // Workgroups are handed to the 8 XCDs round-robin by their linear id.  As launched, an XCD owns
+  // every 8th column group and sees all of dG.  With rows_per_xcd set, the id is re-mapped so
+  // that each XCD works through a contiguous range of (row group, column group) pairs, column
+  // group fastest: the workgroups that share a dG row group then share an L2 and every XCD
+  // fetches only its own eighth of dG -- the better choice when all of WT fits in one L2.
+  const int gx = (int)gridDim.x, total = gx * (int)gridDim.y;
+  const int id = (int)blockIdx.x + gx * (int)blockIdx.y;
+  const int xcd = id & 7;
+  const int work = rows_per_xcd ? xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3) : id;
+  const int bx = work % gx, by = work / gx;
   const int ncol_tiles = (N + 15) / 16;
   const int nsteps = G4 / KSTEP;
   const T* abase[NT];
   const T* bbase[RT];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
-    abase[i] = WT + ((size_t)min((int)blockIdx.x * NT + i, ncol_tiles - 1) * nsteps * 64 + lane) * VEC;
+    abase[i] = WT + ((size_t)min(bx * NT + i, ncol_tiles - 1) * nsteps * 64 + lane) * VEC;
 #pragma unroll
   for (int j = 0; j < RT; ++j)
-    bbase[j] = dG + ((size_t)min((int)blockIdx.y * RT + j, nrow_tiles - 1) * nsteps * 64 + lane) * VEC;
+    bbase[j] = dG + ((size_t)min(by * RT + j, nrow_tiles - 1) * nsteps * 64 + lane) * VEC;
   f32x4 acc[NT][RT];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
@@ -854,8 +864,8 @@ __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT
     for (int w = 0; w < KS; ++w) v += red[(w * NPIECE + piece) * 64 + lane];   // fixed order
     const int tile = piece >> 2, r = piece & 3;
     const int tn = tile / RT, tr = tile % RT;
-    const int row = ((int)blockIdx.y * RT + tr) * 16 + lrow;   // padded row: slot * BP + b
-    const int n = ((int)blockIdx.x * NT + tn) * 16 + 4 * lq + r;
+    const int row = (by * RT + tr) * 16 + lrow;   // padded row: slot * BP + b
+    const int n = (bx * NT + tn) * 16 + 4 * lq + r;
     const int slot = row / BP, b = row % BP;
     if (row >= nrow_tiles * 16 || b >= B || n >= N) continue;
     out[((size_t)slot * B + b) * ld_out + n] = v;
@@ -866,14 +876,15 @@ template <class T>
 static void launch_dgrad_t(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
                            hipStream_t st) {
   const int ncol_tiles = round_up(N, 16) / 16, nrow_tiles = nslots * d.BP / 16;
+  const int rows_per_xcd = (size_t)ncol_tiles * 16 * d.G4 * sizeof(T) <= ((size_t)4 << 20);   // WT fits one XCD's L2
   if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 1) / 2) >= TARGET_WGS) {
     dim3 grid((ncol_tiles + 1) / 2, (nrow_tiles + 1) / 2);
     dgrad_kernel<T, 2, 2, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
-                                                            ld_out);
+                                                            ld_out, rows_per_xcd);
   } else {
     dim3 grid(ncol_tiles, nrow_tiles);
     dgrad_kernel<T, 1, 1, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
-                                                            ld_out);
+                                                            ld_out, rows_per_xcd);
   }
 }
 
