@@ -74,11 +74,16 @@ def forward_bytes(w):
     """Algorithmic bytes of one forward operation: the gate weights once in the GEMM operand
     type, x_t once, and the hidden state (h, c) read and written once in fp32."""
     op = 2 if w.gemm_dtype else 4
-    return 4 * w.H * (w.I + w.H) * op + 4 * w.B * w.I + 16 * w.B * w.H
+    return gate_blocks(w) * w.H * (w.I + w.H) * op + 4 * w.B * w.I + 16 * w.B * w.H
+
+
+def gate_blocks(w):
+    """Gate blocks of the core's weight matrices: 4 (LSTM) or 3 (GRU)."""
+    return 3 if w.cell else 4
 
 
 def forward_flops(w):
-    return 8 * w.B * w.H * (w.I + w.H)
+    return 2 * gate_blocks(w) * w.B * w.H * (w.I + w.H)
 
 
 def pmc_traffic():
@@ -97,6 +102,7 @@ def cpu_baseline(w, inp, budget_s=20.0):
     """The oracle (float64 store-everything BPTT) on this host, on a prefix of the workload's
     sequence sized to take roughly `budget_s` seconds."""
     import numpy as np
+    from oracle import gru_bptt as og
     from oracle import lstm_bptt as ob
     try:
         from threadpoolctl import threadpool_info
@@ -111,7 +117,10 @@ def cpu_baseline(w, inp, budget_s=20.0):
         if inp.dy is not None and dy.shape[0] == 0:
             dy, first = np.zeros((1,) + inp.dy.shape[1:], np.float32), n
         t0 = time.perf_counter()
-        ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[:n], inp.h0, inp.c0, dy, first)
+        if w.cell:
+            og.gru_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[:n], inp.h0, dy, first)
+        else:
+            ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[:n], inp.h0, inp.c0, dy, first)
         return time.perf_counter() - t0
 
     per_step = run(probe) / probe
@@ -200,6 +209,7 @@ def main() -> int:
     ap.add_argument("--fig2b", action="store_true",
                     help="the shape of the paper's timing experiment: LSTM 256->256, batch 64, ms per time step "
                          "vs sequence length at budgets of 10/50/100/500/1000 hidden states (table on stderr)")
+    ap.add_argument("--cell", choices=("lstm", "gru"), default="lstm", help="RNN core run on the workload's shape")
     ap.add_argument("--chen", action="store_true",
                     help="Chen et al.'s sqrt(t) / recursive strategies as policies through the same executor, beside "
                          "BPTT-MSM at the same memory, and the paper's numerical comparison (table on stderr)")
@@ -221,6 +231,8 @@ def main() -> int:
     if args.chen:
         return chen_comparison(args)
     w = wl.CONFIGS[args.workload]
+    if args.cell == "gru":
+        w = w.scaled(name=w.name + "-gru", cell=wl.CELL_GRU)
     log(f"[bench] {mb.mebptt_version()} workload {w}")
     # A plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick
     # that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters into bytes (see profiles/).
@@ -265,8 +277,8 @@ def main() -> int:
     log(f"[bench] event bracket around a minimal launch: {bracket_us:.2f} us -> {overhead_us:.2f} us subtracted from single-launch samples")
     # flops of one launch of each class: forward op 8BH(I+H); backward step (dh GEMM) 8BH^2; the
     # time-batched GEMMs carry t steps over their launches: dW 8BH(I+H), dx 8BHI per step
-    F_fwd, F_dh = forward_flops(w), 8.0 * w.B * w.H * w.H
-    F_dx = 8.0 * w.B * w.H * w.I
+    F_fwd, F_dh = forward_flops(w), 2.0 * gate_blocks(w) * w.B * w.H * w.H
+    F_dx = 2.0 * gate_blocks(w) * w.B * w.H * w.I
     classes = {}
     for k, name in enumerate(mb.K_NAMES):
         n_s = prof.sampled[k]
@@ -330,7 +342,7 @@ def main() -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_stream_launches": eager_ms, "ms_per_step_graph_replay": graph_ms,
         "host_enqueue_ms": enqueue_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_dtype else "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: single-layer LSTM I={w.I} H={w.H} B={w.B} t={w.t}, "
+        "config": {"workload": f"{w.name}: single-layer {'GRU' if w.cell else 'LSTM'} I={w.I} H={w.H} B={w.B} t={w.t}, "
                                f"BPTT-{KIND_NAMES[sess.kind]} budget m={sess.m}, seed {w.seed}",
                    "launch": launch_mode, "budget_m": sess.m, "forward_ops": C, "peak_slots": sess.plan.peak,
                    "slot_pool_bytes": sess.slot_bytes, "workspace_bytes": sess.ws_bytes},

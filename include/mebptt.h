@@ -161,7 +161,10 @@ typedef struct {
                             0.5 * sum_s sum(h_s^2), i.e. dy_s = h_s                             */
   int32_t dy_first_step; /* loss 0: `dy` covers steps dy_first_step .. t (1-based); the steps
                             before carry no loss.  Use 1 for a loss at every step.              */
+  int32_t cell;          /* the RNN core (Section 1: the method does not depend on it):
+                            MEBPTT_CELL_LSTM or MEBPTT_CELL_GRU                                 */
 } mebptt_lstm_desc;
+enum { MEBPTT_CELL_LSTM = 0, MEBPTT_CELL_GRU = 1 };
 
 typedef struct {
   int64_t forward_ops;    /* forward operations launched (== C(t, m))   */
@@ -187,6 +190,12 @@ int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_
  * device, read:  W_ih [4H,I], W_hh [4H,H], b [4H] (NULL = zeros), x [t,B,I],
  *                dy [t-dy_first_step+1, B, H] (loss 0; ignored for loss 1),
  *                h0, c0 [B,H] (NULL = zeros).
+ *                LSTM: gate order i, f, g, o along the 4H axis, one bias vector.
+ *                GRU (cell = MEBPTT_CELL_GRU): W_ih [3H,I], W_hh [3H,H], gate order r, z, n;
+ *                b [6H] = [b_ih | b_hh]; n = tanh(W_in x + b_in + r * (W_hn h + b_hn)),
+ *                h' = (1 - z) * n + z * h.  c0 is ignored.  The gradients have the same
+ *                shapes (dW_ih [3H,I], dW_hh [3H,H], db [6H]); dc0 is written as zero.  A slot
+ *                unit keeps the LSTM's size, so the same plans and budgets apply.
  * device, r/w:   slots (>= mebptt_slot_pool_bytes, 256-byte aligned), workspace
  *                (>= mebptt_workspace_bytes, 256-byte aligned).  Contents on entry are ignored;
  *                contents on exit are unspecified.

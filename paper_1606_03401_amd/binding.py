@@ -41,7 +41,10 @@ STORE_HIDDEN, STORE_INTERNAL = 1, 2
 
 
 class mebptt_lstm_desc(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "I", "H", "t", "gemm_dtype", "loss", "dy_first_step")]
+    _fields_ = [(n, C.c_int32) for n in ("B", "I", "H", "t", "gemm_dtype", "loss", "dy_first_step", "cell")]
+
+
+CELL_LSTM, CELL_GRU = 0, 1
 
 
 class mebptt_stats(C.Structure):
@@ -206,8 +209,9 @@ def mebptt_plan_chen_recursive(t: int, k: int, alpha: int = 4, beta: int = 3) ->
     return Plan(out.value)
 
 
-def make_desc(B: int, I: int, H: int, t: int, gemm_dtype: int, loss: int, dy_first_step: int = 1) -> mebptt_lstm_desc:
-    return mebptt_lstm_desc(B, I, H, t, gemm_dtype, loss, dy_first_step)
+def make_desc(B: int, I: int, H: int, t: int, gemm_dtype: int, loss: int, dy_first_step: int = 1,
+              cell: int = CELL_LSTM) -> mebptt_lstm_desc:
+    return mebptt_lstm_desc(B, I, H, t, gemm_dtype, loss, dy_first_step, cell)
 
 
 def mebptt_unit_bytes(desc: mebptt_lstm_desc) -> int:

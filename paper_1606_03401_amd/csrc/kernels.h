@@ -8,7 +8,8 @@
 // The logical matrices below are all stored fragment-tiled (16-row tiles, one contiguous 1 KiB
 // block per tile and macro step; the exact index map is next to ft_offset in kernels.hip):
 //   Wp  [G4][KP]         forward operand: row 4*u + gate is row gate*H + u of [W_ih | W_hh];
-//                        columns [0,KX) hold W_ih, [KX,KP) hold W_hh.
+//                        columns [0,KX) hold W_ih, [KX,KP) hold W_hh.  (GRU: the four rows of a
+//                        unit are r, z, n_x = [W_in | 0], n_h = [0 | W_hn]; see packed_gate_x/h.)
 //   WTh [HP][G4]         WTh[n][4u+gate] = W_hh[gate*H+u][n]  (operand of dh_{s-1} = dG_s W_hh)
 //   WTx [NX][G4]         WTx[n][4u+gate] = W_ih[gate*H+u][n]  (operand of dx_s   = dG_s W_ih)
 //   dG  [CH*BP][G4]      gate pre-activation gradients of one chunk of CH consecutive steps, row
@@ -21,7 +22,7 @@
 //   bp  [G4] fp32        bias in the permuted order: bp[4u + gate] = b[gate*H + u].
 //
 // State units.  A unit (the granule of the slot pool) holds a hidden state (h, c) or a pair of gate
-// planes; it is `unit` floats long (a multiple of 64).  Gate planes and c are plain [B][H] fp32.
+// planes (GRU: (h, n_h pre-activation) and the pairs (r, z), (n, unused)); it is `unit` floats long (a multiple of 64).  Gate planes and c are plain [B][H] fp32.
 // The h plane comes first in its unit and is `hplane` floats long:
 //   fp32 operands: plain [B][H] fp32.
 //   bf16 operands: the SAME 4 bytes per element, split into two fragment-tiled 16-bit planes of
@@ -43,13 +44,14 @@ struct Dims {
   int HP, KX, KH, KP, NX, BP, G4, NA;
   int CH, KC;   // steps per weight-gradient chunk, padded K of that GEMM
   int dtype;    // 0 fp32, 1 bf16
+  int cell;     // 0 LSTM, 1 GRU
   size_t hplane, unit;   // floats: the h part of a hidden-state unit, a whole unit
   size_t op_bytes() const { return dtype ? 2 : 4; }
 };
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-Dims make_dims(int B, int I, int H, int dtype);
+Dims make_dims(int B, int I, int H, int dtype, int cell);
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_prep_weights(const Dims& d, const float* W_ih, const float* W_hh, const float* b, void* Wp,
@@ -105,6 +107,7 @@ hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslo
 hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, float* db,
                                hipStream_t st);
 
-hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, hipStream_t st);
+// One [B,H] plane: dst = src (accumulate 0), dst += src (1), dst = 0 (2; src unused).
+hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, int accumulate, hipStream_t st);
 
 }  // namespace mebptt

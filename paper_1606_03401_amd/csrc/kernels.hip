@@ -22,8 +22,9 @@ namespace mebptt {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-Dims make_dims(int B, int I, int H, int dtype) {
+Dims make_dims(int B, int I, int H, int dtype, int cell) {
   Dims d{};
+  d.cell = cell;
   d.B = B;
   d.I = I;
   d.H = H;
@@ -172,6 +173,14 @@ __device__ inline size_t ft_offset(int row, int k, int nsteps) {
   return ((((size_t)(row >> 4) * nsteps + k / KSTEP) * 64 + ((k % KSTEP) / VEC) * 16 + (row & 15)) * VEC) + k % VEC;
 }
 
+// The four packed rows 4u .. 4u+3 of hidden unit u, and which gate block of the caller's W_ih / W_hh
+// feeds each of them (-1: that half of the row is zero).
+//   LSTM: rows i, f, g, o, both halves from the same gate block.
+//   GRU:  rows r, z, n_x, n_h.  The candidate's input part and recurrent part are kept as two rows
+//         (n = tanh(n_x + r * n_h)), so one GEMM with the same 4-rows-per-unit shape serves both cells.
+__host__ __device__ inline int packed_gate_x(int cell, int row) { return cell == 0 ? row : (row < 3 ? row : -1); }
+__host__ __device__ inline int packed_gate_h(int cell, int row) { return cell == 0 ? row : (row == 2 ? -1 : (row == 3 ? 2 : row)); }
+
 template <class T>
 __global__ void prep_weights_kernel(Dims d, const float* __restrict__ W_ih, const float* __restrict__ W_hh,
                                     const float* __restrict__ b, T* __restrict__ Wp, float* __restrict__ bp,
@@ -187,11 +196,12 @@ __global__ void prep_weights_kernel(Dims d, const float* __restrict__ W_ih, cons
       int u = rowp >> 2, gate = rowp & 3;
       float v = 0.0f;
       if (u < d.H) {
-        size_t row = (size_t)gate * d.H + u;
         if (k < d.KX) {
-          if (k < d.I) v = W_ih[row * d.I + k];
+          const int gx = packed_gate_x(d.cell, gate);
+          if (k < d.I && gx >= 0) v = W_ih[((size_t)gx * d.H + u) * d.I + k];
         } else if (k - d.KX < d.H) {
-          v = W_hh[row * d.H + (k - d.KX)];
+          const int gh = packed_gate_h(d.cell, gate);
+          if (gh >= 0) v = W_hh[((size_t)gh * d.H + u) * d.H + (k - d.KX)];
         }
       }
       Wp[idx] = (T)v;
@@ -204,18 +214,31 @@ __global__ void prep_weights_kernel(Dims d, const float* __restrict__ W_ih, cons
       int u = kp >> 2, gate = kp & 3;
       float v = 0.0f;
       if (u < d.H) {
-        size_t row = (size_t)gate * d.H + u;
-        if (is_h) {
-          if (n < d.H) v = W_hh[row * d.H + n];
-        } else {
-          if (n < d.I) v = W_ih[row * d.I + n];
+        const int g = is_h ? packed_gate_h(d.cell, gate) : packed_gate_x(d.cell, gate);
+        if (g >= 0) {
+          const size_t row = (size_t)g * d.H + u;
+          if (is_h) {
+            if (n < d.H) v = W_hh[row * d.H + n];
+          } else {
+            if (n < d.I) v = W_ih[row * d.I + n];
+          }
         }
       }
       (is_h ? WTh : WTx)[j] = (T)v;
     } else {
       int kp = (int)(idx - nWp - nWTh - nWTx);
       int u = kp >> 2, gate = kp & 3;
-      bp[kp] = (b != nullptr && u < d.H) ? b[(size_t)gate * d.H + u] : 0.0f;
+      float v = 0.0f;
+      if (b != nullptr && u < d.H) {
+        if (d.cell == 0) {
+          v = b[(size_t)gate * d.H + u];
+        } else {   // b = [b_ih (r, z, n) | b_hh (r, z, n)]
+          const int gx = packed_gate_x(1, gate), gh = packed_gate_h(1, gate);
+          if (gx >= 0) v += b[(size_t)gx * d.H + u];
+          if (gh >= 0) v += b[(size_t)(3 + gh) * d.H + u];
+        }
+      }
+      bp[kp] = v;
     }
   }
 }
@@ -255,16 +278,17 @@ hipError_t launch_init_state(const Dims& d, const float* h0, const float* c0, fl
   return hipGetLastError();
 }
 
-__global__ void copy_plane_kernel(size_t n, const float* __restrict__ src, float* __restrict__ dst) {
+__global__ void copy_plane_kernel(size_t n, const float* __restrict__ src, float* __restrict__ dst, int accumulate) {
   size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    dst[i] = accumulate == 2 ? 0.0f : (accumulate ? dst[i] + src[i] : src[i]);
 }
 
-hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, hipStream_t st) {
+hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, int accumulate, hipStream_t st) {
   size_t n = (size_t)d.B * d.H;
   size_t blocks = (n + 255) / 256;
   if (blocks > 2048) blocks = 2048;
-  copy_plane_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(n, src, dst);
+  copy_plane_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(n, src, dst, accumulate);
   return hipGetLastError();
 }
 
@@ -316,7 +340,7 @@ __device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int
 // wave are in flight.  Partial sums meet in LDS (`red`, forward_red_floats(NG, BT, KS) floats) and
 // are added in a fixed order by the thread that then does the LSTM pointwise step of that
 // (sequence, unit).  (bx, by) = (unit-group tile, batch-tile group).
-template <class T, int NG, int BT, int KS, int U>
+template <class T, int NG, int BT, int KS, int U, int CELL>
 __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
@@ -379,7 +403,8 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     c_prev[q] = 0.0f;
     if (epi[q]) {
       bias[q] = *reinterpret_cast<const float4*>(p.bp + 4 * u);
-      c_prev[q] = p.src_c[eidx[q]];
+      // the state the pointwise step blends with: c_{s-1} (LSTM) or h_{s-1} in full precision (GRU)
+      c_prev[q] = CELL ? HP_::load(p.src_h, b, u, nsh, p.H, hhalf) : p.src_c[eidx[q]];
     }
   }
 
@@ -441,19 +466,36 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
       continue;
     }
     const size_t e = eidx[q];
-    const float gi = sigmoidf_(G[0] + bias[q].x);
-    const float gf = sigmoidf_(G[1] + bias[q].y);
-    const float gg = tanhf_(G[2] + bias[q].z);
-    const float go = sigmoidf_(G[3] + bias[q].w);
-    const float c = gf * c_prev[q] + gi * gg;
-    const float h = go * tanhf_(c);
-    HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
-    p.dst_c[e] = c;
-    if (p.g_i) {
-      p.g_i[e] = gi;
-      p.g_f[e] = gf;
-      p.g_g[e] = gg;
-      p.g_o[e] = go;
+    if (CELL == 0) {
+      const float gi = sigmoidf_(G[0] + bias[q].x);
+      const float gf = sigmoidf_(G[1] + bias[q].y);
+      const float gg = tanhf_(G[2] + bias[q].z);
+      const float go = sigmoidf_(G[3] + bias[q].w);
+      const float c = gf * c_prev[q] + gi * gg;
+      const float h = go * tanhf_(c);
+      HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
+      p.dst_c[e] = c;
+      if (p.g_i) {
+        p.g_i[e] = gi;
+        p.g_f[e] = gf;
+        p.g_g[e] = gg;
+        p.g_o[e] = go;
+      }
+    } else {
+      // GRU: rows r, z, n_x, n_h.  The second plane of the state unit keeps n_h (the recurrent
+      // part of the candidate before the reset gate), which the backward step needs.
+      const float r = sigmoidf_(G[0] + bias[q].x);
+      const float z = sigmoidf_(G[1] + bias[q].y);
+      const float nh = G[3] + bias[q].w;
+      const float n = tanhf_(G[2] + bias[q].z + r * nh);
+      const float h = (1.0f - z) * n + z * c_prev[q];
+      HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
+      p.dst_c[e] = nh;
+      if (p.g_i) {
+        p.g_i[e] = r;
+        p.g_f[e] = z;
+        p.g_g[e] = n;
+      }
     }
   }
 }
@@ -461,10 +503,10 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
 // Floats of LDS a forward workgroup needs for its partial sums.
 constexpr int forward_red_floats(int NG, int BT, int KS) { return KS * 4 * BT * 16 * (NG * 4 + 1); }
 
-template <class T, int NG, int BT, int KS, int U>
+template <class T, int NG, int BT, int KS, int U, int CELL>
 __global__ __launch_bounds__(64 * KS) void forward_kernel(FwdParams p) {
   __shared__ float red[forward_red_floats(NG, BT, KS)];
-  forward_body<T, NG, BT, KS, U>(p, blockIdx.x, blockIdx.y, red);
+  forward_body<T, NG, BT, KS, U, CELL>(p, blockIdx.x, blockIdx.y, red);
 }
 
 // ---- backward step: dh GEMM + loss-gradient injection + LSTM pointwise backward --------------
@@ -481,6 +523,7 @@ struct BwdParams {
   int col0;
   float* y_out_s;
   int B, H, HP, KH, G4, NX, KC, BP;
+  int cell;     // 0 LSTM, 1 GRU
 };
 
 // One workgroup of 64*KS threads = NT hidden-unit tiles x BT batch tiles (16 x 16 outputs each);
@@ -521,11 +564,15 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
       gi[q] = p.g_i[e];
       gf[q] = p.g_f[e];
       gg[q] = p.g_g[e];
-      go[q] = p.g_o[e];
       c_s[q] = p.c[e];
-      c_prev[q] = p.c_prev[e];
       dc_in[q] = p.dc[e];
       h_prev[q] = (float)HPlane<T>::as_operand(p.h_prev, b, n, p.KH / 32, p.H, (size_t)p.BP * p.KH);
+      if (p.cell == 0) {
+        go[q] = p.g_o[e];
+        c_prev[q] = p.c_prev[e];
+      } else {   // GRU blends with h_{s-1} itself: its full-precision value takes c_prev's place
+        c_prev[q] = HPlane<T>::load(p.h_prev, b, n, p.KH / 32, p.H, (size_t)p.BP * p.KH);
+      }
     }
   }
   if (p.dG_next) {
@@ -582,14 +629,28 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
     const int n = en[q], b = eb[q];
     dh += p.dy_is_h ? h[q] : dy[q];
     if (p.y_out_s) p.y_out_s[e] = h[q];
-    const float tc = tanhf_(c_s[q]);
-    const float d_o = dh * tc;
-    const float dct = dc_in[q] + dh * go[q] * (1.0f - tc * tc);
-    const float dGi = dct * gg[q] * gi[q] * (1.0f - gi[q]);
-    const float dGf = dct * c_prev[q] * gf[q] * (1.0f - gf[q]);
-    const float dGg = dct * gi[q] * (1.0f - gg[q] * gg[q]);
-    const float dGo = d_o * go[q] * (1.0f - go[q]);
-    p.dc[e] = dct * gf[q];
+    float dGi, dGf, dGg, dGo;
+    if (p.cell == 0) {
+      const float tc = tanhf_(c_s[q]);
+      const float d_o = dh * tc;
+      const float dct = dc_in[q] + dh * go[q] * (1.0f - tc * tc);
+      dGi = dct * gg[q] * gi[q] * (1.0f - gi[q]);
+      dGf = dct * c_prev[q] * gf[q] * (1.0f - gf[q]);
+      dGg = dct * gi[q] * (1.0f - gg[q] * gg[q]);
+      dGo = d_o * go[q] * (1.0f - go[q]);
+      p.dc[e] = dct * gf[q];
+    } else {
+      // GRU: r = gi, z = gf, n = gg, n_h = c_s, h_{s-1} = c_prev.  The running plane `dc` carries
+      // the part of dL/dh_{s-1} that bypasses the GEMM: dh_s * z_s.
+      dh += dc_in[q];
+      const float r = gi[q], z = gf[q], n = gg[q];
+      const float da_n = dh * (1.0f - z) * (1.0f - n * n);
+      dGi = da_n * c_s[q] * r * (1.0f - r);                 // reset gate
+      dGf = dh * (c_prev[q] - n) * z * (1.0f - z);          // update gate
+      dGg = da_n;                                           // candidate, input part (row n_x)
+      dGo = da_n * r;                                       // candidate, recurrent part (row n_h)
+      p.dc[e] = dh * z;
+    }
     const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
     // dG of this step, fragment-tiled [b][4n + gate]: the four gates are consecutive in one lane slot
     T* dG4 = reinterpret_cast<T*>(p.dG_cur) + ft_offset<T>(b, 4 * n, p.G4 / KSTEP);
@@ -625,14 +686,14 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
 // do not depend on whether a step was fused.
 constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 2, PAIR_BKS = 8, PAIR_BU = 8;
 
-template <class T>
+template <class T, int CELL>
 __global__ __launch_bounds__(64 * PAIR_BKS, 4) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
   __shared__ float red[forward_red_floats(PAIR_NG, 1, PAIR_FKS)];
   static_assert(forward_red_floats(PAIR_NG, 1, PAIR_FKS) >= PAIR_BKS * 4 * 64 && PAIR_FKS == PAIR_BKS,
                 "shared buffer and block size cover both roles");
   const int id = blockIdx.x;
   if (id < nf)
-    forward_body<T, PAIR_NG, 1, PAIR_FKS, PAIR_FU>(f, id % nfx, id / nfx, red);
+    forward_body<T, PAIR_NG, 1, PAIR_FKS, PAIR_FU, CELL>(f, id % nfx, id / nfx, red);
   else
     backward_body<T, 1, 1, PAIR_BKS, PAIR_BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
 }
@@ -668,7 +729,10 @@ static BwdConfig backward_config(const Dims& d) {
 template <class T, int NG, int BT, int KS, int U>
 static hipError_t launch_forward_cfg(const Dims& d, const FwdParams& p, hipStream_t st) {
   dim3 grid((d.HP / 4 + NG - 1) / NG, (d.BP / 16 + BT - 1) / BT), block(64 * KS);
-  forward_kernel<T, NG, BT, KS, U><<<grid, block, 0, st>>>(p);
+  if (d.cell)
+    forward_kernel<T, NG, BT, KS, U, 1><<<grid, block, 0, st>>>(p);
+  else
+    forward_kernel<T, NG, BT, KS, U, 0><<<grid, block, 0, st>>>(p);
   return hipGetLastError();
 }
 
@@ -746,6 +810,7 @@ static BwdParams make_bwd_params(const Dims& d, const BackwardArgs& a) {
   p.g_g = a.state + 2 * d.unit;
   p.g_o = a.state + 2 * d.unit + plane;
   p.h_prev = a.prev;
+  p.cell = d.cell;
   p.c_prev = a.prev + d.hplane;
   p.dy_s = a.dy_s;
   p.dy_is_h = a.dy_is_h;
@@ -785,9 +850,9 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
   const int nbx = d.HP / 16, nby = d.BP / 16;
   dim3 grid(nfx * nfy + nbx * nby), block(64 * PAIR_BKS);
   if (d.dtype)
-    pair_kernel<__bf16><<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+    (d.cell ? pair_kernel<__bf16, 1> : pair_kernel<__bf16, 0>)<<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
   else
-    pair_kernel<float><<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+    (d.cell ? pair_kernel<float, 1> : pair_kernel<float, 0>)<<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
   return hipGetLastError();
 }
 
@@ -1030,32 +1095,42 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
 }
 
 // dW_ih[row][n] / dW_hh[row][n] <- the tile-ordered accumulator (see wgrad_kernel's epilogue).
-// The accumulator's column NX + HP (operand row of ones) holds db.
+// The accumulator's column NX + HP (operand row of ones) holds the bias gradient.  ngates = 4
+// (LSTM: db [4H]) or 3 (GRU: db = [db_ih | db_hh], 6H); the packed row of a gate block differs
+// between the input and the recurrent side for the GRU (packed_gate_x / packed_gate_h).
 __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int NX, int HP, int I, int H,
-                                    float* __restrict__ dW_ih, float* __restrict__ dW_hh, float* __restrict__ db) {
-  const size_t total = (size_t)4 * H * (I + H + 1);
+                                    int cell, float* __restrict__ dW_ih, float* __restrict__ dW_hh,
+                                    float* __restrict__ db) {
+  const int ngates = cell ? 3 : 4;
+  const size_t nih = (size_t)ngates * H * I, nhh = (size_t)ngates * H * H, nb = (size_t)(cell ? 6 : 4) * H;
+  const size_t total = nih + nhh + nb;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
-    int row, n, np;
+    int row, np;
+    bool recurrent;
     float* dst;
-    if (idx < (size_t)4 * H * I) {
+    if (idx < nih) {
       row = (int)(idx / I);
-      n = (int)(idx % I);
-      np = n;
+      np = (int)(idx % I);
+      recurrent = false;
       dst = dW_ih + idx;
-    } else if (idx < (size_t)4 * H * (I + H)) {
-      const size_t j = idx - (size_t)4 * H * I;
+    } else if (idx < nih + nhh) {
+      const size_t j = idx - nih;
       row = (int)(j / H);
-      n = (int)(j % H);
-      np = NX + n;
+      np = NX + (int)(j % H);
+      recurrent = true;
       dst = dW_hh + j;
     } else {
-      row = (int)(idx - (size_t)4 * H * (I + H));
+      row = (int)(idx - nih - nhh);
+      recurrent = row >= ngates * H;   // only the GRU has a second (recurrent) bias block
+      if (recurrent) row -= ngates * H;
       np = NX + HP;
-      dst = db + row;
+      dst = db + (idx - nih - nhh);
     }
     const int gate = row / H, u = row % H;
-    const int mp = 4 * u + gate;                       // permuted row
+    int prow = gate;                                    // packed row of this gate block
+    if (cell) prow = recurrent ? (gate == 2 ? 3 : gate) : gate;
+    const int mp = 4 * u + prow;
     const int mt = mp >> 4, lq = (mp & 15) >> 2, r = mp & 3;
     const int nt = np >> 4, lrow = np & 15;
     const int wgx = mt / (2 * WT), wm = (mt % (2 * WT)) / WT, i = mt % WT;
@@ -1105,7 +1180,7 @@ hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, 
                                hipStream_t st) {
   const int WT = wgrad_wave_tile(d);
   const int grid_y = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
-  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.HP, d.I, d.H, dW_ih, dW_hh, db);
+  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.HP, d.I, d.H, d.cell, dW_ih, dW_hh, db);
   return hipGetLastError();
 }
 

@@ -61,6 +61,8 @@ int check_desc(const mebptt_lstm_desc* desc) {
   if (desc->gemm_dtype != 0 && desc->gemm_dtype != 1)
     return set_error(MEBPTT_EINVAL, "gemm_dtype must be 0 (fp32) or 1 (bf16)");
   if (desc->loss != 0 && desc->loss != 1) return set_error(MEBPTT_EINVAL, "loss must be 0 or 1");
+  if (desc->cell != MEBPTT_CELL_LSTM && desc->cell != MEBPTT_CELL_GRU)
+    return set_error(MEBPTT_EINVAL, "cell must be 0 (LSTM) or 1 (GRU) (got %d)", desc->cell);
   if (desc->loss == 0 && (desc->dy_first_step < 1 || desc->dy_first_step > desc->t))
     return set_error(MEBPTT_EINVAL, "dy_first_step must be in [1, t] (got %d)", desc->dy_first_step);
   if ((int64_t)desc->B * desc->H > (int64_t)1 << 28 || (int64_t)desc->H * 4 * ((int64_t)desc->I + desc->H) > (int64_t)1 << 31)
@@ -204,7 +206,7 @@ int mebptt_profile_collect(mebptt_profile* out) {
 
 size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc) {
   if (!desc || desc->B < 1 || desc->H < 1) return 0;
-  return make_dims(desc->B, 1, desc->H, desc->gemm_dtype ? 1 : 0).unit * sizeof(float);
+  return make_dims(desc->B, 1, desc->H, desc->gemm_dtype ? 1 : 0, 0).unit * sizeof(float);
 }
 
 size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan) {
@@ -215,7 +217,7 @@ size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t*
 
 size_t mebptt_workspace_bytes(const mebptt_lstm_desc* desc) {
   if (check_desc(desc) != MEBPTT_OK) return 0;
-  return layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype)).total;
+  return layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).total;
 }
 
 int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_t budget_bytes) {
@@ -242,7 +244,7 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   if (slots_bytes < mebptt_slot_pool_bytes(desc, plan))
     return set_error(MEBPTT_ENOMEM_SLOTS, "slot pool has %zu bytes, the plan needs %zu", slots_bytes,
                      mebptt_slot_pool_bytes(desc, plan));
-  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype);
+  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell);
   const Workspace w = layout(d);
   if (workspace_bytes < w.total)
     return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
@@ -435,9 +437,15 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
     if (rc) return rc;
   }
-  // dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
+  // LSTM: dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
+  // GRU:  dh_0 = dG_1 W_hh + dh_1 * z_1 (the running plane) ; there is no cell state: dc_0 = 0.
   HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));
-  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, st); }));
+  if (d.cell == MEBPTT_CELL_LSTM) {
+    HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, 0, st); }));
+  } else {
+    HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dh0, 1, st); }));
+    HIP_TRY(launch_copy_plane(d, dc, dc0, 2, st));
+  }
   for (int i = 0; i < 2; ++i)   // join: everything is ordered before whatever follows on `st`
     if (pending[i]) HIP_TRY(hipStreamWaitEvent(st, side->done[i], 0));
   HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {

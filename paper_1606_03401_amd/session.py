@@ -40,7 +40,7 @@ class Session:
         self.kind = w.kind if kind is None else kind
         self.m = w.m if m is None else m
         self.desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype if gemm_dtype is None else gemm_dtype, w.loss,
-                                 w.dy_first_step)
+                                 w.dy_first_step, w.cell)
         self.plan = plan if plan is not None else mb.mebptt_plan(w.t, self.m, self.kind, w.alpha, w.beta)
         dev = self.dev
         up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -48,9 +48,10 @@ class Session:
         self.h0 = None if pass_null_state else up(inp.h0)
         self.c0 = None if pass_null_state else up(inp.c0)
         f32 = dict(dtype=torch.float32, device=dev)
-        self.dW_ih = torch.empty((4 * w.H, w.I), **f32)
-        self.dW_hh = torch.empty((4 * w.H, w.H), **f32)
-        self.db = torch.empty((4 * w.H,), **f32)
+        gates, biases = (3, 6) if w.cell == mb.CELL_GRU else (4, 4)
+        self.dW_ih = torch.empty((gates * w.H, w.I), **f32)
+        self.dW_hh = torch.empty((gates * w.H, w.H), **f32)
+        self.db = torch.empty((biases * w.H,), **f32)
         self.dh0 = torch.empty((w.B, w.H), **f32)
         self.dc0 = torch.empty((w.B, w.H), **f32)
         self.dx = torch.empty((w.t, w.B, w.I), **f32) if want_dx else None

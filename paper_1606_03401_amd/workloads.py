@@ -22,6 +22,7 @@ import numpy as np
 KIND_HSM, KIND_ISM, KIND_MSM = 0, 1, 2
 GEMM_FP32, GEMM_BF16 = 0, 1
 LOSS_EXTERNAL_DY, LOSS_HALF_SUM_H2 = 0, 1
+CELL_LSTM, CELL_GRU = 0, 1
 
 
 @dataclasses.dataclass(frozen=True)
@@ -39,6 +40,7 @@ class Workload:
     alpha: int = 4               # MSM: units of an internal state with unknown input state
     beta: int = 3                # MSM: units of an internal state whose input state is known
     seed: int = 0
+    cell: int = 0                # CELL_LSTM or CELL_GRU
 
     def scaled(self, **kw) -> "Workload":
         return dataclasses.replace(self, **kw)
@@ -63,7 +65,7 @@ CFG5_BYTE_CAP = 4_000_000_000                   # "4 GB of HBM for checkpoints"
 
 @dataclasses.dataclass
 class Inputs:
-    W_ih: np.ndarray            # [4H, I]  float32, gate order i, f, g, o along the 4H axis
+    W_ih: np.ndarray            # [4H, I]  float32, gate order i, f, g, o along the 4H axis (GRU: [3H, I], r, z, n)
     W_hh: np.ndarray            # [4H, H]  float32
     b: np.ndarray               # [4H]     float32
     x: np.ndarray               # [t, B, I] float32
@@ -77,8 +79,10 @@ def make_inputs(w: Workload, *, nonzero_state: bool = False, nonzero_bias: bool 
     that must exercise those paths; the named configurations keep them zero."""
     rng = np.random.default_rng(w.seed)
     k = 1.0 / np.sqrt(w.H)
-    W_ih = rng.uniform(-k, k, size=(4 * w.H, w.I)).astype(np.float32)
-    W_hh = rng.uniform(-k, k, size=(4 * w.H, w.H)).astype(np.float32)
+    G = 3 if w.cell == CELL_GRU else 4          # gate blocks of the weight matrices
+    NB = 6 if w.cell == CELL_GRU else 4         # bias blocks: the GRU carries b_ih and b_hh
+    W_ih = rng.uniform(-k, k, size=(G * w.H, w.I)).astype(np.float32)
+    W_hh = rng.uniform(-k, k, size=(G * w.H, w.H)).astype(np.float32)
     x = rng.standard_normal(size=(w.t, w.B, w.I), dtype=np.float32)
     dy = None
     if w.loss == LOSS_EXTERNAL_DY:
@@ -91,7 +95,7 @@ def make_inputs(w: Workload, *, nonzero_state: bool = False, nonzero_bias: bool 
         h0 = np.zeros((w.B, w.H), np.float32)
         c0 = np.zeros((w.B, w.H), np.float32)
     if nonzero_bias:
-        b = rng.uniform(-k, k, size=(4 * w.H,)).astype(np.float32)
+        b = rng.uniform(-k, k, size=(NB * w.H,)).astype(np.float32)
     else:
-        b = np.zeros((4 * w.H,), np.float32)
+        b = np.zeros((NB * w.H,), np.float32)
     return Inputs(W_ih, W_hh, b, x, dy, h0, c0)

@@ -4,6 +4,7 @@ seeded inputs.  Tolerances (relative Frobenius error per output tensor):
 import numpy as np
 import pytest
 
+from oracle import gru_bptt as og
 from oracle import lstm_bptt as ob
 from oracle import policy_dp as dp
 from paper_1606_03401_amd import binding as mb
@@ -41,11 +42,20 @@ def check_against_oracle(w, inp, out, ref, tol, label=""):
     return worst
 
 
+def oracle_gradients(w, inp):
+    """The oracle for the workload's core; the GRU has no cell state, so dc0 is defined as zero."""
+    if w.cell == wl.CELL_GRU:
+        ref = og.gru_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.dy, w.dy_first_step)
+        ref.dc0 = np.zeros_like(ref.dh0)
+        return ref
+    return ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+
+
 def run_case(w, *, kind=None, m=None, nonzero=False, null_state=False, want_dx=True, ref=None, inp=None):
     from paper_1606_03401_amd.session import Session
     inp = inp if inp is not None else wl.make_inputs(w, nonzero_state=nonzero, nonzero_bias=nonzero)
     if ref is None:
-        ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+        ref = oracle_gradients(w, inp)
     kind = w.kind if kind is None else kind
     m = w.m if m is None else m
     s = Session(w, inp, kind=kind, m=m, want_dx=want_dx, pass_null_state=null_state)
@@ -76,6 +86,36 @@ def test_config1_every_budget_every_strategy():
                 first = out
             for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
                 assert np.array_equal(getattr(out, name), getattr(first, name)), (kind, m, name)
+
+
+@pytest.mark.parametrize("dtype", [wl.GEMM_FP32, wl.GEMM_BF16])
+def test_gru_core(dtype):
+    """A second core behind the same planner, executor and GEMM kernels (Section 1: the method is
+    architecture agnostic): parity with the float64 GRU oracle, for every strategy, and the same
+    bits whatever the budget."""
+    shapes = [(4, 16, 32, 20), (37, 50, 72, 9), (64, 40, 200, 12), (130, 100, 1000, 5), (1, 3, 5, 4)]
+    for B, I, H, t in shapes:
+        for loss, first in ((wl.LOSS_EXTERNAL_DY, 1), (wl.LOSS_EXTERNAL_DY, max(1, t - 2)), (wl.LOSS_HALF_SUM_H2, 1)):
+            w = wl.Workload("gru", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=3, gemm_dtype=dtype, loss=loss,
+                            dy_first_step=first, seed=300 + B, cell=wl.CELL_GRU)
+            inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+            ref = oracle_gradients(w, inp)
+            first_out = None
+            for kind, m in ((wl.KIND_HSM, 1), (wl.KIND_HSM, 3), (wl.KIND_HSM, t), (wl.KIND_ISM, 2), (wl.KIND_ISM, t),
+                            (wl.KIND_MSM, 6), (wl.KIND_MSM, 4 * t)):
+                out, _, _, _ = run_case(w, kind=kind, m=m, ref=ref, inp=inp)
+                assert not out.dc0.any()
+                if first_out is None:
+                    first_out = out
+                for name in ("dW_ih", "dW_hh", "db", "dh0", "dx", "y"):
+                    assert np.array_equal(getattr(out, name), getattr(first_out, name)), (B, H, kind, m, name)
+
+
+def test_gru_benchmark_shape():
+    """The benchmark's shape and budget with the GRU core (sequence shortened to what the float64
+    oracle does in seconds), which runs the large-K kernels and the fused launches."""
+    w = wl.CONFIGS["cfg2"].scaled(t=120, m=12, cell=wl.CELL_GRU, seed=22)
+    run_case(w)
 
 
 def test_chen_strategies_and_caller_policies():
