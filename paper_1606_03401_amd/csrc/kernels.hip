@@ -590,24 +590,44 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
 #pragma unroll
     for (int j = 0; j < BT; ++j)
       bbase[j] = reinterpret_cast<const T*>(p.dG_next) + ((size_t)min(by * BT + j, ntiles_b - 1) * nsteps * 64 + lane) * VEC;
-    for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-      typename M::Frag af[U][NT], bf[U][BT];
+    // This wave's macro steps are wave, wave + KS, ...: nw of them.  A ring of U fragment slots
+    // keeps U steps in flight from the first load to the last: slot u is refilled with the step U
+    // places further on as soon as its MFMAs are issued.  Steps are consumed in the same order
+    // as a plain loop would, so the sums are unchanged.  The main loop covers whole groups of U
+    // steps that all have a refill, so its body has no branches and the number of loads
+    // outstanding at every wait is known at compile time; the tail (at most two groups) is
+    // conditional.
+    const int nw = (nsteps - wave + KS - 1) / KS;
+    typename M::Frag af[U][NT], bf[U][BT];
+    auto load_slot = [&](int u, int j) {   // j: index into this wave's steps (always < nw here or clamped)
+      const size_t off = (size_t)min(wave + j * KS, nsteps - 1) * 64 * VEC;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) af[u][i] = M::load(abase[i] + off);
+#pragma unroll
+      for (int jj = 0; jj < BT; ++jj) bf[u][jj] = M::load(bbase[jj] + off);
+    };
+    auto mma_slot = [&](int u) {
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int jj = 0; jj < BT; ++jj) acc[i][jj] = M::mma(af[u][i], bf[u][jj], acc[i][jj]);
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_slot(u, u);   // surplus slots (u >= nw) hold a clamped copy and are never used
+    int j0 = 0;
+    for (; j0 + 2 * U <= nw; j0 += U) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const size_t off = (size_t)min(s0 + u * KS, nsteps - 1) * 64 * VEC;
-#pragma unroll
-        for (int i = 0; i < NT; ++i) af[u][i] = M::load(abase[i] + off);
-#pragma unroll
-        for (int j = 0; j < BT; ++j) bf[u][j] = M::load(bbase[j] + off);
+        mma_slot(u);
+        load_slot(u, j0 + u + U);
       }
+    }
+    for (; j0 < nw; j0 += U) {
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (s0 + u * KS < nsteps) {
-#pragma unroll
-          for (int i = 0; i < NT; ++i)
-#pragma unroll
-            for (int j = 0; j < BT; ++j) acc[i][j] = M::mma(af[u][i], bf[u][j], acc[i][j]);
-        }
+      for (int u = 0; u < U; ++u) {
+        if (j0 + u < nw) mma_slot(u);
+        if (j0 + u + U < nw) load_slot(u, j0 + u + U);
+      }
     }
 #pragma unroll
     for (int i = 0; i < NT; ++i)
