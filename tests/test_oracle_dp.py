@@ -223,6 +223,37 @@ def test_leftmost_tie_break():
             assert Di[t, m] == 1 + min(range(len(q)), key=lambda k: (q[k], k))
 
 
+@pytest.mark.parametrize("alpha,beta", [(4, 3), (4, 4), (2, 1), (6, 2)])
+def test_msm_splits_and_choice_rederived_by_scanning(alpha, beta):
+    """D1, D2, C1, C2 and H of BPTT-MSM re-derived cell by cell in plain Python from the finished
+    cost table (eq. 6-10): smallest minimising y for each kind of push, the hidden push on a tie."""
+    T, M = 40, 24
+    C, C1, C2, D1, D2, H = dp.msm_tables(T, M, alpha, beta)
+    INF = dp.INF
+
+    def c(t, m):
+        return INF if m < 0 else int(C[t, m])
+
+    for m in range(2, M + 1):
+        for t in range(2, T + 1):
+            q1 = [y + c(y, m) + c(t - y, m - 1) for y in range(1, t)]
+            q2 = [y + c(y - 1, m) + c(t - y, m - (beta if y == 1 else alpha)) for y in range(1, t + 1)]
+            b1, b2 = min(q1), min(q2)
+            if b1 < INF:
+                assert C1[t, m] == b1 and D1[t, m] == 1 + q1.index(b1)
+            else:
+                assert C1[t, m] >= INF
+            if b2 < INF:
+                assert C2[t, m] == b2 and D2[t, m] == 1 + q2.index(b2)
+            else:
+                assert C2[t, m] >= INF
+            if min(b1, b2) < INF:
+                assert C[t, m] == min(b1, b2)
+                assert H[t, m] == (1 if b1 <= b2 else 2)
+            else:
+                assert H[t, m] == 0
+
+
 def test_small_cases_quoted_in_the_paper():
     """Fig. 3 shows (t=4, m=4) and (t=10, m=4); the appendix checks (t=3, m=2) and (t=3, m=3)
     against the bound numerically."""
