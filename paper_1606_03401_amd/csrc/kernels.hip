@@ -537,6 +537,7 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
   constexpr int NTILE = NT * BT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
   const int ntiles_n = p.HP / 16, ntiles_b = p.BP / 16;
   // Epilogue pieces of this wave: piece id = tile * 4 + r, tile = tn * BT + tb.  Their pointwise
@@ -706,16 +707,19 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
 // do not depend on whether a step was fused.
 constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 2, PAIR_BKS = 8, PAIR_BU = 8;
 
-template <class T, int CELL>
-__global__ __launch_bounds__(64 * PAIR_BKS, 4) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf, int nbx) {
-  __shared__ float red[forward_red_floats(PAIR_NG, 1, PAIR_FKS)];
-  static_assert(forward_red_floats(PAIR_NG, 1, PAIR_FKS) >= PAIR_BKS * 4 * 64 && PAIR_FKS == PAIR_BKS,
-                "shared buffer and block size cover both roles");
+// Roles of one fused launch: forward tile FNG x 1 split over FKS waves, backward tile BNT x BBT over
+// BKS waves (the K splits of the stand-alone kernels of the same shape class; FU and BU, the
+// loads in flight, may be smaller than theirs to stay within the register bound).
+template <class T, int CELL, int FNG, int FKS, int FU, int BNT, int BBT, int BKS, int BU>
+__global__ __launch_bounds__(64 * (FKS > BKS ? FKS : BKS), 4) void pair_kernel(FwdParams f, BwdParams b, int nfx, int nf,
+                                                                             int nbx) {
+  constexpr int FRED = forward_red_floats(FNG, 1, FKS), BRED = BKS * BNT * BBT * 4 * 64;
+  __shared__ float red[FRED > BRED ? FRED : BRED];
   const int id = blockIdx.x;
   if (id < nf)
-    forward_body<T, PAIR_NG, 1, PAIR_FKS, PAIR_FU, CELL>(f, id % nfx, id / nfx, red);
+    forward_body<T, FNG, 1, FKS, FU, CELL>(f, id % nfx, id / nfx, red);
   else
-    backward_body<T, 1, 1, PAIR_BKS, PAIR_BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
+    backward_body<T, BNT, BBT, BKS, BU>(b, (id - nf) % nbx, (id - nf) / nbx, red);
 }
 
 // Kernel configurations by shape.  Tiles per workgroup grow with the problem so that the grid
@@ -856,9 +860,30 @@ hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st)
   return d.dtype ? launch_backward_t<__bf16>(d, p, st) : launch_backward_t<float>(d, p, st);
 }
 
-bool can_fuse_pair(const Dims& d) {
-  return d.dtype ? (forward_config<__bf16>(d) == FWD_B1 && backward_config<__bf16>(d) == BWD_11)
-                 : (forward_config<float>(d) == FWD_B1 && backward_config<float>(d) == BWD_11);
+// Shape classes for which a fused launch is instantiated: 1 = large K (forward 4 x 1, backward
+// 1 x 1, 8 waves each); 2 = small-K forward (4 waves) with the 1 x 2 backward (8 waves).  0 = none.
+template <class T>
+static int pair_class(const Dims& d) {
+  const FwdConfig fc = forward_config<T>(d);
+  const BwdConfig bc = backward_config<T>(d);
+  if (fc == FWD_B1 && bc == BWD_11) return 1;
+  if (fc == FWD_SMALLK && bc == BWD_12) return 2;
+  return 0;
+}
+
+bool can_fuse_pair(const Dims& d) { return (d.dtype ? pair_class<__bf16>(d) : pair_class<float>(d)) != 0; }
+
+template <class T, int CELL>
+static void launch_pair_t(const Dims& d, const FwdParams& f, const BwdParams& b, hipStream_t st) {
+  const int nfx = (d.HP / 4 + PAIR_NG - 1) / PAIR_NG, nfy = d.BP / 16;   // both classes: forward 4 x 1
+  if (pair_class<T>(d) == 1) {
+    const int nbx = d.HP / 16, nby = d.BP / 16;
+    pair_kernel<T, CELL, PAIR_NG, PAIR_FKS, PAIR_FU, 1, 1, PAIR_BKS, PAIR_BU>
+        <<<dim3(nfx * nfy + nbx * nby), dim3(64 * PAIR_BKS), 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+  } else {
+    const int nbx = d.HP / 16, nby = (d.BP / 16 + 1) / 2;
+    pair_kernel<T, CELL, 4, 4, 2, 1, 2, 8, 4><<<dim3(nfx * nfy + nbx * nby), dim3(512), 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+  }
 }
 
 hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, const void* Wp, const float* bp,
@@ -866,13 +891,10 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
                                         hipStream_t st) {
   BwdParams b = make_bwd_params(d, a);
   FwdParams f = make_fwd_params(d, Wp, bp, x_s, src_unit, dst_unit, gates_units);
-  const int nfx = (d.HP / 4 + PAIR_NG - 1) / PAIR_NG, nfy = d.BP / 16;
-  const int nbx = d.HP / 16, nby = d.BP / 16;
-  dim3 grid(nfx * nfy + nbx * nby), block(64 * PAIR_BKS);
   if (d.dtype)
-    (d.cell ? pair_kernel<__bf16, 1> : pair_kernel<__bf16, 0>)<<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+    d.cell ? launch_pair_t<__bf16, 1>(d, f, b, st) : launch_pair_t<__bf16, 0>(d, f, b, st);
   else
-    (d.cell ? pair_kernel<float, 1> : pair_kernel<float, 0>)<<<grid, block, 0, st>>>(f, b, nfx, nfx * nfy, nbx);
+    d.cell ? launch_pair_t<float, 1>(d, f, b, st) : launch_pair_t<float, 0>(d, f, b, st);
   return hipGetLastError();
 }
 

@@ -331,6 +331,25 @@ def test_large_k_shapes_every_budget_bit_identical(dtype):
                 assert np.array_equal(getattr(out, name), getattr(first, name)), (kind, m, name)
 
 
+def test_small_k_fused_launches_bit_identical():
+    """The second shape class with fused launches (small-K forward kernel, 1 x 2 backward kernel:
+    config 4's shape, ragged here): every strategy and several budgets against the oracle and bit
+    for bit against each other, for both cores."""
+    for cell in (wl.CELL_LSTM, wl.CELL_GRU):
+        w = wl.Workload("smallk", B=250, I=120, H=500, t=12, kind=wl.KIND_HSM, m=3, gemm_dtype=wl.GEMM_BF16,
+                        loss=wl.LOSS_EXTERNAL_DY, dy_first_step=2, seed=78, cell=cell)
+        inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+        ref = oracle_gradients(w, inp)
+        first = None
+        for kind, budgets in ((wl.KIND_HSM, [1, 2, 3, 12]), (wl.KIND_ISM, [1, 3, 12]), (wl.KIND_MSM, [2, 5, 9, 48])):
+            for m in budgets:
+                out, _, _, _ = run_case(w, kind=kind, m=m, ref=ref, inp=inp)
+                if first is None:
+                    first = out
+                for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+                    assert np.array_equal(getattr(out, name), getattr(first, name)), (cell, kind, m, name)
+
+
 def test_graph_replay_matches_eager():
     """A run captured into a HIP graph: several replays, with eager runs, output clobbering and
     synchronisations in between, must each reproduce the eager result bit for bit."""
