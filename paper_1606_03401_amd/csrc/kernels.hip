@@ -1058,7 +1058,13 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
   const int MT = G4 / 16, NT = NTOT / 16;
   const int mt_wg = blockIdx.x * 2 * WT, nt_wg = blockIdx.y * 2 * WT;
   const int ncs = KC / KSTEP;    // macro steps per row tile in the fragment-tiled operands
-  const int nk = K / KSTEP;      // macro steps that hold data
+  // gridDim.z workgroups share one output tile, each taking a contiguous part of the macro steps
+  // that hold data and keeping its own partial accumulator (summed, in a fixed order, by
+  // wgrad_finish_kernel).  A part may be empty (short last chunk): it then only initialises or
+  // keeps its partial sum.
+  const int nk_all = K / KSTEP;
+  const int k_begin = (int)((long long)nk_all * blockIdx.z / gridDim.z);
+  const int nk = (int)((long long)nk_all * (blockIdx.z + 1) / gridDim.z) - k_begin;
   // this thread copies blocks q*4 + wave, q = 0..WT-1: the first 2*WT blocks are dGT row tiles,
   // the other 2*WT are aT row tiles
   const T* src[WT];
@@ -1066,9 +1072,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
   for (int q = 0; q < WT; ++q) {
     const int blk = q * 4 + wave;
     if (blk < 2 * WT)
-      src[q] = dGT + ((size_t)min(mt_wg + blk, MT - 1) * ncs * 64 + lane) * VEC;
+      src[q] = dGT + (((size_t)min(mt_wg + blk, MT - 1) * ncs + k_begin) * 64 + lane) * VEC;
     else
-      src[q] = aT + ((size_t)min(nt_wg + blk - 2 * WT, NT - 1) * ncs * 64 + lane) * VEC;
+      src[q] = aT + (((size_t)min(nt_wg + blk - 2 * WT, NT - 1) * ncs + k_begin) * 64 + lane) * VEC;
   }
   u32x4 ring[PD][WT];
   auto fetch = [&](int stage, int ks) {
@@ -1087,6 +1093,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
 #pragma unroll
     for (int j = 0; j < WT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  if (nk > 0) {   // uniform over the workgroup
 #pragma unroll
   for (int st = 0; st < PD; ++st) fetch(st, st);
   stash(0, 0);
@@ -1112,13 +1119,14 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
       __syncthreads();
     }
   }
+  }
 
   // Epilogue: the running sum lives in a tile-ordered accumulator (each wave's quarter is one
   // contiguous run, a lane's four accumulator rows one float4), so the
   // read-modify-write of every chunk is fully coalesced; wgrad_finish_kernel converts it to the
   // caller's row-major dW once at the end of the run.
   float4* accp = reinterpret_cast<float4*>(dWacc) +
-                 ((size_t)(blockIdx.x * gridDim.y + blockIdx.y) * 4 + wave) * (WT * WT) * 64 + lane;
+                 (((size_t)blockIdx.z * gridDim.x * gridDim.y + blockIdx.x * gridDim.y + blockIdx.y) * 4 + wave) * (WT * WT) * 64 + lane;
   if (accumulate) {
     float4 old[WT * WT];
 #pragma unroll
@@ -1140,9 +1148,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
 // The accumulator's column NX + HP (operand row of ones) holds the bias gradient.  ngates = 4
 // (LSTM: db [4H]) or 3 (GRU: db = [db_ih | db_hh], 6H); the packed row of a gate block differs
 // between the input and the recurrent side for the GRU (packed_gate_x / packed_gate_h).
-__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int NX, int HP, int I, int H,
-                                    int cell, float* __restrict__ dW_ih, float* __restrict__ dW_hh,
-                                    float* __restrict__ db) {
+__global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int nsplit, size_t split_stride,
+                                    int NX, int HP, int I, int H, int cell, float* __restrict__ dW_ih,
+                                    float* __restrict__ dW_hh, float* __restrict__ db) {
   const int ngates = cell ? 3 : 4;
   const size_t nih = (size_t)ngates * H * I, nhh = (size_t)ngates * H * H, nb = (size_t)(cell ? 6 : 4) * H;
   const size_t total = nih + nhh + nb;
@@ -1179,28 +1187,39 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int
     const int wgy = nt / (2 * WT), wn = (nt % (2 * WT)) / WT, jj = nt % WT;
     const size_t off =
         ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * (WT * WT) + (i * WT + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
-    *dst = dWacc[off];
+    float v = dWacc[off];
+    for (int sp = 1; sp < nsplit; ++sp) v += dWacc[(size_t)sp * split_stride + off];   // partial sums, fixed order
+    *dst = v;
   }
 }
 
-// Wave tile of the weight-gradient GEMM: 4 x 4 MFMA tiles when that still gives the chip enough
-// workgroups, else 2 x 2.
+// Wave tile of the weight-gradient GEMM (4 x 4 MFMA tiles, 128 x 128 per workgroup, whenever the
+// output has at least one such tile in each direction; else 2 x 2) and the number of workgroups
+// that split K for one output tile: enough to give the chip about 1.5 workgroups per compute unit
+// when the output alone has too few tiles (long chunks of small matrices).
 static int wgrad_wave_tile(const Dims& d) {
   const int MT = d.G4 / 16, NT = d.NA / 16;
-  return ((MT + 7) / 8) * ((NT + 7) / 8) >= 200 ? 4 : 2;
+  return (MT >= 8 && NT >= 8) ? 4 : 2;
 }
-
-size_t wgrad_accumulator_bytes(const Dims& d) {
+static int wgrad_splits(const Dims& d) {
+  const int WT = wgrad_wave_tile(d);
+  const int tiles = ((d.G4 / 16 + 2 * WT - 1) / (2 * WT)) * ((d.NA / 16 + 2 * WT - 1) / (2 * WT));
+  const int s = (384 + tiles / 2) / tiles;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+static size_t wgrad_partial_floats(const Dims& d) {   // one partial accumulator
   const int WT = wgrad_wave_tile(d);
   const size_t gx = (d.G4 / 16 + 2 * WT - 1) / (2 * WT), gy = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
-  return gx * gy * 4 * WT * WT * 64 * sizeof(float4);
+  return gx * gy * 4 * WT * WT * 64 * 4;
 }
+
+size_t wgrad_accumulator_bytes(const Dims& d) { return wgrad_partial_floats(d) * wgrad_splits(d) * sizeof(float); }
 
 template <class T>
 static void launch_wgrad_t(const Dims& d, const void* dGT, const void* aT, int K, int accumulate, float* dWacc,
                            hipStream_t st) {
   const int NTOT = d.NA, WT = wgrad_wave_tile(d);
-  dim3 grid((d.G4 / 16 + 2 * WT - 1) / (2 * WT), (NTOT / 16 + 2 * WT - 1) / (2 * WT)), block(256);
+  dim3 grid((d.G4 / 16 + 2 * WT - 1) / (2 * WT), (NTOT / 16 + 2 * WT - 1) / (2 * WT), wgrad_splits(d)), block(256);
   if (WT == 4)
     wgrad_kernel<T, 4><<<grid, block, 0, st>>>((const T*)dGT, (const T*)aT, K, d.KC, d.G4, NTOT, accumulate, dWacc);
   else
@@ -1222,7 +1241,8 @@ hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, 
                                hipStream_t st) {
   const int WT = wgrad_wave_tile(d);
   const int grid_y = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
-  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, d.NX, d.HP, d.I, d.H, d.cell, dW_ih, dW_hh, db);
+  wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, wgrad_splits(d), wgrad_partial_floats(d), d.NX, d.HP,
+                                                        d.I, d.H, d.cell, dW_ih, dW_hh, db);
   return hipGetLastError();
 }
 
