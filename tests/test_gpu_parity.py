@@ -215,6 +215,11 @@ def test_error_paths_launch_nothing():
         mb.mebptt_run(s.desc, other, s.W_ih, s.W_hh, s.b, s.x, s.dy, s.h0, s.c0, s.slots, s.workspace,
                       s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0)
     assert e.value.code == mb.ESHAPE
+    bad = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype, w.loss, 1, cell=7)
+    with pytest.raises(mb.MebpttError) as e:
+        mb.mebptt_run(bad, s.plan, s.W_ih, s.W_hh, s.b, s.x, s.dy, s.h0, s.c0, s.slots, s.workspace,
+                      s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0)
+    assert e.value.code == mb.EINVAL
     torch.cuda.synchronize()
     assert bool((s.dW_ih == 7.0).all())
 
@@ -335,8 +340,8 @@ def test_small_k_fused_launches_bit_identical():
     """The second shape class with fused launches (small-K forward kernel, 1 x 2 backward kernel:
     config 4's shape, ragged here): every strategy and several budgets against the oracle and bit
     for bit against each other, for both cores."""
-    for cell in (wl.CELL_LSTM, wl.CELL_GRU):
-        w = wl.Workload("smallk", B=250, I=120, H=500, t=12, kind=wl.KIND_HSM, m=3, gemm_dtype=wl.GEMM_BF16,
+    for cell, B in ((wl.CELL_LSTM, 250), (wl.CELL_GRU, 250), (wl.CELL_LSTM, 230)):   # 230: odd number of batch tiles
+        w = wl.Workload("smallk", B=B, I=120, H=500, t=12, kind=wl.KIND_HSM, m=3, gemm_dtype=wl.GEMM_BF16,
                         loss=wl.LOSS_EXTERNAL_DY, dy_first_step=2, seed=78, cell=cell)
         inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
         ref = oracle_gradients(w, inp)
