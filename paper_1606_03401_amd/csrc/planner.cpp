@@ -162,7 +162,11 @@ void solve_ism(int t, int m, Tables& T) {
       int64_t best;
       int arg;
       // column 0 is infinite for t > 0, so the convexity argument starts with column 2
-      if (convex && mm >= 2 && tt >= 2) {
+      if (mm == 1) {
+        // a single slot: with C(t', 0) infinite for t' > 0, y = t is the only finite term of the scan
+        best = (int64_t)tt + cm[tt - 1];
+        arg = tt;
+      } else if (convex && tt >= 2) {
         auto Q = [&](int y) { return (int64_t)y + cm[y - 1] + cm1[tt - y]; };
         convex_first_argmin(Q, 1, tt, D[mm][tt - 1], best, arg);
       } else {

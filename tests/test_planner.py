@@ -175,6 +175,21 @@ def test_long_sequence_tables_match_the_plain_recurrence(kind):
     _assert_tables_equal(plan, kind, tabs)
 
 
+@pytest.mark.parametrize("kind", [mb.HSM, mb.ISM])
+def test_planning_stays_interactive_at_1e5_steps(kind):
+    """The range of the paper's numerical bound check (appendix: t up to 10^5).  The tables of this
+    size are beyond the oracle's triple loop; what is checked is the replay of the schedule, the
+    count against the table, and the appendix's upper bound C <= m t^(1+1/m)."""
+    import time
+    t, m = 100000, 100
+    t0 = time.perf_counter()
+    plan = mb.mebptt_plan(t, m, kind)
+    assert time.perf_counter() - t0 < 30.0
+    assert plan.forward_ops == plan.cost()[t, m]
+    assert plan.forward_ops <= m * t ** (1.0 + 1.0 / m)
+    assert check_schedule(plan, t, m, kind) == plan.forward_ops
+
+
 def test_constant_memory_is_run_length_encoded():
     plan = mb.mebptt_plan(2000, 1, mb.HSM)
     assert plan.forward_ops == 2000 * 2001 // 2
