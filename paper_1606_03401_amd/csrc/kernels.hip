@@ -1044,7 +1044,8 @@ hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, v
 // fragments of its block (1 KiB each, already in fragment order) from HBM/L2 into LDS with fully
 // coalesced 16-byte loads -- fetched PD macro steps ahead through a ring of registers -- and every
 // wave reads the WT + WT fragments it needs from LDS, so each operand byte crosses the L2 fabric
-// once per workgroup instead of once per wave.
+// once per workgroup instead of once per wave.  gridDim.z workgroups may share one output block,
+// each with its own part of K and its own partial accumulator.
 template <class T, int WT>
 __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, const T* __restrict__ aT, int K, int KC,
                                                     int G4, int NTOT, int accumulate, float* __restrict__ dWacc) {
