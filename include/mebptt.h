@@ -151,6 +151,53 @@ int32_t mebptt_plan_peak(const mebptt_plan_t* plan);
 /* The flat schedule; *n receives the number of entries. */
 const mebptt_op* mebptt_plan_schedule(const mebptt_plan_t* plan, size_t* n);
 
+/* ---- non-homogeneous chains (planning only) ----------------------------------------------------
+ * Appendix "Generalizing to deep feed-forward networks": the policy for a linear chain whose
+ * layers differ in forward cost u_i, output size s_i and working-memory size p_i (memory in
+ * arbitrary integer units; the network input is always available and not counted).
+ *   C(t, m, x) = cost of back-propagating through layers x+1 .. x+t with m free units when the
+ *                input of layer x+1 is available;  Q = U(x,y) + K(x,y,m) + C(t-y, m-s_{x+y}, x+y)
+ *                + C(y, m, x), 1 <= y < t;  D = smallest minimising y.
+ * Readings: one layer costs u if p fits; at every node the sub-chain may also be processed
+ * without memorising anything (re-run from its input before each backward step), recorded as
+ * D = 0; a tie goes to the memorisation.  With u = s = 1, p = 0 this is BPTT-HSM with the start
+ * state outside the budget.  There is no GPU executor for such chains in this library: the plan,
+ * its tables and its schedule are the product. */
+typedef struct {
+  int64_t cost;        /* u_i >= 1 */
+  int32_t state_units; /* s_i >= 1: size of the layer's output */
+  int32_t work_units;  /* p_i >= 0: memory a forward or backward operation of the layer needs */
+} mebptt_layer;
+typedef struct mebptt_chain_plan_s mebptt_chain_plan_t;
+enum { MEBPTT_CHAIN_FORWARD = 1, MEBPTT_CHAIN_BACKWARD = 2 };
+enum { MEBPTT_CHAIN_INPUT = -1, MEBPTT_CHAIN_WORKING = -2 };
+/* FORWARD:  `count` layers layer .. layer+count-1 from the state at `src` (unit offset in the pool
+ *           of m units, MEBPTT_CHAIN_INPUT, or MEBPTT_CHAIN_WORKING); the last output is memorised
+ *           at unit offset `dst`, or stays in working memory (MEBPTT_CHAIN_WORKING).
+ * BACKWARD: one backward operation of `layer`, whose input state is at `src`.  Backward entries
+ *           come in the order n, n-1, ..., 1. */
+typedef struct {
+  int32_t op;
+  int32_t layer;
+  int32_t count;
+  int32_t src;
+  int32_t dst;
+} mebptt_chain_op;
+/* Solves the program for every sub-chain and every m' <= m and flattens the policy of the whole
+ * chain.  `layers` (host, n entries) is copied.  Errors: EINVAL, EINFEASIBLE (some layer cannot
+ * run in m units), ENOMEM_HOST (the table has (n+1)(n+2)/2 x (m+1) cells). */
+int mebptt_chain_plan(const mebptt_layer* layers, int32_t n, int32_t m, mebptt_chain_plan_t** out);
+void mebptt_chain_plan_free(mebptt_chain_plan_t* plan);
+/* C(t, m', x) and D(t, m', x) for 0 <= t, x + t <= n, m' <= m (MEBPTT_COST_INF / 0 outside or if
+ * infeasible; m' < 0 is infeasible). */
+int64_t mebptt_chain_cost(const mebptt_chain_plan_t* plan, int32_t t, int32_t m, int32_t x);
+int32_t mebptt_chain_split(const mebptt_chain_plan_t* plan, int32_t t, int32_t m, int32_t x);
+/* Forward cost summed over the schedule (= C(n, m, 0)) and the high-water mark of memorised
+ * outputs plus working memory while it runs (<= m). */
+int64_t mebptt_chain_plan_forward_cost(const mebptt_chain_plan_t* plan);
+int32_t mebptt_chain_plan_peak(const mebptt_chain_plan_t* plan);
+const mebptt_chain_op* mebptt_chain_plan_schedule(const mebptt_chain_plan_t* plan, size_t* n);
+
 /* ---- LSTM execution ---------------------------------------------------------------------- */
 
 typedef struct {

@@ -40,6 +40,18 @@ class mebptt_decision(C.Structure):
 STORE_HIDDEN, STORE_INTERNAL = 1, 2
 
 
+class mebptt_layer(C.Structure):
+    _fields_ = [("cost", C.c_int64), ("state_units", C.c_int32), ("work_units", C.c_int32)]
+
+
+class mebptt_chain_op(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("op", "layer", "count", "src", "dst")]
+
+
+CHAIN_FORWARD, CHAIN_BACKWARD = 1, 2
+CHAIN_INPUT, CHAIN_WORKING = -1, -2
+
+
 class mebptt_lstm_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "I", "H", "t", "gemm_dtype", "loss", "dy_first_step", "cell")]
 
@@ -72,6 +84,13 @@ SIGNATURES = {
     "mebptt_plan_chen_sqrt": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
     "mebptt_plan_chen_recursive": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
     "mebptt_plan_free": (None, [_P]),
+    "mebptt_chain_plan": (C.c_int, [C.POINTER(mebptt_layer), C.c_int32, C.c_int32, C.POINTER(_P)]),
+    "mebptt_chain_plan_free": (None, [_P]),
+    "mebptt_chain_cost": (C.c_int64, [_P, C.c_int32, C.c_int32, C.c_int32]),
+    "mebptt_chain_split": (C.c_int32, [_P, C.c_int32, C.c_int32, C.c_int32]),
+    "mebptt_chain_plan_forward_cost": (C.c_int64, [_P]),
+    "mebptt_chain_plan_peak": (C.c_int32, [_P]),
+    "mebptt_chain_plan_schedule": (C.POINTER(mebptt_chain_op), [_P, C.POINTER(C.c_size_t)]),
     "mebptt_plan_cost": (C.POINTER(C.c_int64), [_P, C.c_int32]),
     "mebptt_plan_split": (C.POINTER(C.c_int32), [_P, C.c_int32]),
     "mebptt_plan_choice": (C.POINTER(C.c_uint8), [_P]),
@@ -187,6 +206,49 @@ def mebptt_plan(t: int, m: int, kind: int, alpha: int = 4, beta: int = 3) -> Pla
     out = _P()
     _check(lib().mebptt_plan(t, m, kind, alpha, beta, C.byref(out)))
     return Plan(out.value)
+
+
+class ChainPlan:
+    """Owner of a ``mebptt_chain_plan_t*`` (non-homogeneous chain; planning only)."""
+
+    def __init__(self, handle: int, n: int, m: int):
+        self.handle, self.n, self.m = handle, n, m
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.mebptt_chain_plan_free(self.handle)
+            self.handle = None
+
+    def cost(self, t: int, m: int, x: int) -> int:
+        return lib().mebptt_chain_cost(self.handle, t, m, x)
+
+    def split(self, t: int, m: int, x: int) -> int:
+        return lib().mebptt_chain_split(self.handle, t, m, x)
+
+    @property
+    def forward_cost(self) -> int:
+        return lib().mebptt_chain_plan_forward_cost(self.handle)
+
+    @property
+    def peak(self) -> int:
+        return lib().mebptt_chain_plan_peak(self.handle)
+
+    def schedule(self) -> np.ndarray:
+        n = C.c_size_t(0)
+        ptr = lib().mebptt_chain_plan_schedule(self.handle, C.byref(n))
+        dt = np.dtype([(f, np.int32) for f, _ in mebptt_chain_op._fields_])
+        if n.value == 0:
+            return np.zeros(0, dt)
+        raw = np.ctypeslib.as_array(C.cast(ptr, C.POINTER(C.c_int32)), shape=(n.value, 5))
+        return raw.copy().view(dt).reshape(n.value)
+
+
+def mebptt_chain_plan(layers, m: int) -> ChainPlan:
+    """`layers`: sequence of (cost, state_units, work_units)."""
+    arr = (mebptt_layer * max(len(layers), 1))(*[mebptt_layer(int(u), int(s), int(p)) for u, s, p in layers])
+    out = _P()
+    _check(lib().mebptt_chain_plan(arr, len(layers), m, C.byref(out)))
+    return ChainPlan(out.value, len(layers), m)
 
 
 def mebptt_plan_from_policy(t: int, m: int, decisions, alpha: int = 4, beta: int = 3) -> Plan:
