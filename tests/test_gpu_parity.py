@@ -182,6 +182,22 @@ def test_ragged_shapes(B, I, H, t, kind, m, dtype):
         run_case(w, nonzero=True)
 
 
+@pytest.mark.parametrize("dtype", [wl.GEMM_FP32, wl.GEMM_BF16])
+def test_tile_boundary_shapes(dtype):
+    """Shapes on and next to the tile edges of every operand layout (16-row tiles, 32-wide macro
+    steps, 4-unit groups), for both cores: one forward step of slack in any index computation
+    would show here."""
+    shapes = [(16, 32, 32, 3), (17, 33, 33, 3), (15, 31, 31, 3), (16, 1, 16, 2), (32, 64, 48, 3), (31, 17, 47, 3),
+              (48, 96, 96, 2), (1, 40, 64, 3), (2, 16, 17, 3), (64, 8, 8, 2)]
+    for B, I, H, t in shapes:
+        if dtype == wl.GEMM_BF16 and B * H < 64:
+            continue                      # too few elements for a relative bound on bf16 rounding
+        for cell in (wl.CELL_LSTM, wl.CELL_GRU):
+            w = wl.Workload("edge", B=B, I=I, H=H, t=t, kind=wl.KIND_MSM, m=5, gemm_dtype=dtype,
+                            loss=wl.LOSS_EXTERNAL_DY, dy_first_step=1, seed=500 + B + H, cell=cell)
+            run_case(w, nonzero=True)
+
+
 def test_null_state_and_bias_and_no_dx():
     w = wl.CONFIGS["cfg1"].scaled(loss=wl.LOSS_EXTERNAL_DY)
     out, _, _, _ = run_case(w, null_state=True, want_dx=False)
