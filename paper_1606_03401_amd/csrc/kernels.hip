@@ -767,7 +767,7 @@ static hipError_t launch_forward_t(const Dims& d, const FwdParams& p, hipStream_
   switch (forward_config<T>(d)) {
     case FWD_TINY: return launch_forward_cfg<T, 1, 1, 4, 2>(d, p, st);   // tiny K: one small workgroup per tile
     case FWD_SMALLK: return launch_forward_cfg<T, 4, 1, 4, 5>(d, p, st);
-    case FWD_82: return launch_forward_cfg<T, 8, 2, 8, 2>(d, p, st);
+    case FWD_82: return launch_forward_cfg<T, 8, 2, 8, 1>(d, p, st);
     case FWD_42: return launch_forward_cfg<T, 4, 2, 8, 3>(d, p, st);
     default: return launch_forward_cfg<T, PAIR_NG, 1, PAIR_FKS, 5>(d, p, st);
   }
