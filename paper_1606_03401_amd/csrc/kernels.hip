@@ -705,7 +705,7 @@ __global__ __launch_bounds__(64 * KS) void backward_kernel(BwdParams p) {
 // the same time and the 2 x 256 workgroups of a launch run as one wave of work, not two.  Each role splits K over the
 // same number of waves as its stand-alone kernel, so sums are formed in the same order and results
 // do not depend on whether a step was fused.
-constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 1, PAIR_BKS = 8, PAIR_BU = 8, PAIR_BU_FUSED = 4;
+constexpr int PAIR_FKS = 8, PAIR_NG = 4, PAIR_FU = 1, PAIR_BKS = 8, PAIR_BU = 4;
 
 // Roles of one fused launch: forward tile FNG x 1 split over FKS waves, backward tile BNT x BBT over
 // BKS waves (the K splits of the stand-alone kernels of the same shape class).  FU and BU, the
@@ -880,7 +880,7 @@ static void launch_pair_t(const Dims& d, const FwdParams& f, const BwdParams& b,
   const int nfx = (d.HP / 4 + PAIR_NG - 1) / PAIR_NG, nfy = d.BP / 16;   // both classes: forward 4 x 1
   if (pair_class<T>(d) == 1) {
     const int nbx = d.HP / 16, nby = d.BP / 16;
-    pair_kernel<T, CELL, PAIR_NG, PAIR_FKS, PAIR_FU, 1, 1, PAIR_BKS, PAIR_BU_FUSED>
+    pair_kernel<T, CELL, PAIR_NG, PAIR_FKS, PAIR_FU, 1, 1, PAIR_BKS, PAIR_BU>
         <<<dim3(nfx * nfy + nbx * nby), dim3(64 * PAIR_BKS), 0, st>>>(f, b, nfx, nfx * nfy, nbx);
   } else {
     const int nbx = d.HP / 16, nby = (d.BP / 16 + 1) / 2;
