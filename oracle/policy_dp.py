@@ -7,9 +7,10 @@ Each function writes the recurrences of the paper out directly, cell by cell, in
 notation:  C(t, m) = optimal number of forward operations for back-propagating through a
 sequence of length t with m memory slots; D(t, m) = position of the first state to memorise.
 
-  * BPTT-HSM  (Section 3.1, eq. 1-3; Algorithm 1 in the appendix)
+  * BPTT-HSM  (Section 3.1, eq. 1-3)
         Q(t,m,y) = y + C(t-y, m-1) + C(y, m),           D = argmin over 1 <= y <  t
-        C(t,1) = t(t+1)/2,  C(t,m) = 2t-1 and D = 1 for m >= t,  C(1,m) = 1.
+        base cases C(t,1) = t(t+1)/2 and C(1,m) = 1; the boundary C(t,m) = 2t-1, D = 1 for
+        m >= t that the section quotes follows from the recurrence.
   * BPTT-ISM  (Section 3.2, eq. 4-5)
         Q(t,m,y) = y + C(y-1, m) + C(t-y, m-1),         D = argmin over 1 <= y <= t
         single base case C(0,m) = 0 (m >= 0); C(t,0) = infinity for t > 0.  The boundaries the
@@ -25,7 +26,6 @@ Readings where the text is silent or inconsistent:
     "<" comparison produces; H prefers the hidden branch on a tie (argmin over i = 1, 2 in order).
   * the appendix prints C(t,1) = t(t+2)/2 once; the body and Algorithm 1 say t(t+1)/2, which is
     also what the constant-memory procedure of Section 3 costs.  t(t+1)/2 is used.
-  * Algorithm 1's first loop is printed over "r" while its body uses t; it is a loop over t.
   * MSM: Section 3.3 gives "C = infinity for m <= 0" and "C(0, m) = 0" which collide at
     (0, m <= 0), and states no t = 1 base case.  Used here: C(0,m) = 0 for m >= 0, infinity
     for m < 0; C(t,0) = infinity for t > 0; C(1,m) = 1 for m >= 1 (the HSM base case);
@@ -49,23 +49,31 @@ def _clip(c):
 
 
 def hsm_tables(t_max: int, m_max: int):
-    """BPTT-HSM cost and policy tables (Section 3.1, eq. 1-3, Algorithm 1)."""
+    """BPTT-HSM cost and policy tables: eq. 1-3 applied to every cell the boundary conditions of
+    Section 3.1 do not fix.
+
+    Boundaries (Section 3.1): C(t, 1) = t(t+1)/2 -- with one slot every backward step re-forwards
+    from the start state -- and C(1, m) = 1, the single forward operation of a one-step sequence
+    (the m >= t boundary C = 2t - 1 at t = 1).  Every other cell is the recurrence
+        C(t, m) = min over 1 <= y < t of  y + C(y, m) + C(t - y, m - 1)
+    with D(t, m) the smallest minimiser.  The section's second boundary, C(t, m) = 2t - 1 with
+    D = 1 for all m >= t, is not imposed: it follows (y = 1 gives 1 + 1 + 2(t-1) - 1), and the tests
+    pin it.  D(1, m) = 1 is the value the section's boundary assigns where no split exists."""
     assert t_max >= 1 and m_max >= 1
     C = np.full((t_max + 1, m_max + 1), INF, dtype=np.int64)
     D = np.zeros((t_max + 1, m_max + 1), dtype=np.int32)
-    C[0, :] = 0                                   # empty sequence: nothing to do (Algorithm 2, t = 0)
-    for t in range(1, t_max + 1):
-        C[t, 1] = t * (t + 1) // 2                # minimal memory: re-forward from the start each time
-        for m in range(t, m_max + 1):             # memory is plentiful
-            C[t, m] = 2 * t - 1
-            D[t, m] = 1
+    C[0, :] = 0                                       # empty sequence: nothing to do
+    tt = np.arange(1, t_max + 1, dtype=np.int64)
+    C[1:, 1] = tt * (tt + 1) // 2
+    C[1, 1:] = 1
+    D[1, 1:] = 1
     for m in range(2, m_max + 1):
-        for t in range(m + 1, t_max + 1):
-            y = np.arange(1, t, dtype=np.int64)   # 1 <= y < t
-            Q = y + C[y, m] + C[t - y, m - 1]
-            k = int(np.argmin(Q))                 # first minimum = smallest y
-            C[t, m] = _clip(Q[k])
-            D[t, m] = y[k]
+        for t in range(2, t_max + 1):
+            y = np.arange(1, t, dtype=np.int64)       # 1 <= y < t
+            Q = y + C[y, m] + C[t - y, m - 1]         # eq. 1
+            k = int(np.argmin(Q))                     # first minimum = smallest y
+            C[t, m] = _clip(Q[k])                     # eq. 2
+            D[t, m] = y[k]                            # eq. 3
     return C, D
 
 
