@@ -216,18 +216,23 @@ enum { MEBPTT_CELL_LSTM = 0, MEBPTT_CELL_GRU = 1 };
 typedef struct {
   int64_t forward_ops;    /* forward operations launched (== C(t, m))   */
   int64_t backward_ops;   /* backward operations launched (== t)        */
-  int32_t peak;           /* as mebptt_plan_peak                        */
+  int32_t peak;           /* highest slot occupied by any launch, in budget units (<= m) */
   int32_t reserved;
-  size_t peak_slot_bytes; /* peak * bytes per budget unit               */
+  size_t peak_slot_bytes; /* the same high-water mark in bytes of the slot pool          */
 } mebptt_stats;
 
-/* Bytes of one unit: a hidden state (h, c) in fp32 = 2 * B * H * 4. */
+/* Bytes of one unit: a hidden state (h, c) (Definition 2) in fp32 = 2 * B * H * 4. */
 size_t mebptt_unit_bytes(const mebptt_lstm_desc* desc);
-/* Bytes of the slot pool for this plan: m budget units (ISM: m slots of four units). */
+/* Bytes of the slot pool for this plan.  A memory slot (Definition 4) holds one hidden state
+ * (HSM; MSM counts in these units) or one internal state with its input state (ISM: four
+ * units); the pool is the plan's m slots and nothing else -- this is the budget of Section 3. */
 size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan);
-/* Bytes of workspace: working core, transients, running gradients, operand copies of the
- * weights and bounded staging for the time-batched weight-gradient GEMM.  Independent of t
- * and of the budget. */
+/* Bytes of workspace, the memory outside the budget.  Section 3.1 grants the method "a single
+ * RNN core available for intermediate calculations, able to store a single internal state":
+ * that is the working core and the two transient hidden states here.  The rest is what this
+ * implementation adds around it: operand copies of the weights in the GEMM type, the running
+ * gradients, a dW accumulator, and staging of dG / [x; h] for the steps of two chunks of the
+ * time-batched weight-gradient GEMM.  Independent of t and of the budget. */
 size_t mebptt_workspace_bytes(const mebptt_lstm_desc* desc);
 /* Largest budget, in the given kind's unit, whose slot pool fits in budget_bytes (0 if none). */
 int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_t budget_bytes);
@@ -251,6 +256,18 @@ int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_
  * host, write:   stats (may be NULL); filled before the call returns.
  * stream:        a hipStream_t (NULL = the default stream).  The call only enqueues work; results
  *                are valid once the caller has synchronised the stream.
+ * stats:         forward_ops and backward_ops count the launches made; peak is the highest slot
+ *                unit any launch of this run was handed (rounded up to budget units), tracked by
+ *                the executor while it walks the schedule -- it equals mebptt_plan_peak().
+ *
+ * Library-owned resources.  The time-batched dW and dx GEMMs of finished chunks run on a second,
+ * non-blocking HIP stream of default priority that the library creates on the first run on a
+ * device, with four events to fork from and join back into `stream` (no host synchronisation:
+ * the whole call can be captured into a HIP graph).  They live until mebptt_shutdown().  Because
+ * they are shared, a process-wide mutex serialises the ENQUEUE phase of concurrent mebptt_run
+ * calls (any thread, any stream); the device work of two runs on different streams, slot pools
+ * and workspaces may overlap.  The measurement hooks below use process-wide state and must not
+ * be toggled while another thread is inside a run.
  * Errors: EINVAL, ESHAPE, ENOMEM_SLOTS, EWORKSPACE, EHIP. */
 int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
                const float* W_ih, const float* W_hh, const float* b,
@@ -258,6 +275,30 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
                void* slots, size_t slots_bytes, void* workspace, size_t workspace_bytes,
                float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
                float* dx, float* y_out, mebptt_stats* stats, void* stream);
+
+/* The same gradient step in two calls, for weights that stay unchanged over several runs (e.g.
+ * several sequences per optimiser step).  mebptt_prepare builds the operand copies of the
+ * weights (GEMM type, gate-interleaved, transposed for the backward GEMMs) and clears the staging
+ * inside `workspace`; mebptt_run_prepared then runs any number of gradient steps of that shape
+ * (B, I, H, gemm_dtype, cell; t, loss and the plan may change) on it without repeating that work.
+ * mebptt_run == mebptt_prepare + mebptt_run_prepared.  The library remembers on the host which
+ * workspace pointers were prepared for which shape and refuses others (EWORKSPACE); it cannot
+ * see the caller overwrite the workspace or change the weights -- prepare again after either.
+ * Arguments, ownership and stream semantics are those of mebptt_run.
+ * Errors: as mebptt_run. */
+int mebptt_prepare(const mebptt_lstm_desc* desc, const float* W_ih, const float* W_hh, const float* b,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
+                        const float* x, const float* dy, const float* h0, const float* c0,
+                        void* slots, size_t slots_bytes, void* workspace, size_t workspace_bytes,
+                        float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
+                        float* dx, float* y_out, mebptt_stats* stats, void* stream);
+
+/* Releases what the library created on every device: the side streams and their events, the
+ * events of the measurement hooks, the record of prepared workspaces.  Waits for the side
+ * streams first; the caller makes sure no run is being enqueued.  The library can be used again
+ * afterwards (resources are re-created on demand).  Errors: EHIP. */
+int mebptt_shutdown(void);
 
 /* ---- measurement hooks ---------------------------------------------------------------------
  * Kernel classes of the hot path, for timing with HIP events on the run's own stream. */
@@ -287,6 +328,11 @@ int mebptt_profile_enable(int32_t every_n);
 /* Waits for the recorded events, writes the sums since the last collect (host memory) and
  * clears them.  Errors: EINVAL, EHIP. */
 int mebptt_profile_collect(mebptt_profile* out);
+
+/* Average time, in microseconds, of `launches` back-to-back empty kernel launches on `stream`
+ * (host memory out_us), bracketed by one event pair: the floor every dependent launch of the
+ * sequential chain pays on this machine.  Synchronises the stream.  Errors: EINVAL, EHIP. */
+int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us);
 
 const char* mebptt_last_error(void);
 /* Library version string, e.g. "mebptt 0.1 (gfx950)". */

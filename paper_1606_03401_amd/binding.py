@@ -106,6 +106,11 @@ SIGNATURES = {
     "mebptt_units_for_bytes": (C.c_int32, [_DESC, C.c_int32, C.c_size_t]),
     "mebptt_run": (C.c_int, [_DESC, _P] + [_P] * 7 + [_P, C.c_size_t, _P, C.c_size_t] + [_P] * 7
                    + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_prepare": (C.c_int, [_DESC] + [_P] * 3 + [_P, C.c_size_t, _P]),
+    "mebptt_run_prepared": (C.c_int, [_DESC, _P] + [_P] * 4 + [_P, C.c_size_t, _P, C.c_size_t] + [_P] * 7
+                            + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_shutdown": (C.c_int, []),
+    "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
     "mebptt_profile_collect": (C.c_int, [C.POINTER(mebptt_profile)]),
     "mebptt_last_error": (C.c_char_p, []),
@@ -326,3 +331,41 @@ def mebptt_run(desc: mebptt_lstm_desc, plan: Plan, W_ih, W_hh, b, x, dy, h0, c0,
                           _ptr(dc0), _ptr(dx), _ptr(y_out), C.byref(stats), stream)
     _check(rc)
     return stats
+
+
+def _stream(stream: Optional[int]) -> int:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return stream
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def mebptt_prepare(desc: mebptt_lstm_desc, W_ih, W_hh, b, workspace, stream: Optional[int] = None) -> None:
+    """Builds the operand copies of the weights inside `workspace` (see mebptt_run_prepared)."""
+    _check(lib().mebptt_prepare(C.byref(desc), _ptr(W_ih), _ptr(W_hh), _ptr(b), _ptr(workspace), _nbytes(workspace),
+                                _stream(stream)))
+
+
+def mebptt_run_prepared(desc: mebptt_lstm_desc, plan: Plan, x, dy, h0, c0, slots, workspace, dW_ih, dW_hh, db, dh0,
+                        dc0, dx=None, y_out=None, stream: Optional[int] = None) -> mebptt_stats:
+    """mebptt_run on a workspace that mebptt_prepare has filled for these weights."""
+    stats = mebptt_stats()
+    _check(lib().mebptt_run_prepared(C.byref(desc), plan.handle, _ptr(x), _ptr(dy), _ptr(h0), _ptr(c0), _ptr(slots),
+                                     _nbytes(slots), _ptr(workspace), _nbytes(workspace), _ptr(dW_ih), _ptr(dW_hh),
+                                     _ptr(db), _ptr(dh0), _ptr(dc0), _ptr(dx), _ptr(y_out), C.byref(stats),
+                                     _stream(stream)))
+    return stats
+
+
+def mebptt_shutdown() -> None:
+    _check(lib().mebptt_shutdown())
+
+
+def mebptt_null_launch_us(launches: int = 2000, stream: Optional[int] = None) -> float:
+    out = C.c_double(0.0)
+    _check(lib().mebptt_null_launch_us(launches, _stream(stream), C.byref(out)))
+    return out.value

@@ -99,6 +99,9 @@ hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* d
 // x of `nslots` consecutive steps -> rows [0,NX) of aT, and ones into row NX+HP for the same columns.
 hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, void* aT, hipStream_t st);
 
+// Zeroes columns [c0, c1) of every row of the two weight-gradient operands dGT and aT (c1 <= KC).
+hipError_t launch_zero_operand_columns(const Dims& d, void* dGT, void* aT, int c0, int c1, hipStream_t st);
+
 // Tile-ordered running sum of [dW | db] (+)= dGT * aT^T over K = nslots*B columns.
 // launch_wgrad_finish writes the caller's row-major dW_ih, dW_hh and db from it.
 size_t wgrad_accumulator_bytes(const Dims& d);

@@ -1038,6 +1038,34 @@ hipError_t launch_transpose_x(const Dims& d, const float* x_first, int nslots, v
   return hipGetLastError();
 }
 
+// Zeroes columns [c0, c1) of the two weight-gradient operands (dGT: G4 rows, aT: NA rows).
+template <class T>
+__global__ void zero_operand_columns_kernel(T* __restrict__ dGT, int G4, T* __restrict__ aT, int NA, int KC, int c0, int c1) {
+  const int ncols = c1 - c0, ncs = KC / (4 * Mma<T>::VEC);
+  const size_t total = (size_t)(G4 + NA) * ncols;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int row = (int)(i / ncols), col = c0 + (int)(i % ncols);
+    if (row < G4)
+      dGT[ft_offset<T>(row, col, ncs)] = (T)0.0f;
+    else
+      aT[ft_offset<T>(row - G4, col, ncs)] = (T)0.0f;
+  }
+}
+
+hipError_t launch_zero_operand_columns(const Dims& d, void* dGT, void* aT, int c0, int c1, hipStream_t st) {
+  if (c1 <= c0) return hipSuccess;
+  if (c0 < 0 || c1 > d.KC) return hipErrorInvalidValue;
+  const size_t total = (size_t)(d.G4 + d.NA) * (c1 - c0);
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  if (d.dtype)
+    zero_operand_columns_kernel<__bf16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>((__bf16*)dGT, d.G4, (__bf16*)aT, d.NA, d.KC, c0, c1);
+  else
+    zero_operand_columns_kernel<float><<<dim3((unsigned)blocks), dim3(256), 0, st>>>((float*)dGT, d.G4, (float*)aT, d.NA, d.KC, c0, c1);
+  return hipGetLastError();
+}
+
 // ---- weight-gradient GEMM: dW[row(m)][n] (+)= sum_k dGT[m][k] * aT[n][k] ------------------------
 
 // A workgroup of 2 x 2 waves owns a block of 2*WT x 2*WT MFMA tiles of dW (128 x 128 elements for

@@ -12,6 +12,7 @@
 // the budget or the policy -- and gradients are bit-identical for every budget.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -120,19 +121,23 @@ hipError_t timed(int cls, hipStream_t st, F&& launch) {
 // The weight-gradient and dx GEMMs of a finished chunk do not feed the sequential chain, so they
 // run on a second stream (default priority) while the main stream carries on with the next
 // steps.  Fork/join is by events only, so a caller may capture the whole run in a HIP graph.
+// One such stream and four events exist per device, created by the first mebptt_run on that
+// device and destroyed by mebptt_shutdown; g_run_mutex serialises the enqueue of runs because
+// they share them.
+constexpr int MAX_DEVICES = 16;
 struct SideStream {
   hipStream_t stream = nullptr;
   hipEvent_t full[2] = {nullptr, nullptr};   // main -> side: chunk buffer is complete
   hipEvent_t done[2] = {nullptr, nullptr};   // side -> main: chunk buffer may be overwritten
 };
-SideStream g_side[16];
+SideStream g_side[MAX_DEVICES];
 std::mutex g_run_mutex;
 
 hipError_t get_side_stream(SideStream** out) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
   SideStream& s = g_side[dev];
   if (!s.stream) {
     e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking);
@@ -148,11 +153,53 @@ hipError_t get_side_stream(SideStream** out) {
   return hipSuccess;
 }
 
+// ---- workspaces that mebptt_prepare has filled ---------------------------------------------------
+// Host-side record only (the device memory is the caller's): which workspace holds the operand
+// copies of which weights for which shape, so that mebptt_run_prepared can refuse a workspace
+// that was never prepared or was prepared for another shape.
+struct Prepared {
+  const void* workspace;
+  int B, I, H, dtype, cell;
+};
+std::vector<Prepared> g_prepared;
+std::mutex g_prepared_mutex;
+
+void remember_prepared(const void* ws, const Dims& d) {
+  std::lock_guard<std::mutex> lock(g_prepared_mutex);
+  for (Prepared& p : g_prepared)
+    if (p.workspace == ws) {
+      p = Prepared{ws, d.B, d.I, d.H, d.dtype, d.cell};
+      return;
+    }
+  if (g_prepared.size() >= 64) g_prepared.erase(g_prepared.begin());   // oldest record goes
+  g_prepared.push_back(Prepared{ws, d.B, d.I, d.H, d.dtype, d.cell});
+}
+
+bool is_prepared(const void* ws, const Dims& d) {
+  std::lock_guard<std::mutex> lock(g_prepared_mutex);
+  for (const Prepared& p : g_prepared)
+    if (p.workspace == ws) return p.B == d.B && p.I == d.I && p.H == d.H && p.dtype == d.dtype && p.cell == d.cell;
+  return false;
+}
+
+__global__ void null_kernel() {}
+
 #define HIP_TRY(expr)                                                                                 \
   do {                                                                                                \
     hipError_t e_ = (expr);                                                                           \
     if (e_ != hipSuccess) return set_error(MEBPTT_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
+
+enum RunMode {
+  RUN_FULL,       // operand copies of the weights are built inside the call
+  RUN_PREPARED,   // mebptt_prepare has built them in this workspace
+  RUN_STATIC      // as RUN_FULL, on one stream, with nothing created or allocated
+};
+
+int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih,
+             const float* W_hh, const float* b, const float* x, const float* dy, const float* h0, const float* c0,
+             void* slots, size_t slots_bytes, void* workspace, size_t workspace_bytes, float* dW_ih, float* dW_hh,
+             float* db, float* dh0, float* dc0, float* dx, float* y_out, mebptt_stats* stats, void* stream);
 
 }  // namespace
 
@@ -231,13 +278,126 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
                const float* b, const float* x, const float* dy, const float* h0, const float* c0, void* slots,
                size_t slots_bytes, void* workspace, size_t workspace_bytes, float* dW_ih, float* dW_hh, float* db,
                float* dh0, float* dc0, float* dx, float* y_out, mebptt_stats* stats, void* stream) {
+  return run_impl(RUN_FULL, desc, plan, W_ih, W_hh, b, x, dy, h0, c0, slots, slots_bytes, workspace, workspace_bytes,
+                  dW_ih, dW_hh, db, dh0, dc0, dx, y_out, stats, stream);
+}
+
+int mebptt_prepare(const mebptt_lstm_desc* desc, const float* W_ih, const float* W_hh, const float* b, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!W_ih || !W_hh) return set_error(MEBPTT_EINVAL, "a required device pointer is NULL");
+  if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
+  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell);
+  const Workspace w = layout(d);
+  if (workspace_bytes < w.total)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  if (misaligned(workspace, ALIGN)) return set_error(MEBPTT_EWORKSPACE, "workspace must be 256-byte aligned");
+  if (misaligned(W_ih, 16) || misaligned(W_hh, 16) || (b && misaligned(b, 16)))
+    return set_error(MEBPTT_EINVAL, "device arrays must be 16-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  std::lock_guard<std::mutex> lock(g_run_mutex);   // the measurement hooks' state is shared with runs
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] {
+    return launch_prep_weights(d, W_ih, W_hh, b, ws + w.Wp, reinterpret_cast<float*>(ws + w.bp), ws + w.WTh, ws + w.WTx, st);
+  }));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
+  remember_prepared(workspace, d);
+  return MEBPTT_OK;
+}
+
+int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* x, const float* dy,
+                        const float* h0, const float* c0, void* slots, size_t slots_bytes, void* workspace,
+                        size_t workspace_bytes, float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0, float* dx,
+                        float* y_out, mebptt_stats* stats, void* stream) {
+  return run_impl(RUN_PREPARED, desc, plan, nullptr, nullptr, nullptr, x, dy, h0, c0, slots, slots_bytes, workspace,
+                  workspace_bytes, dW_ih, dW_hh, db, dh0, dc0, dx, y_out, stats, stream);
+}
+
+int mebptt_shutdown(void) {
+  std::lock_guard<std::mutex> lock(g_run_mutex);
+  int rc = MEBPTT_OK;
+  auto drop = [&](hipError_t e) {
+    if (e != hipSuccess) rc = set_error(MEBPTT_EHIP, "releasing a library resource failed: %s", hipGetErrorString(e));
+  };
+  int cur = 0;
+  const bool have_dev = hipGetDevice(&cur) == hipSuccess;
+  for (int dev = 0; dev < MAX_DEVICES; ++dev) {
+    SideStream& s = g_side[dev];
+    if (!s.stream) continue;
+    drop(hipSetDevice(dev));
+    drop(hipStreamSynchronize(s.stream));
+    for (int i = 0; i < 2; ++i) {
+      if (s.full[i]) drop(hipEventDestroy(s.full[i]));
+      if (s.done[i]) drop(hipEventDestroy(s.done[i]));
+    }
+    drop(hipStreamDestroy(s.stream));
+    s = SideStream{};
+  }
+  if (have_dev) drop(hipSetDevice(cur));
+  Profiler& p = g_prof;
+  for (Sample& sm : p.pending) {
+    p.pool.push_back(sm.start);
+    p.pool.push_back(sm.stop);
+  }
+  for (Sample& sm : p.runs) {
+    p.pool.push_back(sm.start);
+    p.pool.push_back(sm.stop);
+  }
+  p.pending.clear();
+  p.runs.clear();
+  for (hipEvent_t e : p.pool)
+    if (e) drop(hipEventDestroy(e));
+  p.pool.clear();
+  p.every_n = 0;
+  {
+    std::lock_guard<std::mutex> lk(g_prepared_mutex);
+    g_prepared.clear();
+  }
+  return rc;
+}
+
+int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us) {
+  if (launches < 1 || launches > 100000) return set_error(MEBPTT_EINVAL, "launches must be in [1, 100000]");
+  if (!out_us) return set_error(MEBPTT_EINVAL, "out_us is NULL");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipEvent_t a = nullptr, z = nullptr;
+  HIP_TRY(hipEventCreate(&a));
+  hipError_t e = hipEventCreate(&z);
+  if (e == hipSuccess) {
+    for (int i = 0; i < 16; ++i) null_kernel<<<dim3(256), dim3(256), 0, st>>>();   // warm-up
+    e = hipEventRecord(a, st);
+  }
+  if (e == hipSuccess) {
+    for (int i = 0; i < launches; ++i) null_kernel<<<dim3(256), dim3(256), 0, st>>>();
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(z, st);
+  if (e == hipSuccess) e = hipEventSynchronize(z);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, z);
+  (void)hipEventDestroy(a);
+  if (z) (void)hipEventDestroy(z);
+  if (e != hipSuccess) return set_error(MEBPTT_EHIP, "null-launch timing failed: %s", hipGetErrorString(e));
+  *out_us = (double)ms * 1e3 / launches;
+  return MEBPTT_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih,
+             const float* W_hh, const float* b, const float* x, const float* dy, const float* h0, const float* c0,
+             void* slots, size_t slots_bytes, void* workspace, size_t workspace_bytes, float* dW_ih, float* dW_hh,
+             float* db, float* dh0, float* dc0, float* dx, float* y_out, mebptt_stats* stats, void* stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (!plan) return set_error(MEBPTT_EINVAL, "plan is NULL");
   if (plan->t != desc->t) return set_error(MEBPTT_ESHAPE, "plan is for t=%d, descriptor says t=%d", plan->t, desc->t);
   if (plan->ops.empty()) return set_error(MEBPTT_EINVAL, "plan carries no LSTM schedule (tables only)");
-  if (!W_ih || !W_hh || !x || !dW_ih || !dW_hh || !db || !dh0 || !dc0)
-    return set_error(MEBPTT_EINVAL, "a required device pointer is NULL");
+  if (mode != RUN_PREPARED && (!W_ih || !W_hh)) return set_error(MEBPTT_EINVAL, "a required device pointer is NULL");
+  if (!x || !dW_ih || !dW_hh || !db || !dh0 || !dc0) return set_error(MEBPTT_EINVAL, "a required device pointer is NULL");
   if (desc->loss == 0 && !dy) return set_error(MEBPTT_EINVAL, "dy is NULL but loss == 0");
   if (!slots) return set_error(MEBPTT_ENOMEM_SLOTS, "slots is NULL");
   if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
@@ -253,6 +413,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   const void* f32ptrs[] = {W_ih, W_hh, b, x, dy, h0, c0, dW_ih, dW_hh, db, dh0, dc0, dx, y_out};
   for (const void* p : f32ptrs)
     if (p && misaligned(p, 16)) return set_error(MEBPTT_EINVAL, "device arrays must be 16-byte aligned");
+  if (mode == RUN_PREPARED && !is_prepared(workspace, d))
+    return set_error(MEBPTT_EWORKSPACE, "workspace was not prepared for this shape: call mebptt_prepare first");
 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* ws = reinterpret_cast<char*>(workspace);
@@ -271,7 +433,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
       default: return nullptr;
     }
   };
-  const int64_t pool_units = (int64_t)plan->m * (plan->kind == MEBPTT_ISM ? 4 : 1);
+  const int units_per_budget = plan->kind == MEBPTT_ISM ? 4 : 1;
+  const int64_t pool_units = (int64_t)plan->m * units_per_budget;
   // Host-side check of every location before anything is enqueued.
   for (const mebptt_op& op : plan->ops) {
     const int32_t locs[3] = {op.src, op.dst, op.prev};
@@ -284,6 +447,13 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     }
     if (op.step < 1 || op.step + op.count - 1 > desc->t) return set_error(MEBPTT_EINVAL, "schedule step out of range");
   }
+  // Slot units the launches of this run are handed, as the executor hands them out: the highest
+  // unit index (+ span) among all state arguments.  This, not the planner's simulation, is what
+  // the statistics report as the peak.
+  int64_t high_water = 0;
+  auto touch = [&](int32_t l, int span) {
+    if (l >= 0) high_water = std::max<int64_t>(high_water, (int64_t)l + span);
+  };
 
   float* bp = reinterpret_cast<float*>(ws + w.bp);
   float* dc = reinterpret_cast<float*>(ws + w.dc);
@@ -291,24 +461,47 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   void* WTh = ws + w.WTh;
   void* WTx = ws + w.WTx;
   const size_t op_b = d.op_bytes();
+  const int t = desc->t, CH = d.CH;
+  const bool use_profiler = mode != RUN_STATIC;   // event brackets create events: not in the no-allocation path
+  auto tm = [&](int cls, hipStream_t s, auto&& launch) -> hipError_t {
+    return use_profiler ? timed(cls, s, launch) : launch();
+  };
+
+  std::lock_guard<std::mutex> lock(g_run_mutex);   // side stream, events, profiler and static scratch are shared
 
   // Set-up: operand copies of the weights, zeroed staging (the padding must stay zero), start state.
-  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st); }));
-  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
-  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] {
+  if (mode != RUN_PREPARED) {
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st); }));
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
+  } else {
+    // The staging keeps what the previous run left.  Only the running gradient plane must start
+    // at zero, and -- when the last chunk in time is short and its K is padded -- the operand
+    // columns between its last step and the padded K, which a full chunk of the previous run
+    // filled.
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.dG[0] - w.dc, st); }));
+    const int last_chunk = (t - 1) / CH, nslots = t - last_chunk * CH;
+    const int cols = nslots * d.B, kstep = d.dtype ? 32 : 16;
+    if (cols % kstep != 0)
+      HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] {
+        return launch_zero_operand_columns(d, ws + w.dGT[last_chunk & 1], ws + w.aT[last_chunk & 1], cols,
+                                           round_up(cols, kstep), st);
+      }));
+  }
+  HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] {
     return launch_init_state(d, h0, c0, plan->kind == MEBPTT_ISM ? loc(MEBPTT_LOC_INIT) : loc(0), st);
   }));
+  if (plan->kind != MEBPTT_ISM) touch(0, 1);
 
-  std::lock_guard<std::mutex> lock(g_run_mutex);   // the side stream and its events are shared
+  // The time-batched GEMMs go to the side stream, or -- in the no-allocation path, which creates
+  // no stream and no event -- stay on the caller's stream in the same order.
   SideStream* side = nullptr;
-  HIP_TRY(get_side_stream(&side));
-  hipStream_t st2 = side->stream;
+  if (mode != RUN_STATIC) HIP_TRY(get_side_stream(&side));
+  hipStream_t st2 = side ? side->stream : st;
   bool pending[2] = {false, false};   // side-stream work on chunk buffer i not yet joined
   int cur_chunk = -1;
 
   int64_t fwd = 0, bwd = 0;
   bool first_chunk = true;
-  const int t = desc->t, CH = d.CH;
   const size_t dG_step = (size_t)d.BP * d.G4 * op_b;   // bytes of one step inside a dG chunk buffer
   const bool fuse = can_fuse_pair(d);
 
@@ -322,34 +515,38 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   // time-batched work of its chunk if the step completed one.
   auto flush_backward = [&](const float* x_s, const float* f_src, float* f_dst, float* f_gates) -> int {
     if (x_s) {
-      HIP_TRY(timed(MEBPTT_K_PAIR, st, [&] {
+      HIP_TRY(tm(MEBPTT_K_PAIR, st, [&] {
         return launch_backward_forward_pair(d, pend, Wp, bp, x_s, f_src, f_dst, f_gates, st);
       }));
       ++fwd;
     } else {
-      HIP_TRY(timed(MEBPTT_K_BACKWARD, st, [&] { return launch_backward(d, pend, st); }));
+      HIP_TRY(tm(MEBPTT_K_BACKWARD, st, [&] { return launch_backward(d, pend, st); }));
     }
     ++bwd;
     have_pending = false;
     const int s = pend_step;
     const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
-    if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx on the side stream
+    if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
       const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
       const size_t x_off = (size_t)chunk * CH * d.B * d.I;
-      HIP_TRY(hipEventRecord(side->full[buf], st));
-      HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
-      HIP_TRY(timed(MEBPTT_K_WGRAD, st2, [&] {
+      if (side) {
+        HIP_TRY(hipEventRecord(side->full[buf], st));
+        HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
+      }
+      HIP_TRY(tm(MEBPTT_K_WGRAD, st2, [&] {
         hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
         if (e != hipSuccess) return e;
         return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1,
                             reinterpret_cast<float*>(ws + w.dWacc), st2);
       }));
       if (dx)
-        HIP_TRY(timed(MEBPTT_K_DGRAD, st2, [&] {
+        HIP_TRY(tm(MEBPTT_K_DGRAD, st2, [&] {
           return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
         }));
-      HIP_TRY(hipEventRecord(side->done[buf], st2));
-      pending[buf] = true;
+      if (side) {
+        HIP_TRY(hipEventRecord(side->done[buf], st2));
+        pending[buf] = true;
+      }
       first_chunk = false;
     }
     return MEBPTT_OK;
@@ -359,9 +556,12 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
     if (op.op == MEBPTT_OP_FWD_RUN) {
       if (op.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
       const float* cur = loc(op.src);
+      touch(op.src, 1);
+      touch(op.dst, op.keep ? 3 : 1);
+      if (op.count > 1) touch(op.prev, 1);
       // Measurement hook: one event pair around the back-to-back launches of a long run (all but
       // its first step, which may share a launch with a backward step).
-      const bool bracket = g_prof.every_n > 0 && op.count >= 9 && g_prof.runs.size() < 100000;
+      const bool bracket = use_profiler && g_prof.every_n > 0 && op.count >= 9 && g_prof.runs.size() < 100000;
       Sample run_sample{MEBPTT_K_FORWARD, nullptr, nullptr, op.count - 1};
       for (int j = 1; j <= op.count; ++j) {
         if (bracket && j == 2) {
@@ -391,7 +591,7 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
           rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
           if (rc) return rc;
         }
-        HIP_TRY(timed(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_s, cur, dst, gates, st); }));
+        HIP_TRY(tm(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_s, cur, dst, gates, st); }));
         cur = dst;
         ++fwd;
       }
@@ -414,6 +614,8 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
         }
         cur_chunk = chunk;
       }
+      touch(op.dst, 3);
+      touch(op.src, 1);
       pend = BackwardArgs{};
       pend.WTh = WTh;
       pend.dG_next = (s == t) ? nullptr : ws + w.dG[(s / CH) & 1] + (size_t)(s % CH) * dG_step;
@@ -439,27 +641,27 @@ int mebptt_run(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const fl
   }
   // LSTM: dh_0 = dG_1 W_hh ; dc_0 is the running cell gradient after step 1.
   // GRU:  dh_0 = dG_1 W_hh + dh_1 * z_1 (the running plane) ; there is no cell state: dc_0 = 0.
-  HIP_TRY(timed(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));
+  HIP_TRY(tm(MEBPTT_K_DGRAD, st, [&] { return launch_dgrad_gemm(d, WTh, d.H, ws + w.dG[0], 1, dh0, d.H, st); }));
   if (d.cell == MEBPTT_CELL_LSTM) {
-    HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, 0, st); }));
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dc0, 0, st); }));
   } else {
-    HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dh0, 1, st); }));
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_copy_plane(d, dc, dh0, 1, st); }));
     HIP_TRY(launch_copy_plane(d, dc, dc0, 2, st));
   }
   for (int i = 0; i < 2; ++i)   // join: everything is ordered before whatever follows on `st`
     if (pending[i]) HIP_TRY(hipStreamWaitEvent(st, side->done[i], 0));
-  HIP_TRY(timed(MEBPTT_K_WGRAD, st, [&] {
+  HIP_TRY(tm(MEBPTT_K_WGRAD, st, [&] {
     return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, db, st);
   }));
 
   if (stats) {
     stats->forward_ops = fwd;
     stats->backward_ops = bwd;
-    stats->peak = plan->peak;
+    stats->peak = (int32_t)((high_water + units_per_budget - 1) / units_per_budget);
     stats->reserved = 0;
-    stats->peak_slot_bytes = (size_t)plan->peak * mebptt_unit_bytes(desc) * (plan->kind == MEBPTT_ISM ? 4 : 1);
+    stats->peak_slot_bytes = (size_t)high_water * mebptt_unit_bytes(desc);
   }
   return MEBPTT_OK;
 }
 
-}  // extern "C"
+}  // namespace

@@ -32,7 +32,8 @@ class Session:
 
     def __init__(self, w: Workload, inp: Inputs, *, kind: Optional[int] = None, m: Optional[int] = None,
                  gemm_dtype: Optional[int] = None, want_dx: bool = True, want_y: bool = True,
-                 pass_null_state: bool = False, device: str = "cuda:0", plan: Optional[mb.Plan] = None):
+                 pass_null_state: bool = False, device: str = "cuda:0", plan: Optional[mb.Plan] = None,
+                 guard_bytes: int = 0, fill_byte: int = 0xFF):
         if not torch.cuda.is_available():
             raise RuntimeError("mebptt needs a GPU: no HIP device is visible")
         self.w = w
@@ -58,14 +59,31 @@ class Session:
         self.y = torch.empty((w.t, w.B, w.H), **f32) if want_y else None
         self.slot_bytes = mb.mebptt_slot_pool_bytes(self.desc, self.plan)
         self.ws_bytes = mb.mebptt_workspace_bytes(self.desc)
-        # 0xFF bytes are NaNs as float32: stale memory can never pass for a valid result
-        self.slots = torch.full((self.slot_bytes,), 0xFF, dtype=torch.uint8, device=dev)
-        self.workspace = torch.full((self.ws_bytes,), 0xFF, dtype=torch.uint8, device=dev)
+        # 0xFF bytes are NaNs as float32: stale memory can never pass for a valid result.  With
+        # guard_bytes > 0 (a multiple of 256) the pool and the workspace are interior views of larger
+        # buffers filled with the same byte, so that a test can see any write outside them.
+        if guard_bytes % 256:
+            raise ValueError("guard_bytes must be a multiple of 256")
+        self.guard_bytes, self.fill_byte = guard_bytes, fill_byte
+        self.slots_outer = torch.full((self.slot_bytes + 2 * guard_bytes,), fill_byte, dtype=torch.uint8, device=dev)
+        self.slots = self.slots_outer[guard_bytes:guard_bytes + self.slot_bytes]
+        self.workspace_outer = torch.full((self.ws_bytes + 2 * guard_bytes,), fill_byte, dtype=torch.uint8, device=dev)
+        self.workspace = self.workspace_outer[guard_bytes:guard_bytes + self.ws_bytes]
+        self.prepared = False
 
     def run(self, stream: Optional[int] = None) -> mb.mebptt_stats:
+        if self.prepared:
+            return mb.mebptt_run_prepared(self.desc, self.plan, self.x, self.dy, self.h0, self.c0, self.slots,
+                                          self.workspace, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
+                                          self.dx, self.y, stream)
         return mb.mebptt_run(self.desc, self.plan, self.W_ih, self.W_hh, self.b, self.x, self.dy, self.h0, self.c0,
                              self.slots, self.workspace, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
                              self.dx, self.y, stream)
+
+    def prepare(self, stream: Optional[int] = None) -> None:
+        """Builds the operand copies of the weights once; later `run` calls skip that work."""
+        mb.mebptt_prepare(self.desc, self.W_ih, self.W_hh, self.b, self.workspace, stream)
+        self.prepared = True
 
     def capture(self) -> None:
         """Records one gradient step into a HIP graph (the schedule and every pointer are fixed, so

@@ -1,6 +1,10 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
-seeded inputs.  Tolerances (relative Frobenius error per output tensor):
-  fp32 GEMM operands 1e-4, bf16 GEMM operands 2e-2; forward-operation counts bit-exact."""
+seeded inputs.  Tolerances: fp32 GEMM operands 1e-4, bf16 GEMM operands 2e-2, applied three ways
+to every output tensor -- relative Frobenius error; largest element-wise error over the largest
+reference magnitude; and, for the matrices whose rows are separate sums (dW_ih, dW_hh, dx), the
+error of every row against that row's own norm (floored at the tensor's RMS row norm, since a
+row that cancels to almost nothing has no scale of its own).  Forward-operation counts and the
+peak slot occupancy are bit-exact."""
 import numpy as np
 import pytest
 
@@ -29,16 +33,60 @@ def oracle_cost(kind, t, m, alpha=4, beta=3):
     return int(dp.msm_tables(t, m, alpha, beta)[0][t, m])
 
 
+def elementwise_err(a, ref):
+    """max |a - ref| / max |ref|: one wrong tile or row shows here however large the tensor is."""
+    ref = np.asarray(ref, np.float64)
+    den = float(np.abs(ref).max()) if ref.size else 0.0
+    return float(np.abs(np.asarray(a, np.float64) - ref).max() / (den if den > 0 else 1.0)) if ref.size else 0.0
+
+
+def worst_row_err(a, ref):
+    """max over rows (vectors along the last axis) of |a_row - ref_row| / max(|ref_row|, RMS row norm)."""
+    ref = np.asarray(ref, np.float64).reshape(-1, np.shape(ref)[-1])
+    a = np.asarray(a, np.float64).reshape(ref.shape)
+    rn = np.linalg.norm(ref, axis=1)
+    floor = float(np.sqrt(np.mean(rn * rn)))
+    den = np.maximum(rn, floor if floor > 0 else 1.0)
+    return float((np.linalg.norm(a - ref, axis=1) / den).max())
+
+
+ROW_CHECKED = ("dW_ih", "dW_hh", "dx")
+ERROR_LOG = []          # (label, {tensor: (frobenius, element-wise, worst row)}) of every comparison
+
+
+def is_degenerate_bf16(w):
+    """bf16 GEMM operands on tensors of fewer than 64 elements per plane: the tolerance of 2e-2 is a
+    statement about errors averaged over many elements, which a handful of elements cannot
+    honour -- a single operand rounding (relative 2^-9) under cancellation can exceed it."""
+    return w.gemm_dtype == wl.GEMM_BF16 and w.B * w.H < 64
+
+
 def check_against_oracle(w, inp, out, ref, tol, label=""):
     worst = {}
-    for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+    names = [n for n in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y") if getattr(out, n) is not None]
+    for name in names:
         got = getattr(out, name)
-        if got is None:
-            continue
         assert np.all(np.isfinite(got)), f"{label}{name} has non-finite values"
-        worst[name] = rel_err(got, getattr(ref, name))
-    bad = {k: v for k, v in worst.items() if not v <= tol}
-    assert not bad, f"{label} relative errors above {tol}: {bad} (all: {worst})"
+    if is_degenerate_bf16(w):
+        # Worst-case linear bound instead of the averaged one: every step rounds three operands
+        # (weights, h, dG) to bf16, relative 2^-9 each, forward and backward: 6 t 2^-9 of the
+        # largest magnitude among the tensors of the same family (gradients; outputs).
+        bound = 6 * w.t * 2.0 ** -9
+        gscale = max(float(np.abs(getattr(ref, n)).max()) for n in names if n != "y")
+        for name in names:
+            scale = float(np.abs(ref.y).max()) if name == "y" else gscale
+            err = float(np.abs(np.asarray(getattr(out, name), np.float64) - getattr(ref, name)).max())
+            worst[name] = (err / max(scale, 1e-30),)
+            assert err <= bound * max(scale, 1e-30), f"{label}{name}: |error| {err} above {bound} x {scale}"
+        ERROR_LOG.append((label, worst))
+        return worst
+    for name in names:
+        got, want = getattr(out, name), getattr(ref, name)
+        worst[name] = (rel_err(got, want), elementwise_err(got, want),
+                       worst_row_err(got, want) if name in ROW_CHECKED else 0.0)
+    ERROR_LOG.append((label, worst))
+    bad = {k: v for k, v in worst.items() if not max(v) <= tol}
+    assert not bad, f"{label} errors (Frobenius, element-wise, worst row) above {tol}: {bad} (all: {worst})"
     return worst
 
 
@@ -62,7 +110,7 @@ def run_case(w, *, kind=None, m=None, nonzero=False, null_state=False, want_dx=T
     out = s.run_and_fetch()
     assert out.stats.forward_ops == oracle_cost(kind, w.t, m, w.alpha, w.beta)
     assert out.stats.backward_ops == w.t
-    assert out.stats.peak <= m
+    assert out.stats.peak <= m and out.stats.peak == s.plan.peak      # tracked by the executor, not copied
     assert out.stats.peak_slot_bytes <= s.slot_bytes
     errs = check_against_oracle(w, inp, out, ref, TOL[w.gemm_dtype], label=f"{w.name} kind={kind} m={m}: ")
     return out, ref, inp, errs
@@ -172,10 +220,6 @@ def _bisection_nodes(n):
     (120, 72, 2040, 4, wl.KIND_HSM, 2),    # largest workgroup tiles (8 x 2 forward, 2 x 2 backward), ragged
 ])
 def test_ragged_shapes(B, I, H, t, kind, m, dtype):
-    if H == 1 and dtype == wl.GEMM_BF16:
-        # a one-element tensor has no norm to average over: a single bf16 rounding (2^-9 relative
-        # per operand) under cancellation already exceeds a 2e-2 relative bound
-        pytest.skip("relative tolerance is not meaningful for single-element bf16 results")
     for loss, first in ((wl.LOSS_EXTERNAL_DY, 1), (wl.LOSS_EXTERNAL_DY, max(1, t - 1)), (wl.LOSS_HALF_SUM_H2, 1)):
         w = wl.Workload("ragged", B=B, I=I, H=H, t=t, kind=kind, m=m, gemm_dtype=dtype, loss=loss,
                         dy_first_step=first, seed=100 + B)
@@ -190,8 +234,6 @@ def test_tile_boundary_shapes(dtype):
     shapes = [(16, 32, 32, 3), (17, 33, 33, 3), (15, 31, 31, 3), (16, 1, 16, 2), (32, 64, 48, 3), (31, 17, 47, 3),
               (48, 96, 96, 2), (1, 40, 64, 3), (2, 16, 17, 3), (64, 8, 8, 2)]
     for B, I, H, t in shapes:
-        if dtype == wl.GEMM_BF16 and B * H < 64:
-            continue                      # too few elements for a relative bound on bf16 rounding
         for cell in (wl.CELL_LSTM, wl.CELL_GRU):
             w = wl.Workload("edge", B=B, I=I, H=H, t=t, kind=wl.KIND_MSM, m=5, gemm_dtype=dtype,
                             loss=wl.LOSS_EXTERNAL_DY, dy_first_step=1, seed=500 + B + H, cell=cell)
@@ -337,10 +379,13 @@ def test_config4_full_size():
     ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x[t0:], h8, c8, inp.dy, w.dy_first_step - t0)
     peak = max(np.abs(ref.dx).max(), 1e-300)
     assert np.abs(ref.dh0).max() <= 1e-12 * peak and np.abs(ref.dc0).max() <= 1e-12 * peak
+    assert elementwise_err(out.y, y_ref) <= TOL[w.gemm_dtype]
     for name in ("dW_ih", "dW_hh", "db"):
-        e = rel_err(getattr(out, name), getattr(ref, name))
-        assert e <= TOL[w.gemm_dtype], (name, e)
-    assert rel_err(out.dx[t0:], ref.dx) <= TOL[w.gemm_dtype]
+        e = (rel_err(getattr(out, name), getattr(ref, name)), elementwise_err(getattr(out, name), getattr(ref, name)),
+             worst_row_err(getattr(out, name), getattr(ref, name)) if name != "db" else 0.0)
+        assert max(e) <= TOL[w.gemm_dtype], (name, e)
+    e = (rel_err(out.dx[t0:], ref.dx), elementwise_err(out.dx[t0:], ref.dx), worst_row_err(out.dx[t0:], ref.dx))
+    assert max(e) <= TOL[w.gemm_dtype], ("dx", e)
     assert np.abs(out.dx[:t0]).max() <= 1e-6 * np.abs(out.dx).max()
     assert np.abs(out.dh0).max() <= 1e-6 and np.abs(out.dc0).max() <= 1e-6
 
@@ -408,3 +453,33 @@ def test_graph_replay_matches_eager():
         if rep % 2 == 0:          # the program's own eager work between replays
             again = s.run_and_fetch()
             assert np.array_equal(again.dW_hh, eager.dW_hh)
+
+
+def test_paper_experiment_shape():
+    """The shape of the paper's own timing experiment (Section 4: an LSTM mapping 256 inputs to 256
+    outputs, batch 64) at t = 100 under budgets of 10, 50 and 100 hidden states, bf16 GEMM operands,
+    against the float64 oracle and bit for bit across the budgets."""
+    w = wl.Workload("paper-experiment", B=64, I=256, H=256, t=100, kind=wl.KIND_HSM, m=10, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, seed=256)
+    inp = wl.make_inputs(w)
+    ref = oracle_gradients(w, inp)
+    first = None
+    for m in (10, 50, 100):
+        out, _, _, _ = run_case(w, m=m, ref=ref, inp=inp)
+        if first is None:
+            first = out
+        for name in ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y"):
+            assert np.array_equal(getattr(out, name), getattr(first, name)), (m, name)
+
+
+def test_zz_report_errors(capsys):
+    """Not a check: prints the worst error of every comparison above so that a run's log shows how
+    much of each tolerance was used."""
+    with capsys.disabled():
+        top = {}
+        for label, worst in ERROR_LOG:
+            for name, v in worst.items():
+                key = label.split(":")[0].split(" kind=")[0]
+                top[key] = max(top.get(key, 0.0), max(v))
+        for key in sorted(top):
+            print(f"[parity] {key}: worst error ratio {top[key]:.3e}")
