@@ -300,6 +300,25 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
  * afterwards (resources are re-created on demand).  Errors: EHIP. */
 int mebptt_shutdown(void);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): mebptt_run with the workspace taken from a file-scope device array of
+ * MEBPTT_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the process ends.
+ * The call creates no stream and no event and allocates nothing: every kernel, including the
+ * time-batched GEMMs, is enqueued on `stream` in schedule order; the measurement hooks are
+ * ignored.  Results are bit-identical to mebptt_run's.  Shapes whose mebptt_workspace_bytes()
+ * exceeds the array are refused with EWORKSPACE before anything is enqueued.  All calls on one
+ * GPU share the array, which keeps the previous call's contents (the call clears what must start
+ * at zero): calls whose device work overlaps on one GPU race -- keep them on one stream or
+ * order them with events.  Other arguments as mebptt_run. */
+#define MEBPTT_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+size_t mebptt_static_workspace_bytes(void);
+int mebptt_run_static(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
+                      const float* W_ih, const float* W_hh, const float* b,
+                      const float* x, const float* dy, const float* h0, const float* c0,
+                      void* slots, size_t slots_bytes,
+                      float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
+                      float* dx, float* y_out, mebptt_stats* stats, void* stream);
+
 /* ---- measurement hooks ---------------------------------------------------------------------
  * Kernel classes of the hot path, for timing with HIP events on the run's own stream. */
 enum {

@@ -109,6 +109,9 @@ SIGNATURES = {
     "mebptt_prepare": (C.c_int, [_DESC] + [_P] * 3 + [_P, C.c_size_t, _P]),
     "mebptt_run_prepared": (C.c_int, [_DESC, _P] + [_P] * 4 + [_P, C.c_size_t, _P, C.c_size_t] + [_P] * 7
                             + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_run_static": (C.c_int, [_DESC, _P] + [_P] * 7 + [_P, C.c_size_t] + [_P] * 7
+                          + [C.POINTER(mebptt_stats), _P]),
+    "mebptt_static_workspace_bytes": (C.c_size_t, []),
     "mebptt_shutdown": (C.c_int, []),
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
@@ -359,6 +362,20 @@ def mebptt_run_prepared(desc: mebptt_lstm_desc, plan: Plan, x, dy, h0, c0, slots
                                      _ptr(db), _ptr(dh0), _ptr(dc0), _ptr(dx), _ptr(y_out), C.byref(stats),
                                      _stream(stream)))
     return stats
+
+
+def mebptt_run_static(desc: mebptt_lstm_desc, plan: Plan, W_ih, W_hh, b, x, dy, h0, c0, slots, dW_ih, dW_hh, db, dh0,
+                      dc0, dx=None, y_out=None, stream: Optional[int] = None) -> mebptt_stats:
+    """mebptt_run with the workspace in the library's static device array: allocates nothing."""
+    stats = mebptt_stats()
+    _check(lib().mebptt_run_static(C.byref(desc), plan.handle, _ptr(W_ih), _ptr(W_hh), _ptr(b), _ptr(x), _ptr(dy),
+                                   _ptr(h0), _ptr(c0), _ptr(slots), _nbytes(slots), _ptr(dW_ih), _ptr(dW_hh), _ptr(db),
+                                   _ptr(dh0), _ptr(dc0), _ptr(dx), _ptr(y_out), C.byref(stats), _stream(stream)))
+    return stats
+
+
+def mebptt_static_workspace_bytes() -> int:
+    return lib().mebptt_static_workspace_bytes()
 
 
 def mebptt_shutdown() -> None:

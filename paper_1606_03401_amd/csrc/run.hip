@@ -182,6 +182,31 @@ bool is_prepared(const void* ws, const Dims& d) {
   return false;
 }
 
+// ---- static scratch for callers that cannot allocate ---------------------------------------------
+// mebptt_run_static keeps its workspace here instead of taking one from the caller.  In host code
+// the array's name is only a handle: its device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[MEBPTT_STATIC_WORKSPACE_BYTES];
+void* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t get_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 __global__ void null_kernel() {}
 
 #define HIP_TRY(expr)                                                                                 \
@@ -381,6 +406,24 @@ int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us) {
   if (e != hipSuccess) return set_error(MEBPTT_EHIP, "null-launch timing failed: %s", hipGetErrorString(e));
   *out_us = (double)ms * 1e3 / launches;
   return MEBPTT_OK;
+}
+
+size_t mebptt_static_workspace_bytes(void) { return MEBPTT_STATIC_WORKSPACE_BYTES; }
+
+int mebptt_run_static(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih, const float* W_hh,
+                      const float* b, const float* x, const float* dy, const float* h0, const float* c0, void* slots,
+                      size_t slots_bytes, float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0, float* dx,
+                      float* y_out, mebptt_stats* stats, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  const size_t need = layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).total;
+  if (need > MEBPTT_STATIC_WORKSPACE_BYTES)
+    return set_error(MEBPTT_EWORKSPACE, "this shape needs %zu bytes of workspace; the static scratch holds %zu", need,
+                     (size_t)MEBPTT_STATIC_WORKSPACE_BYTES);
+  void* ptr = nullptr;
+  HIP_TRY(get_scratch(&ptr));
+  return run_impl(RUN_STATIC, desc, plan, W_ih, W_hh, b, x, dy, h0, c0, slots, slots_bytes, ptr,
+                  MEBPTT_STATIC_WORKSPACE_BYTES, dW_ih, dW_hh, db, dh0, dc0, dx, y_out, stats, stream);
 }
 
 }  // extern "C"

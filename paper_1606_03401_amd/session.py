@@ -33,7 +33,7 @@ class Session:
     def __init__(self, w: Workload, inp: Inputs, *, kind: Optional[int] = None, m: Optional[int] = None,
                  gemm_dtype: Optional[int] = None, want_dx: bool = True, want_y: bool = True,
                  pass_null_state: bool = False, device: str = "cuda:0", plan: Optional[mb.Plan] = None,
-                 guard_bytes: int = 0, fill_byte: int = 0xFF):
+                 guard_bytes: int = 0, fill_byte: int = 0xFF, static_workspace: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("mebptt needs a GPU: no HIP device is visible")
         self.w = w
@@ -67,11 +67,19 @@ class Session:
         self.guard_bytes, self.fill_byte = guard_bytes, fill_byte
         self.slots_outer = torch.full((self.slot_bytes + 2 * guard_bytes,), fill_byte, dtype=torch.uint8, device=dev)
         self.slots = self.slots_outer[guard_bytes:guard_bytes + self.slot_bytes]
-        self.workspace_outer = torch.full((self.ws_bytes + 2 * guard_bytes,), fill_byte, dtype=torch.uint8, device=dev)
-        self.workspace = self.workspace_outer[guard_bytes:guard_bytes + self.ws_bytes]
+        self.static_workspace = static_workspace
+        if static_workspace:
+            self.workspace_outer = self.workspace = None
+        else:
+            self.workspace_outer = torch.full((self.ws_bytes + 2 * guard_bytes,), fill_byte, dtype=torch.uint8, device=dev)
+            self.workspace = self.workspace_outer[guard_bytes:guard_bytes + self.ws_bytes]
         self.prepared = False
 
     def run(self, stream: Optional[int] = None) -> mb.mebptt_stats:
+        if self.static_workspace:
+            return mb.mebptt_run_static(self.desc, self.plan, self.W_ih, self.W_hh, self.b, self.x, self.dy, self.h0,
+                                        self.c0, self.slots, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
+                                        self.dx, self.y, stream)
         if self.prepared:
             return mb.mebptt_run_prepared(self.desc, self.plan, self.x, self.dy, self.h0, self.c0, self.slots,
                                           self.workspace, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0,
