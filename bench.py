@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: one LSTM gradient step under the DP checkpoint policy.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--sweep | --fig2b | --chen]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--only] [--sweep | --fig2b | --chen]
 
 A "step" is one call of ``mebptt_run``: every forward operation, every recomputation and every
 backward operation of the schedule for one batch of synthetic sequences.  Inputs are resident in
 device memory before the timed region.  Prints ONE JSON line on stdout (everything else goes to
 stderr): throughput in time-steps/s at the named budget, the measured and theoretical cost
 ratio against store-everything BPTT, the roofline position of the dominant kernel measured
-with HIP events on the run's stream, and the CPU oracle timed on this host as a baseline.
+with HIP events on the run's stream, and the CPU oracle timed on this host as a baseline.  Unless
+--only is given the same line carries `configs` (every named configuration, a few steps each,
+config 5 at each budget of its sweep) and `fig2b` (the shape of the paper's timing experiment).
 """
 from __future__ import annotations
 
@@ -86,9 +88,9 @@ def forward_flops(w):
     return 2 * gate_blocks(w) * w.B * w.H * (w.I + w.H)
 
 
-def pmc_traffic():
+def pmc_traffic(name="cfg2"):
     """HBM bytes per forward launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "forward_kernel_cfg2_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"forward_kernel_{name}_hbm_traffic.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -130,34 +132,6 @@ def cpu_baseline(w, inp, budget_s=20.0):
             "sample": f"first {n} of {w.t} steps of {w.name} (float64 store-everything BPTT, numpy), {dt:.1f} s"}
 
 
-def fig2b(args) -> int:
-    """Section 4 / Fig. 2b: time per time step of one gradient step as a function of the sequence
-    length, for budgets of 10, 50, 100, 500, 1000 hidden states, beside the cost model's forward
-    operations per step (Fig. 2a).  Synthetic inputs; the paper states no hardware or precision."""
-    import torch
-    from paper_1606_03401_amd import workloads as wl
-    from paper_1606_03401_amd.session import Session
-    rows = []
-    for t in (100, 200, 400, 600, 800, 1000):
-        base = wl.Workload("fig2b", B=64, I=256, H=256, t=t, kind=wl.KIND_HSM, m=t, gemm_dtype=wl.GEMM_BF16,
-                           loss=wl.LOSS_EXTERNAL_DY, seed=t)
-        inp = wl.make_inputs(base)
-        line = {"t": t}
-        for m in (10, 50, 100, 500, 1000):
-            s = Session(base, inp, kind=wl.KIND_HSM, m=min(m, t), want_dx=True, want_y=False)
-            ms = time_runs(s, args.steps, args.warmup) * 1e3
-            line[m] = (ms / t * 1e3, s.plan.forward_ops / t)
-            del s
-        sa = Session(base, inp, kind=wl.KIND_ISM, m=t, want_dx=True, want_y=False)
-        line["store_all"] = (time_runs(sa, args.steps, args.warmup) * 1e3 / t * 1e3, 1.0)
-        del sa
-        rows.append(line)
-        log(f"[fig2b] t={t}: " + "  ".join(
-            f"m={k}: {v[0]:.1f} us/step ({v[1]:.2f} fwd/step)" for k, v in line.items() if k != "t"))
-    print(json.dumps({"experiment": "fig2b", "unit": "us per time step (forward ops per step)", "rows": rows}), flush=True)
-    return 0
-
-
 def chen_comparison(args) -> int:
     """Sections 4.2-4.3: Chen et al.'s sqrt(t) and recursive strategies run as policies through the
     same executor on the benchmark workload, beside the optimal BPTT-MSM policy at the same memory,
@@ -197,18 +171,157 @@ def chen_comparison(args) -> int:
     return 0
 
 
+def memory_report(w, sess):
+    """Bytes this run keeps against what store-everything BPTT would keep: the slot pool (the
+    budget), the workspace outside it (working core, operand copies of the weights, dW accumulator,
+    staging of two chunks), and t stored hidden or internal states in fp32."""
+    plane = 4 * w.B * w.H
+    return {"slot_pool_bytes": sess.slot_bytes, "workspace_bytes": sess.ws_bytes,
+            "store_all_hidden_bytes": 2 * plane * w.t, "store_all_internal_bytes": 6 * plane * w.t,
+            "pool_plus_workspace_over_store_all_internal": (sess.slot_bytes + sess.ws_bytes) / (6 * plane * w.t)}
+
+
+def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile=True, store_all=True,
+            launch_floor_us=None, bracket_us=None):
+    """Times one configuration: ms per gradient step (stream launches and HIP-graph replay, the
+    faster is reported), per kernel class the event-sampled time per launch and its MFMA fraction,
+    the forward kernel's roofline position, the store-everything run for the cost ratio."""
+    import torch
+    from paper_1606_03401_amd import binding as mb
+    from paper_1606_03401_amd import workloads as wl
+    from paper_1606_03401_amd.session import Session
+    sess = Session(w, inp, kind=kind, m=m, want_dx=True, want_y=False)
+    ms = time_runs(sess, steps, warmup) * 1e3
+    enqueue_ms = time_runs.last_enqueue_ms
+    C = sess.plan.forward_ops
+    eager_ms = ms
+    graph_ms = time_graph(sess, steps, warmup) if graph else None
+    launch_mode = "stream launches"
+    if graph_ms is not None and graph_ms < ms:
+        ms, launch_mode = graph_ms, "HIP graph replay"
+    log(f"[bench] {w.name} {KIND_NAMES[sess.kind]} m={sess.m}: {ms:.3f} ms/step ({launch_mode}; host enqueue "
+        f"{enqueue_ms:.3f} ms), forward ops {C}, peak {sess.plan.peak}")
+    out = {"workload": f"{w.name}: single-layer {'GRU' if w.cell else 'LSTM'} I={w.I} H={w.H} B={w.B} t={w.t}, "
+                       f"BPTT-{KIND_NAMES[sess.kind]} budget m={sess.m}, seed {w.seed}",
+           "name": w.name, "kind": KIND_NAMES[sess.kind], "budget_m": sess.m, "forward_ops": C,
+           "peak_slots": sess.plan.peak, "ms_per_step": ms, "ms_per_step_stream_launches": eager_ms,
+           "ms_per_step_graph_replay": graph_ms, "launch": launch_mode, "host_enqueue_ms": enqueue_ms,
+           "time_steps_per_s": w.t / (ms * 1e-3), "dtype": "bf16" if w.gemm_dtype else "f32",
+           "memory": memory_report(w, sess)}
+    flops_exec = (C + 2 * w.t) * forward_flops(w)
+    peak_tf = MFMA_PEAK_TFLOPS[w.gemm_dtype]
+    out["gflops"] = {"executed": flops_exec / (ms * 1e-3) / 1e9, "useful": 3 * w.t * forward_flops(w) / (ms * 1e-3) / 1e9,
+                     "executed_frac_of_mfma_peak": flops_exec / (ms * 1e-3) / 1e12 / peak_tf}
+    if profile:
+        mb.mebptt_profile_enable(8)
+        prof_steps = max(1, min(steps, 2))
+        for _ in range(prof_steps):
+            sess.run()
+        torch.cuda.synchronize()
+        prof = mb.mebptt_profile_collect()
+        mb.mebptt_profile_enable(0)
+        overhead_us = max(0.0, (bracket_us or 0.0) - (launch_floor_us or 0.0))
+        # flops of one launch of each class: forward op 8BH(I+H); backward step (dh GEMM) 8BH^2; the
+        # time-batched GEMMs carry t steps over their launches: dW 8BH(I+H), dx 8BHI per step.
+        # The sequential GEMMs stream their weights once per launch: B flop per weight byte (bf16
+        # operands: 2*B*K*N flop over 2*K*N bytes), so min(MFMA peak, B x HBM peak) is the most
+        # such a launch can reach; the time-batched ones are bounded by the MFMA peak alone.
+        F_fwd, F_dh = forward_flops(w), 2.0 * gate_blocks(w) * w.B * w.H * w.H
+        F_dx = 2.0 * gate_blocks(w) * w.B * w.H * w.I
+        opb = 2 if w.gemm_dtype else 4
+        seq_cap_tf = min(peak_tf, 2.0 * w.B / opb * HBM_PEAK_GBS / 1e3)
+        classes = {}
+        for k, name in enumerate(mb.K_NAMES):
+            n_s = prof.sampled[k]
+            lps = prof.launches[k] / prof_steps
+            avg_us = prof.sampled_ms[k] / n_s * 1e3 if n_s else None
+            classes[name] = {"launches_per_step": lps, "avg_us": avg_us}
+            if avg_us is not None and lps > 0:
+                net_us = max(avg_us - overhead_us, 1e-3)
+                flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_dh + F_fwd,
+                         "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps}.get(name)
+                classes[name]["net_us"] = net_us
+                if flops:
+                    tf = flops / (net_us * 1e-6) / 1e12
+                    cap = peak_tf if name in ("wgrad", "dgrad") else seq_cap_tf
+                    classes[name].update({"gflop_per_launch": flops / 1e9, "tflops": tf, "frac_mfma_peak": tf / peak_tf,
+                                          "attainable_tflops": cap, "frac_of_attainable": tf / cap})
+            log(f"[bench]   {name}: {lps:.0f} launches/step, avg {avg_us if avg_us is None else round(avg_us, 2)} us ({n_s} samples)"
+                + (f", net {classes[name]['net_us']:.2f} us, {classes[name]['tflops']:.0f} TFLOP/s = "
+                   f"{100 * classes[name]['frac_mfma_peak']:.1f}% of MFMA peak, {100 * classes[name]['frac_of_attainable']:.0f}% of attainable"
+                   if "tflops" in classes[name] else ""))
+        out["kernel_classes"] = classes
+        # The dominant kernel's launch duration: whole forward runs bracketed by one event pair on the
+        # run's stream (single-launch brackets carry the cost of the events themselves).
+        if prof.forward_run_launches:
+            fwd_us = prof.forward_run_ms / prof.forward_run_launches * 1e3
+        else:
+            fwd_us = classes["forward"].get("net_us") or classes["backward+forward"].get("net_us")
+        if fwd_us:
+            achieved = forward_bytes(w) / (fwd_us * 1e-6) / 1e9
+            out["roofline"] = {"bound": "hbm", "kernel": "forward_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": pmc_traffic(w.name),
+                               "avg_launch_us": fwd_us, "bytes_per_launch": forward_bytes(w),
+                               "mfma_tflops": forward_flops(w) / (fwd_us * 1e-6) / 1e12,
+                               "mfma_frac": forward_flops(w) / (fwd_us * 1e-6) / 1e12 / peak_tf}
+    del sess
+    store_all_ms = None
+    if store_all:
+        try:   # store-everything BPTT through the same path: an internal-state slot for every step
+            sa = Session(w, inp, kind=wl.KIND_ISM, m=w.t, want_dx=True, want_y=False)
+            store_all_ms = time_runs(sa, max(2, steps // 2), 1) * 1e3
+            if graph and launch_mode == "HIP graph replay":
+                g = time_graph(sa, max(2, steps // 2), 1)
+                store_all_ms = min(store_all_ms, g) if g is not None else store_all_ms
+            log(f"[bench]   store-all (ISM m=t): {store_all_ms:.3f} ms/step")
+            del sa
+        except Exception as e:   # e.g. the store-all pool does not fit
+            log(f"[bench]   store-all run skipped: {e}")
+    out["cost_ratio_vs_store_all"] = {"measured": (ms / store_all_ms) if store_all_ms else None,
+                                      "theoretical": (C + 2 * w.t) / (3 * w.t), "store_all_ms": store_all_ms}
+    return out
+
+
+def fig2b_rows(steps, warmup, lengths=(100, 400, 1000)):
+    """Section 4 / Fig. 2b as numbers: LSTM 256 -> 256, batch 64; microseconds per time step and
+    forward operations per time step for budgets of 10/50/100/500/1000 hidden states and for
+    store-everything BPTT, at several sequence lengths."""
+    from paper_1606_03401_amd import workloads as wl
+    from paper_1606_03401_amd.session import Session
+    rows = []
+    for t in lengths:
+        base = wl.Workload("fig2b", B=64, I=256, H=256, t=t, kind=wl.KIND_HSM, m=t, gemm_dtype=wl.GEMM_BF16,
+                           loss=wl.LOSS_EXTERNAL_DY, seed=t)
+        inp = wl.make_inputs(base)
+        row = {"t": t, "us_per_time_step": {}, "forward_ops_per_time_step": {}}
+        for m in (10, 50, 100, 500, 1000):
+            s = Session(base, inp, kind=wl.KIND_HSM, m=min(m, t), want_dx=True, want_y=False)
+            row["us_per_time_step"][str(m)] = time_runs(s, steps, warmup) * 1e6 / t
+            row["forward_ops_per_time_step"][str(m)] = s.plan.forward_ops / t
+            del s
+        sa = Session(base, inp, kind=wl.KIND_ISM, m=t, want_dx=True, want_y=False)
+        row["us_per_time_step"]["store_all"] = time_runs(sa, steps, warmup) * 1e6 / t
+        row["forward_ops_per_time_step"]["store_all"] = 1.0
+        del sa
+        rows.append(row)
+        log(f"[fig2b] t={t}: " + "  ".join(f"m={k}: {v:.1f} us ({row['forward_ops_per_time_step'][k]:.2f} fwd)"
+                                           for k, v in row["us_per_time_step"].items()))
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--sweep", action="store_true", help="also time the budget sweep m = t .. 5%% of t (stderr)")
+    ap.add_argument("--workload", default="cfg2", help="the configuration the headline value is measured on")
+    ap.add_argument("--only", action="store_true", help="time the headline workload only (no `configs`, no `fig2b`)")
+    ap.add_argument("--sweep", action="store_true", help="also time the budget sweep m = t .. 5%% of t on the headline shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time stream launches only")
     ap.add_argument("--fig2b", action="store_true",
-                    help="the shape of the paper's timing experiment: LSTM 256->256, batch 64, ms per time step "
-                         "vs sequence length at budgets of 10/50/100/500/1000 hidden states (table on stderr)")
+                    help="only the shape of the paper's timing experiment: LSTM 256->256, batch 64, us per time step "
+                         "vs sequence length at budgets of 10/50/100/500/1000 hidden states")
     ap.add_argument("--cell", choices=("lstm", "gru"), default="lstm", help="RNN core run on the workload's shape")
     ap.add_argument("--chen", action="store_true",
                     help="Chen et al.'s sqrt(t) / recursive strategies as policies through the same executor, beside "
@@ -221,13 +334,14 @@ def main() -> int:
     import torch
     from paper_1606_03401_amd import binding as mb
     from paper_1606_03401_amd import workloads as wl
-    from paper_1606_03401_amd.session import Session
 
     if not torch.cuda.is_available():
         log("no GPU visible: the HIP path cannot run")
         return 1
     if args.fig2b:
-        return fig2b(args)
+        print(json.dumps({"experiment": "fig2b", "rows": fig2b_rows(args.steps, args.warmup, (100, 200, 400, 600, 800, 1000))}),
+              flush=True)
+        return 0
     if args.chen:
         return chen_comparison(args)
     w = wl.CONFIGS[args.workload]
@@ -241,121 +355,94 @@ def main() -> int:
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
     del cal_src, cal_dst
-    inp = wl.make_inputs(w)
-    sess = Session(w, inp, want_dx=True, want_y=False)
-    ms = time_runs(sess, args.steps, args.warmup) * 1e3
-    C = sess.plan.forward_ops
-    enqueue_ms = time_runs.last_enqueue_ms
-    log(f"[bench] {KIND_NAMES[sess.kind]} m={sess.m}: {ms:.3f} ms/step (host enqueue {enqueue_ms:.3f} ms), "
-        f"forward ops {C}, peak {sess.plan.peak}")
-    eager_ms = ms
-    graph_ms = None if args.no_graph else time_graph(sess, args.steps, args.warmup)
-    launch_mode = "stream launches"
-    if graph_ms is not None and graph_ms < ms:
-        ms, launch_mode = graph_ms, "HIP graph replay"
-
-    # dominant kernel: event-bracketed samples on the run's stream, in extra profiled steps
-    mb.mebptt_profile_enable(8)
-    prof_steps = max(1, min(args.steps, 3))
-    for _ in range(prof_steps):
-        sess.run()
-    torch.cuda.synchronize()
-    prof = mb.mebptt_profile_collect()
-    mb.mebptt_profile_enable(0)
-    # What an event pair around a single launch adds: the same bracket around a launch that does
-    # nothing measurable (a 4-byte fill), minus nothing -- an upper bound of the bracket's own cost.
-    cal = torch.zeros(1, device=sess.dev)
+    # The floor of a dependent launch on this machine, and what an event pair around a single launch
+    # adds to it (the low decile of brackets around a 4-byte fill): single-launch samples are
+    # reported net of the difference.
+    launch_floor_us = mb.mebptt_null_launch_us(4000)
+    cal = torch.zeros(1, device="cuda:0")
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
     for a, b in pairs:
         a.record()
         cal.zero_()
         b.record()
     torch.cuda.synchronize()
-    bracket_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 10]   # low decile: the bracket's floor
-    null_us = 2.4   # a back-to-back empty launch on this stack: part of every kernel's own time
-    overhead_us = max(0.0, bracket_us - null_us)
-    log(f"[bench] event bracket around a minimal launch: {bracket_us:.2f} us -> {overhead_us:.2f} us subtracted from single-launch samples")
-    # flops of one launch of each class: forward op 8BH(I+H); backward step (dh GEMM) 8BH^2; the
-    # time-batched GEMMs carry t steps over their launches: dW 8BH(I+H), dx 8BHI per step
-    F_fwd, F_dh = forward_flops(w), 2.0 * gate_blocks(w) * w.B * w.H * w.H
-    F_dx = 2.0 * gate_blocks(w) * w.B * w.H * w.I
-    classes = {}
-    for k, name in enumerate(mb.K_NAMES):
-        n_s = prof.sampled[k]
-        lps = prof.launches[k] / prof_steps
-        avg_us = prof.sampled_ms[k] / n_s * 1e3 if n_s else None
-        classes[name] = {"launches_per_step": lps, "avg_us": avg_us}
-        if avg_us is not None and lps > 0:
-            net_us = max(avg_us - overhead_us, 1e-3)
-            flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_dh + F_fwd,
-                     "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps}.get(name)
-            classes[name]["net_us"] = net_us
-            if flops:
-                tf = flops / (net_us * 1e-6) / 1e12
-                classes[name].update({"gflop_per_launch": flops / 1e9, "tflops": tf, "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS[w.gemm_dtype]})
-        log(f"[bench] kernel class {name}: {lps:.0f} launches/step, "
-            f"avg {avg_us if avg_us is None else round(avg_us, 2)} us (event-bracketed, {n_s} samples)"
-            + (f", net {classes[name]['net_us']:.2f} us, {classes[name]['tflops']:.0f} TFLOP/s = "
-               f"{100 * classes[name]['frac_mfma_peak']:.1f}% of MFMA peak" if "tflops" in classes[name] else ""))
-    # The dominant kernel's launch duration: whole forward runs bracketed by one event pair (the
-    # figure rocprofv3's kernel trace reports); single-launch brackets carry ~4 us of event cost.
-    if prof.forward_run_launches:
-        fwd_us = prof.forward_run_ms / prof.forward_run_launches * 1e3
-        log(f"[bench] forward kernel inside long runs: avg {fwd_us:.2f} us over {prof.forward_run_launches} launches")
-    else:
-        fwd_us = classes["forward"]["avg_us"]
-    achieved = forward_bytes(w) / (fwd_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "forward_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": pmc_traffic(),
-                "avg_launch_us": fwd_us, "bytes_per_launch": forward_bytes(w),
-                "mfma_tflops": forward_flops(w) / (fwd_us * 1e-6) / 1e12,
-                "mfma_frac": forward_flops(w) / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    bracket_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 10]
+    log(f"[bench] back-to-back empty launches: {launch_floor_us:.2f} us each; event bracket around a minimal launch: "
+        f"{bracket_us:.2f} us -> {max(0.0, bracket_us - launch_floor_us):.2f} us subtracted from single-launch samples")
 
-    # store-everything BPTT through the same path: internal-state slots for every step
-    store_all_ms = None
-    try:
-        sa = Session(w, inp, kind=wl.KIND_ISM, m=w.t, want_dx=True, want_y=False)
-        store_all_ms = time_runs(sa, max(2, args.steps // 2), 1) * 1e3
-        if launch_mode == "HIP graph replay":
-            g = time_graph(sa, max(2, args.steps // 2), 1)
-            store_all_ms = min(store_all_ms, g) if g is not None else store_all_ms
-        log(f"[bench] store-all (ISM m=t): {store_all_ms:.3f} ms/step, forward ops {sa.plan.forward_ops}")
-        del sa
-    except Exception as e:   # e.g. the store-all pool does not fit
-        log(f"[bench] store-all run skipped: {e}")
-
+    inp = wl.make_inputs(w)
+    head = measure(w, inp, steps=args.steps, warmup=args.warmup, graph=not args.no_graph,
+                   launch_floor_us=launch_floor_us, bracket_us=bracket_us)
     if args.sweep:
+        from paper_1606_03401_amd.session import Session
+        sa_ms = head["cost_ratio_vs_store_all"]["store_all_ms"]
+        head["budget_sweep"] = []
         for kind in (wl.KIND_HSM, wl.KIND_ISM):
             for m in (w.t, w.t // 2, w.t // 4, w.t // 10, w.t // 20):
                 s2 = Session(w, inp, kind=kind, m=m, want_dx=True, want_y=False)
                 ms2 = time_runs(s2, max(2, args.steps // 2), 1) * 1e3
                 Cm = s2.plan.forward_ops
+                head["budget_sweep"].append({"kind": KIND_NAMES[kind], "m": m, "ms_per_step": ms2, "forward_ops": Cm,
+                                             "theoretical_ratio": (Cm + 2 * w.t) / (3 * w.t),
+                                             "measured_ratio": ms2 / sa_ms if sa_ms else None})
                 log(f"[sweep] {KIND_NAMES[kind]} m={m}: {ms2:.3f} ms, {w.t / ms2 * 1e3:.0f} steps/s, C={Cm}, "
-                    f"theoretical ratio {(Cm + 2 * w.t) / (3 * w.t):.3f}, "
-                    f"measured {ms2 / store_all_ms if store_all_ms else float('nan'):.3f}")
+                    f"theoretical ratio {(Cm + 2 * w.t) / (3 * w.t):.3f}, measured {ms2 / sa_ms if sa_ms else float('nan'):.3f}")
                 del s2
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, inp, 12.0 if not args.only else 20.0)
+        log(f"[bench] cpu baseline {cpu}")
+    del inp
 
-    flops_exec = (C + 2 * w.t) * forward_flops(w)
-    flops_useful = 3 * w.t * forward_flops(w)
+    ms = head["ms_per_step"]
     result = {
         "metric": METRIC, "value": w.t / (ms * 1e-3), "unit": "time-steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_stream_launches": eager_ms, "ms_per_step_graph_replay": graph_ms,
-        "host_enqueue_ms": enqueue_ms, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_dtype else "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: single-layer {'GRU' if w.cell else 'LSTM'} I={w.I} H={w.H} B={w.B} t={w.t}, "
-                               f"BPTT-{KIND_NAMES[sess.kind]} budget m={sess.m}, seed {w.seed}",
-                   "launch": launch_mode, "budget_m": sess.m, "forward_ops": C, "peak_slots": sess.plan.peak,
-                   "slot_pool_bytes": sess.slot_bytes, "workspace_bytes": sess.ws_bytes},
-        "cost_ratio_vs_store_all": {"measured": (ms / store_all_ms) if store_all_ms else None,
-                                    "theoretical": (C + 2 * w.t) / (3 * w.t), "store_all_ms": store_all_ms},
-        "gflops": {"executed": flops_exec / (ms * 1e-3) / 1e9, "useful": flops_useful / (ms * 1e-3) / 1e9,
-                   "executed_frac_of_mfma_peak": flops_exec / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-        "kernel_classes": classes,
-        "roofline": roofline,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "ms_per_step_stream_launches": head["ms_per_step_stream_launches"], "ms_per_step_graph_replay": head["ms_per_step_graph_replay"],
+        "host_enqueue_ms": head["host_enqueue_ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "launch": head["launch"], "budget_m": head["budget_m"],
+                   "forward_ops": head["forward_ops"], "peak_slots": head["peak_slots"],
+                   "slot_pool_bytes": head["memory"]["slot_pool_bytes"], "workspace_bytes": head["memory"]["workspace_bytes"]},
+        "cost_ratio_vs_store_all": head["cost_ratio_vs_store_all"],
+        "gflops": head["gflops"],
+        "launch_floor_us": launch_floor_us, "event_bracket_us": bracket_us,
+        "kernel_classes": head.get("kernel_classes"),
+        "roofline": head.get("roofline"),
+        "memory": head["memory"],
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, inp)
-        log(f"[bench] cpu baseline {result['cpu_baseline']}")
+    if "budget_sweep" in head:
+        result["budget_sweep"] = head["budget_sweep"]
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
+
+    if not args.only:
+        # Every other configuration, a few steps each (cfg5 at each budget of its sweep), with the
+        # same per-class and roofline figures and a short CPU-oracle sample of its own.
+        configs = [dict(head, cpu_baseline=cpu)]
+        for name in ("cfg1", "cfg3", "cfg4", "cfg5"):
+            if name == args.workload:
+                continue
+            wc = wl.CONFIGS[name]
+            inp_c = wl.make_inputs(wc)
+            budgets = wl.CFG5_BUDGET_SWEEP if name == "cfg5" else (wc.m,)
+            for i, m in enumerate(budgets):
+                few = 2 if (name == "cfg5" and m < 31) else 3
+                row = measure(wc, inp_c, m=m, steps=few, warmup=1, graph=(name != "cfg4" and not args.no_graph),
+                              profile=(m == wc.m), store_all=(i == 0),
+                              launch_floor_us=launch_floor_us, bracket_us=bracket_us)
+                if i > 0:   # one store-everything run serves the whole sweep
+                    sa_ms = configs[-i]["cost_ratio_vs_store_all"]["store_all_ms"]
+                    row["cost_ratio_vs_store_all"].update({"store_all_ms": sa_ms,
+                                                           "measured": row["ms_per_step"] / sa_ms if sa_ms else None})
+                if m == wc.m and not args.no_cpu_baseline:
+                    row["cpu_baseline"] = cpu_baseline(wc, inp_c, 4.0)
+                    log(f"[bench]   cpu baseline {row['cpu_baseline']}")
+                configs.append(row)
+            del inp_c
+        result["configs"] = configs
+        result["fig2b"] = {"shape": "LSTM I=256 H=256 B=64, bf16 GEMM operands, HSM budgets and store-all",
+                           "rows": fig2b_rows(3, 1)}
     print(json.dumps(result), flush=True)
     return 0
 
