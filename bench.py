@@ -79,6 +79,16 @@ def forward_bytes(w):
     return gate_blocks(w) * w.H * (w.I + w.H) * op + 4 * w.B * w.I + 16 * w.B * w.H
 
 
+def backward_bytes(w):
+    """Algorithmic bytes of one backward operation's sequential half: W_hh once in the GEMM operand
+    type, dG of the step after, the ten fp32 planes the pointwise step reads (h, c, four gates,
+    c_prev, h_prev, dy, dc) and what it writes (dG twice -- row- and column-major -- h_prev
+    transposed, dc)."""
+    op = 2 if w.gemm_dtype else 4
+    return (gate_blocks(w) * w.H * w.H * op + 4 * w.B * w.H * op + 40 * w.B * w.H
+            + 2 * 4 * w.B * w.H * op + w.B * w.H * op + 4 * w.B * w.H)
+
+
 def gate_blocks(w):
     """Gate blocks of the core's weight matrices: 4 (LSTM) or 3 (GRU)."""
     return 3 if w.cell else 4
@@ -88,9 +98,9 @@ def forward_flops(w):
     return 2 * gate_blocks(w) * w.B * w.H * (w.I + w.H)
 
 
-def pmc_traffic(name="cfg2"):
-    """HBM bytes per forward launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"forward_kernel_{name}_hbm_traffic.txt")
+def pmc_traffic(name="cfg2", kernel="forward_kernel"):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{name}_hbm_traffic.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -239,7 +249,8 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
             if avg_us is not None and lps > 0:
                 net_us = max(avg_us - overhead_us, 1e-3)
                 flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_dh + F_fwd,
-                         "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps}.get(name)
+                         "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps,
+                         "forward chain": F_fwd * prof.chain_steps / max(prof.launches[k], 1)}.get(name)
                 classes[name]["net_us"] = net_us
                 if flops:
                     tf = flops / (net_us * 1e-6) / 1e12
@@ -251,19 +262,49 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
                    f"{100 * classes[name]['frac_mfma_peak']:.1f}% of MFMA peak, {100 * classes[name]['frac_of_attainable']:.0f}% of attainable"
                    if "tflops" in classes[name] else ""))
         out["kernel_classes"] = classes
-        # The dominant kernel's launch duration: whole forward runs bracketed by one event pair on the
-        # run's stream (single-launch brackets carry the cost of the events themselves).
+        # Per-launch time of the sequential classes.  Forward launches: whole runs bracketed by one
+        # event pair on the run's stream where there are any (single-launch brackets carry the cost
+        # of the events themselves); forward chains: every launch bracketed, per carried step.
         if prof.forward_run_launches:
-            fwd_us = prof.forward_run_ms / prof.forward_run_launches * 1e3
-        else:
-            fwd_us = classes["forward"].get("net_us") or classes["backward+forward"].get("net_us")
-        if fwd_us:
-            achieved = forward_bytes(w) / (fwd_us * 1e-6) / 1e9
-            out["roofline"] = {"bound": "hbm", "kernel": "forward_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                               "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": pmc_traffic(w.name),
-                               "avg_launch_us": fwd_us, "bytes_per_launch": forward_bytes(w),
-                               "mfma_tflops": forward_flops(w) / (fwd_us * 1e-6) / 1e12,
-                               "mfma_frac": forward_flops(w) / (fwd_us * 1e-6) / 1e12 / peak_tf}
+            classes["forward"]["net_us"] = prof.forward_run_ms / prof.forward_run_launches * 1e3
+        if prof.chain_steps:
+            ch = classes["forward chain"]
+            ch["steps_per_step"] = prof.chain_steps / prof_steps
+            ch["us_per_forward_op"] = prof.chain_ms / prof.chain_steps * 1e3
+            log(f"[bench]   forward chain: {ch['steps_per_step']:.0f} forward ops/step in {ch['launches_per_step']:.0f} launches, "
+                f"{ch['us_per_forward_op']:.2f} us per forward op")
+        # The dominant kernel = the class with the largest share of the step; its roofline block.
+        share = {}
+        for name in ("forward", "backward", "backward+forward"):
+            c = classes[name]
+            if c.get("net_us") and c["launches_per_step"]:
+                share[name] = c["net_us"] * c["launches_per_step"]
+        if prof.chain_steps:
+            share["forward chain"] = prof.chain_ms / prof_steps * 1e3
+        out["time_share_us"] = share
+        if share:
+            dom = max(share, key=share.get)
+            kernel = {"forward": "forward_kernel", "backward": "backward_kernel", "backward+forward": "pair_kernel",
+                      "forward chain": "forward_chain_kernel"}[dom]
+            if dom == "forward chain":
+                # weights stay on the chip: what bounds a step is the matrix pipe and the exchange of h,
+                # so the launch is placed on the MFMA roof
+                us = classes[dom]["us_per_forward_op"]
+                tf = forward_flops(w) / (us * 1e-6) / 1e12
+                out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
+                                   "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
+                                   "flops_per_launch": forward_flops(w), "note": "per forward operation inside a chain launch"}
+            else:
+                us = classes[dom]["net_us"]
+                nbytes = {"forward": forward_bytes(w), "backward": backward_bytes(w),
+                          "backward+forward": forward_bytes(w) + backward_bytes(w)}[dom]
+                flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_fwd + F_dh}[dom]
+                achieved = nbytes / (us * 1e-6) / 1e9
+                out["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                                   "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": pmc_traffic(w.name, kernel),
+                                   "avg_launch_us": us, "bytes_per_launch": nbytes,
+                                   "mfma_tflops": flops / (us * 1e-6) / 1e12,
+                                   "mfma_frac": flops / (us * 1e-6) / 1e12 / peak_tf}
     del sess
     store_all_ms = None
     if store_all:

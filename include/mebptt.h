@@ -294,6 +294,30 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
                         float* dW_ih, float* dW_hh, float* db, float* dh0, float* dc0,
                         float* dx, float* y_out, mebptt_stats* stats, void* stream);
 
+/* Forward operations that follow each other (Algorithm 2's forward loop, and the consecutive
+ * single-step pushes of a sub-sequence that fits into memory) are issued as "forward-chain"
+ * launches where the shape allows it (bf16 operands, LSTM, H a multiple of 128 and gate weights
+ * that fit into the registers and LDS of one XCD's compute units): one launch then carries up to
+ * 48 steps, keeps the gate weights on the chip, splits the batch over the 8 XCDs and lets the 32
+ * compute units of an XCD exchange h through their shared L2.  Results are bit-identical to the
+ * launch-per-step path.  Such a launch assumes that its 256 workgroups are all resident and dealt
+ * round-robin to the XCDs; each workgroup checks this, every wait inside is bounded by a wall
+ * clock, and a launch that cannot proceed gives up and raises a status word in the workspace
+ * instead of hanging.  mebptt_run_status copies that word to *status (host) after waiting for
+ * `stream`: 0 = every launch of the last run on this workspace completed; non-zero = a launch
+ * gave up and the run's outputs are invalid (1: a wait ran into its bound, 2: a workgroup was
+ * not placed on the XCD its id implies).  Two runs that use such launches must not overlap on one
+ * device (each would hold a part of the chip and wait for the rest): the library orders its own
+ * eager runs across streams with an event; replays of captured graphs are the caller's to order.
+ * Errors: EINVAL, EWORKSPACE, EHIP. */
+int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_t workspace_bytes, void* stream,
+                      int32_t* status);
+
+/* on = 0: from now on every forward operation gets a launch of its own, whatever the shape (the
+ * path the forward-chain launches are checked against, and the "before" of their measurement);
+ * on != 0 (the default) restores them.  Process-wide; not to be toggled while a run is enqueued. */
+int mebptt_forward_chain_enable(int32_t on);
+
 /* Releases what the library created on every device: the side streams and their events, the
  * events of the measurement hooks, the record of prepared workspaces.  Waits for the side
  * streams first; the caller makes sure no run is being enqueued.  The library can be used again
@@ -328,7 +352,8 @@ enum {
   MEBPTT_K_DGRAD = 3,    /* time-batched dx GEMM and the final dh0 GEMM                       */
   MEBPTT_K_SETUP = 4,    /* operand copies of the weights, zero fills, start-state copy       */
   MEBPTT_K_PAIR = 5,     /* one launch carrying a backward step and an independent forward op */
-  MEBPTT_K_CLASSES = 6
+  MEBPTT_K_CHAIN = 6,    /* one launch carrying a chain of forward operations, weights resident  */
+  MEBPTT_K_CLASSES = 7
 };
 typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
@@ -339,6 +364,9 @@ typedef struct {
    * events themselves disappears from the per-launch average. */
   int64_t forward_run_launches;
   double forward_run_ms;
+  /* Forward-chain launches are all bracketed: forward operations they carried, and their time. */
+  int64_t chain_steps;
+  double chain_ms;
 } mebptt_profile;
 /* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
  * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;

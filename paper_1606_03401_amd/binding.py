@@ -64,14 +64,14 @@ class mebptt_stats(C.Structure):
                 ("reserved", C.c_int32), ("peak_slot_bytes", C.c_size_t)]
 
 
-K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_PAIR, K_CLASSES = 0, 1, 2, 3, 4, 5, 6
-K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward")
+K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_PAIR, K_CHAIN, K_CLASSES = 0, 1, 2, 3, 4, 5, 6, 7
+K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward", "forward chain")
 
 
 class mebptt_profile(C.Structure):
     _fields_ = [("launches", C.c_int64 * K_CLASSES), ("sampled", C.c_int64 * K_CLASSES),
                 ("sampled_ms", C.c_double * K_CLASSES), ("forward_run_launches", C.c_int64),
-                ("forward_run_ms", C.c_double)]
+                ("forward_run_ms", C.c_double), ("chain_steps", C.c_int64), ("chain_ms", C.c_double)]
 
 
 # name -> (restype, argtypes): every symbol the header declares
@@ -112,6 +112,8 @@ SIGNATURES = {
     "mebptt_run_static": (C.c_int, [_DESC, _P] + [_P] * 7 + [_P, C.c_size_t] + [_P] * 7
                           + [C.POINTER(mebptt_stats), _P]),
     "mebptt_static_workspace_bytes": (C.c_size_t, []),
+    "mebptt_run_status": (C.c_int, [_DESC, _P, C.c_size_t, _P, C.POINTER(C.c_int32)]),
+    "mebptt_forward_chain_enable": (C.c_int, [C.c_int32]),
     "mebptt_shutdown": (C.c_int, []),
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
@@ -376,6 +378,17 @@ def mebptt_run_static(desc: mebptt_lstm_desc, plan: Plan, W_ih, W_hh, b, x, dy, 
 
 def mebptt_static_workspace_bytes() -> int:
     return lib().mebptt_static_workspace_bytes()
+
+
+def mebptt_run_status(desc: mebptt_lstm_desc, workspace, stream: Optional[int] = None) -> int:
+    """Waits for the stream and returns the status word of the last run on `workspace` (0 = fine)."""
+    out = C.c_int32(0)
+    _check(lib().mebptt_run_status(C.byref(desc), _ptr(workspace), _nbytes(workspace), _stream(stream), C.byref(out)))
+    return out.value
+
+
+def mebptt_forward_chain_enable(on: bool) -> None:
+    _check(lib().mebptt_forward_chain_enable(1 if on else 0))
 
 
 def mebptt_shutdown() -> None:

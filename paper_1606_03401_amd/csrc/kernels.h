@@ -91,6 +91,31 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
                                         const float* x_s, const float* src_unit, float* dst_unit, float* gates_units,
                                         hipStream_t st);
 
+// A chain of consecutive forward operations in one launch, with the gate weights resident on the
+// chip (shapes for which can_run_forward_chain() holds).  Step j (0-based) of the chain consumes
+// x_first + j*B*I; its state goes to steps[j].out and its gates to the two units at
+// steps[j].gates where these are not NULL (states nobody asked for never leave the chip).
+// `ring` (forward_chain_ring_bytes) and `sync` (forward_chain_sync_bytes, zero before the first
+// launch of a run) are workspace; `base` is the number of arrivals earlier launches of the run left in
+// the group counters (sum of forward_chain_arrivals over them), `launch` the number of those launches.
+// The word at forward_chain_status_offset() inside `sync` is a status word: 0, or non-zero when
+// a launch gave up (an XCD did not receive exactly 32 of the 256 workgroups, or a wait ran into
+// its wall-clock bound); results are then invalid.  Launches that overlap
+// on the device would wait for each other's compute units: the caller orders them.
+struct ChainStep {
+  float* out;
+  float* gates;
+};
+bool can_run_forward_chain(const Dims& d);
+int forward_chain_max_steps();
+size_t forward_chain_ring_bytes(const Dims& d);
+size_t forward_chain_sync_bytes();
+size_t forward_chain_status_offset();
+unsigned forward_chain_arrivals(int steps);
+hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, const float* x_first, const float* src_unit,
+                                const ChainStep* steps, int count, void* ring, unsigned* sync, unsigned base,
+                                unsigned launch, hipStream_t st);
+
 // out[slot*B + b][n] = sum_k dG[slot*BP + b][k] * WT[n][k] for slot < nslots, b < B, n < N;
 // ld_out = row stride of out.  Used for dx (WT = WTx, N = I) and for dh_0 (WT = WTh, N = H).
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,

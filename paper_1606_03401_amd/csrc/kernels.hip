@@ -292,6 +292,43 @@ hipError_t launch_copy_plane(const Dims& d, const float* src, float* dst, int ac
   return hipGetLastError();
 }
 
+// ---- pointwise forward step of one (sequence, hidden unit) -------------------------------------
+// G: the four gate-GEMM results of the unit (packed rows), bias: their biases, state_prev: c_{s-1}
+// (LSTM) or h_{s-1} in full precision (GRU).  Returns h_s; `second` is what the second plane of
+// the state unit keeps (LSTM: c_s; GRU: the recurrent part n_h of the candidate), `gate` the
+// values the backward step needs (LSTM: i, f, g, o; GRU: r, z, n).  Every kernel that computes a
+// forward step calls this one function, with the multiply-adds spelled out, so that a step gives
+// the same bits whichever kernel ran it.
+template <int CELL>
+__device__ inline float cell_forward(const float (&G)[4], const float4& bias, float state_prev, float& second,
+                                     float (&gate)[4]) {
+  if (CELL == 0) {
+    const float gi = sigmoidf_(G[0] + bias.x);
+    const float gf = sigmoidf_(G[1] + bias.y);
+    const float gg = tanhf_(G[2] + bias.z);
+    const float go = sigmoidf_(G[3] + bias.w);
+    const float c = __fmaf_rn(gf, state_prev, __fmul_rn(gi, gg));
+    gate[0] = gi;
+    gate[1] = gf;
+    gate[2] = gg;
+    gate[3] = go;
+    second = c;
+    return __fmul_rn(go, tanhf_(c));
+  } else {
+    // rows r, z, n_x, n_h: n = tanh(n_x + r * n_h), h = (1 - z) n + z h_prev
+    const float r = sigmoidf_(G[0] + bias.x);
+    const float z = sigmoidf_(G[1] + bias.y);
+    const float nh = G[3] + bias.w;
+    const float n = tanhf_(__fmaf_rn(r, nh, G[2] + bias.z));
+    gate[0] = r;
+    gate[1] = z;
+    gate[2] = n;
+    gate[3] = 0.0f;
+    second = nh;
+    return __fmaf_rn(1.0f - z, n, __fmul_rn(z, state_prev));
+  }
+}
+
 // ---- forward step: gate GEMM + LSTM pointwise -------------------------------------------------
 
 struct FwdParams {
@@ -466,36 +503,15 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
       continue;
     }
     const size_t e = eidx[q];
-    if (CELL == 0) {
-      const float gi = sigmoidf_(G[0] + bias[q].x);
-      const float gf = sigmoidf_(G[1] + bias[q].y);
-      const float gg = tanhf_(G[2] + bias[q].z);
-      const float go = sigmoidf_(G[3] + bias[q].w);
-      const float c = gf * c_prev[q] + gi * gg;
-      const float h = go * tanhf_(c);
-      HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
-      p.dst_c[e] = c;
-      if (p.g_i) {
-        p.g_i[e] = gi;
-        p.g_f[e] = gf;
-        p.g_g[e] = gg;
-        p.g_o[e] = go;
-      }
-    } else {
-      // GRU: rows r, z, n_x, n_h.  The second plane of the state unit keeps n_h (the recurrent
-      // part of the candidate before the reset gate), which the backward step needs.
-      const float r = sigmoidf_(G[0] + bias[q].x);
-      const float z = sigmoidf_(G[1] + bias[q].y);
-      const float nh = G[3] + bias[q].w;
-      const float n = tanhf_(G[2] + bias[q].z + r * nh);
-      const float h = (1.0f - z) * n + z * c_prev[q];
-      HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
-      p.dst_c[e] = nh;
-      if (p.g_i) {
-        p.g_i[e] = r;
-        p.g_f[e] = z;
-        p.g_g[e] = n;
-      }
+    float second, gate[4];
+    const float h = cell_forward<CELL>(G, bias[q], c_prev[q], second, gate);
+    HP_::store(p.dst_h, eb[q], eu[q], h, nsh, p.H, hhalf);
+    p.dst_c[e] = second;
+    if (p.g_i) {
+      p.g_i[e] = gate[0];
+      p.g_f[e] = gate[1];
+      p.g_g[e] = gate[2];
+      if (CELL == 0) p.g_o[e] = gate[3];
     }
   }
 }
@@ -898,6 +914,413 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
   else
     d.cell ? launch_pair_t<float, 1>(d, f, b, st) : launch_pair_t<float, 0>(d, f, b, st);
   return hipGetLastError();
+}
+
+// ---- forward chain with resident weights -----------------------------------------------------
+// Consecutive forward operations (Algorithm 2's forward loop; also the single-step pushes that
+// follow each other when memory is plentiful) depend on each other only through h, so a chain of
+// them can run inside ONE launch if the gate weights stay on the chip and only h travels.  The
+// chip is split along the batch: XCD g (one of 8, each with its own L2) takes the sequences
+// [g*nb, (g+1)*nb) and never needs anything from another XCD, so no step synchronises across
+// XCDs.  Inside an XCD the 32 workgroups (one per compute unit) split the hidden units: workgroup
+// `rank` owns units [rank*H/32, (rank+1)*H/32), keeps the 4*H/32 packed weight rows of those units
+// in registers (and a part in LDS) for the whole launch, and per step
+//   1. waits until all 32 workgroups of its XCD have published their slice of h_{s-1}
+//      (a counter in the XCD's L2, bumped with an atomic add and polled with agent-scope loads),
+//   2. fetches the bf16 h_{s-1} of its sequences from the exchange ring with loads that bypass the
+//      compute unit's vector cache (the ring is written through to the L2 the 32 share),
+//   3. runs its slice of the gate GEMM and the pointwise step, keeps c in registers, publishes
+//      its slice of h_s, and stores the full state only where the schedule wants one.
+// Which XCD a workgroup runs on is read from the hardware (register XCC_ID), not inferred from
+// its id: workgroups are dealt round-robin to the XCDs, but where the deal starts depends on the
+// launches before.  A workgroup takes the next free rank of its XCD from a counter; the launch
+// relies on every XCD receiving exactly 32 of the 256 workgroups, checks it (a rank counter that
+// runs past 32 raises the status word; an XCD that gets fewer never completes its first wait,
+// which is bounded by a wall-clock limit like every other) and gives up rather than compute on
+// an assumption that does not hold.
+// Sums are formed exactly as forward_body forms them (KS partial sums over the macro steps
+// w, w+KS, ..., added in the order 0..KS-1), so a step gives the same bits either way.
+constexpr int RES_MAX_STEPS = 48;   // steps of one launch: their destinations travel as kernel arguments
+constexpr int RES_RING = 4;         // h slices in flight (two would do: a step ahead at most)
+constexpr int RES_WGS = 256, RES_GROUPS = 8, RES_MEMBERS = RES_WGS / RES_GROUPS;
+constexpr long long RES_WAIT_TICKS = 50000000;   // 0.5 s of the 100 MHz wall clock
+
+struct ResStep {
+  float* out;     // unit that receives (h, c) of this step, or NULL
+  float* gates;   // two units that receive (i, f), (g, o), or NULL
+};
+struct ResParams {
+  const void* Wp;
+  const float* bp;
+  const float* x0;     // x of the first step of this launch
+  const float* src;    // unit holding the input state of the first step
+  void* ring;          // RES_RING x [BP][KH] bf16, fragment-tiled like the 16-bit h plane
+  unsigned* sync;      // words: arrival counter of XCD g at [g*64], rank counter at [512 + g*64], status at [1024]
+  unsigned base;       // value of every arrival counter when the launch starts
+  unsigned launch;     // chain launches of this run before this one (every rank counter stands at 32 * launch)
+  int count;
+  int B, I, H, KX, KH, BP, nb;
+  size_t unit;         // floats per unit
+  ResStep step[RES_MAX_STEPS];
+};
+
+__device__ inline unsigned xcc_id() {
+  unsigned v;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+  return v & 0xf;
+}
+
+template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
+__global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
+  using T = __bf16;
+  using M = Mma<T>;
+  constexpr int VEC = 8, KSTEP = 32, FRAG = 64 * VEC;
+  constexpr int NT = NRT * NBT, NSR = NSW - NSL;
+  constexpr int UW = NRT * 4, ITEMS = NBT * 16 * UW, NTHR = 64 * KS, IPT = (ITEMS + NTHR - 1) / NTHR;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* red = reinterpret_cast<float*>(smem);                               // [KS][NT][4][64]
+  T* wl = reinterpret_cast<T*>(smem + (size_t)KS * NT * 4 * 64 * sizeof(float));   // [KS][NRT][NSL] fragments
+  __shared__ int s_go, s_g, s_rank;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lrow = lane & 15, lq = lane >> 4;
+  if (threadIdx.x == 0) {
+    const unsigned xcc = xcc_id();
+    int ok = xcc < (unsigned)RES_GROUPS;
+    unsigned ticket = 0;
+    if (ok) {
+      ticket = __hip_atomic_fetch_add(p.sync + 512 + xcc * 64, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ok = ticket / RES_MEMBERS == p.launch;   // more than 32 workgroups on this XCD: ranks would collide
+    }
+    if (!ok) __hip_atomic_store(p.sync + 1024, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_go = ok;
+    s_g = ok ? (int)xcc : 0;
+    s_rank = (int)(ticket % RES_MEMBERS);
+  }
+  __syncthreads();
+  if (!s_go) return;
+  const int g = s_g, rank = s_rank;
+  constexpr int nsteps = KS * NSW;
+  const int nsx = p.KX / KSTEP, nsh = p.KH / KSTEP;
+  const size_t hhalf = (size_t)p.BP * p.KH;
+  const int b_lo = g * p.nb, b_hi = min(p.B, b_lo + p.nb);
+  const int nbt_all = p.BP / 16;
+  const int ct0 = min(b_lo / 16, nbt_all - 1);
+  unsigned* ctr = p.sync + g * 64;
+  unsigned* status = p.sync + 1024;
+
+  // This workgroup's packed weight rows: row tiles rank*NRT .. +NRT, this wave's macro steps
+  // wave, wave + KS, ...; the last NSL of them are parked in LDS (read back by this wave only).
+  typename M::Frag wr[NRT][NSR > 0 ? NSR : 1];
+  {
+    const T* wbase = reinterpret_cast<const T*>(p.Wp) + ((size_t)rank * NRT * nsteps * 64 + lane) * VEC;
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int i = 0; i < NSW; ++i) {
+        const typename M::Frag f = M::load(wbase + ((size_t)rt * nsteps + wave + KS * i) * FRAG);
+        if (i < NSR)
+          wr[rt][i] = f;
+        else
+          *reinterpret_cast<typename M::Frag*>(&wl[((size_t)(wave * NRT + rt) * NSL + (i - NSR)) * FRAG + lane * VEC]) = f;
+      }
+  }
+
+  // Pointwise items of this thread: item = (output tile, lane of the MFMA layout), i.e. the
+  // (sequence, unit) whose four gate sums that lane holds, so that the partial sums are read back
+  // from LDS at consecutive addresses by consecutive threads.  c stays in registers.
+  bool mine[IPT];
+  int ib[IPT], iu[IPT], icell[IPT];
+  float4 bias[IPT];
+  float c_state[IPT];
+#pragma unroll
+  for (int q = 0; q < IPT; ++q) {
+    const int item = (int)threadIdx.x + q * NTHR;
+    const int tile = item >> 6, il = item & 63;          // tile = rt * NBT + bt
+    const int rt = tile / NBT, bt = tile % NBT;
+    const int b = (ct0 + bt) * 16 + (il & 15), u = rank * UW + rt * 4 + (il >> 4);
+    mine[q] = item < ITEMS && b >= b_lo && b < b_hi;
+    ib[q] = b;
+    iu[q] = u;
+    icell[q] = tile * 4 * 64 + il;   // where the four gate sums of this item sit inside one wave's block of `red`
+    bias[q] = float4{0.f, 0.f, 0.f, 0.f};
+    c_state[q] = 0.0f;
+    if (mine[q]) {
+      bias[q] = *reinterpret_cast<const float4*>(p.bp + 4 * u);
+      c_state[q] = p.src[hhalf + (size_t)b * p.H + u];
+    }
+  }
+  const bool x_vec = (p.I & 3) == 0;
+#ifdef MEBPTT_CHAIN_TIMELINE
+  long long tl_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long tl_prev = wall_clock64();
+#define TL_MARK(i)                                   \
+  do {                                               \
+    if (threadIdx.x == 0 && j > 0) {                 \
+      const long long now_ = wall_clock64();         \
+      tl_sum[i] += now_ - tl_prev;                   \
+      tl_prev = now_;                                \
+    }                                                \
+  } while (0)
+#else
+#define TL_MARK(i)
+#endif
+
+  // Raw x values of this wave's x macro steps for the step about to run (NSXW = how many of the
+  // wave's first steps can fall into the x segment at all: KX / 32 / KS rounded up).
+  RawAct<VEC> xraw[NSXW][NBT];
+  auto fetch_x = [&](int j) {
+    const float* x_j = p.x0 + (size_t)j * p.B * p.I;
+#pragma unroll
+    for (int i = 0; i < NSXW; ++i) {
+      const int s = wave + KS * i;
+      if (s < nsx) {
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt) {
+          const int b_ld = min(min(ct0 + bt, nbt_all - 1) * 16 + lrow, p.B - 1);
+          xraw[i][bt] = load_raw<VEC>(x_j + (size_t)b_ld * p.I, s * KSTEP + VEC * lq, p.I, x_vec);
+        }
+      }
+    }
+  };
+  fetch_x(0);
+
+  for (int j = 0; j < p.count; ++j) {
+#ifdef MEBPTT_CHAIN_TIMELINE
+    if (threadIdx.x == 0) tl_prev = wall_clock64();
+#endif
+    // x fragments: the raw fp32 values were requested a step ahead (see below) and are converted
+    // now; they do not depend on the other workgroups
+    typename M::Frag bf[NSW][NBT];
+#pragma unroll
+    for (int i = 0; i < NSXW; ++i)
+      if (wave + KS * i < nsx) {
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt) bf[i][bt] = M::from_f32(xraw[i][bt].v);
+      }
+    TL_MARK(0);   // x fragments fetched and converted
+    if (j > 0) {
+      // all 32 workgroups of this XCD have published h of the previous step?
+      if (threadIdx.x == 0) {
+        const unsigned target = p.base + (unsigned)j * RES_MEMBERS;
+        int ok = 1, polls = 0;
+        long long t0 = 0;
+        // agent-scope loads see the counter in the L2 (32 pollers do not queue behind each other as
+        // read-modify-writes would: 1.95 -> 1.59 us per exchange round in isolation)
+        while ((int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+          if ((++polls & 15) == 0) {
+            const long long now = wall_clock64();
+            if (t0 == 0) t0 = now;
+            if (now - t0 > RES_WAIT_TICKS ||
+                __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+              __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              ok = 0;
+              break;
+            }
+          }
+        }
+        s_go = ok;
+      }
+      TL_MARK(1);   // wait for the other workgroups
+      __syncthreads();
+      if (!s_go) return;
+    }
+    TL_MARK(2);
+    // h fragments: the stored input state for the first step, then the exchange ring
+    {
+      const T* hsrc = (j == 0) ? reinterpret_cast<const T*>(p.src)
+                               : reinterpret_cast<const T*>(p.ring) + (size_t)((j - 1) % RES_RING) * hhalf;
+#pragma unroll
+      for (int i = 0; i < NSW; ++i) {
+        const int s = wave + KS * i;
+        if (s >= nsx) {
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt) {
+            const T* fp = hsrc + (((size_t)min(ct0 + bt, nbt_all - 1) * nsh + (s - nsx)) * 64 + lane) * VEC;
+            if (j == 0) {
+              bf[i][bt] = M::load(fp);
+            } else {
+              // agent-scope loads: they skip this compute unit's vector cache and are served by the XCD's L2
+              union { unsigned long long q[2]; typename M::Frag f; } cv;
+              const unsigned long long* qp = reinterpret_cast<const unsigned long long*>(fp);
+              cv.q[0] = __hip_atomic_load(qp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              cv.q[1] = __hip_atomic_load(qp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              bf[i][bt] = cv.f;
+            }
+          }
+        }
+      }
+    }
+    f32x4 acc[NRT][NBT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NSW; ++i)
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        const typename M::Frag a =
+            (i < NSR) ? wr[rt][i < NSR ? i : 0]
+                      : M::load(&wl[((size_t)(wave * NRT + rt) * NSL + (i - NSR)) * FRAG + lane * VEC]);
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = M::mma(a, bf[i][bt], acc[rt][bt]);
+      }
+    if (j + 1 < p.count) fetch_x(j + 1);   // in flight while this step finishes and the next wait runs
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((wave * NT + rt * NBT + bt) * 4 + r) * 64 + lane] = acc[rt][bt][r];
+    TL_MARK(3);   // h fetched, GEMM slice done, partial sums in LDS
+    __syncthreads();
+    TL_MARK(4);
+    const ResStep dst = p.step[j];
+    T* ring_out = reinterpret_cast<T*>(p.ring) + (size_t)(j % RES_RING) * hhalf;
+    const bool publish = j + 1 < p.count;
+#pragma unroll
+    for (int q = 0; q < IPT; ++q) {
+      if (!mine[q]) continue;
+      float G[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < KS; ++w)   // fixed order, as in forward_body
+#pragma unroll
+        for (int r = 0; r < 4; ++r) G[r] += red[w * NT * 4 * 64 + icell[q] + r * 64];
+      float second, gate[4];
+      const float h = cell_forward<0>(G, bias[q], c_state[q], second, gate);
+      c_state[q] = second;
+      const int b = ib[q], u = iu[q];
+      if (publish) {
+        // Units u and u + 1 of one sequence sit 16 lanes apart in this layout and next to each other
+        // in the ring: the lane of the even unit stores both as one dword (the rows of a tile belong
+        // to one XCD or, split in halves, to two -- a lane and its partner are always on the same side).
+        const unsigned hi16 = (__float_as_uint(h) + 0x8000u) >> 16;
+        const unsigned other = __shfl_xor(hi16, 16);
+        if (((threadIdx.x >> 4) & 1) == 0)
+          reinterpret_cast<unsigned*>(ring_out)[ft_offset<T>(b, u, nsh) >> 1] = hi16 | (other << 16);
+      }
+      if (dst.out) {
+        HPlane<T>::store(dst.out, b, u, h, nsh, p.H, hhalf);
+        dst.out[hhalf + (size_t)b * p.H + u] = second;
+      }
+      if (dst.gates) {
+        const size_t e = (size_t)b * p.H + u, plane = (size_t)p.B * p.H;
+        dst.gates[e] = gate[0];
+        dst.gates[plane + e] = gate[1];
+        dst.gates[p.unit + e] = gate[2];
+        dst.gates[p.unit + plane + e] = gate[3];
+      }
+    }
+    TL_MARK(5);   // pointwise step, stores issued
+    if (publish) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's slice of h has reached the L2
+      TL_MARK(6);
+      __syncthreads();
+      if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      TL_MARK(7);
+    }
+  }
+#ifdef MEBPTT_CHAIN_TIMELINE
+  if (threadIdx.x == 0 && p.count > 4) {   // ticks of the 100 MHz clock per phase, summed over the launch's steps
+    unsigned long long* outp = reinterpret_cast<unsigned long long*>(p.sync + 1088) + (size_t)(g * RES_MEMBERS + rank) * 9;
+    for (int i = 0; i < 8; ++i) outp[i] += (unsigned long long)tl_sum[i];
+    outp[8] += (unsigned long long)(p.count - 1);
+  }
+#endif
+#undef TL_MARK
+}
+
+// Shape classes with an instantiation: {NRT = H/128, NSW = macro steps per wave, NSL, KS, NBT}.
+struct ResConfig {
+  int nrt, nsw, nsl, ks, nbt, nsxw;
+};
+static const ResConfig RES_CONFIGS[] = {
+    {8, 5, 1, 8, 1, 1},   // H = 1024, I <= 256
+    {4, 5, 0, 4, 1, 1}, {4, 5, 0, 4, 2, 1},   // H = 512, I <= 128
+    {2, 4, 0, 4, 1, 2}, {2, 4, 0, 4, 2, 2},   // H = 256, 128 < I <= 256
+    {1, 2, 0, 4, 1, 1}, {1, 2, 0, 4, 2, 1},   // H = 128, I <= 128
+};
+
+// Index into RES_CONFIGS for this shape, or -1 when the chain kernel does not apply.
+static int resident_config(const Dims& d) {
+  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H) return -1;
+  const int nsteps = d.KP / 32;
+  const FwdConfig fc = forward_config<__bf16>(d);
+  const int ks = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;   // the K split of the per-step kernels
+  if (nsteps % ks != 0) return -1;
+  const int nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  int nbt = 1;
+  for (int g = 0; g < RES_GROUPS; ++g) {
+    const int lo = g * nb, hi = (lo + nb < d.B ? lo + nb : d.B);
+    if (lo >= d.B) break;
+    const int span = (hi - 1) / 16 - lo / 16 + 1;
+    nbt = span > nbt ? span : nbt;
+  }
+  for (size_t i = 0; i < sizeof RES_CONFIGS / sizeof RES_CONFIGS[0]; ++i) {
+    const ResConfig& c = RES_CONFIGS[i];
+    if (c.nrt == d.H / 128 && c.ks == ks && c.nsw == nsteps / ks && c.nbt == nbt && c.nsxw == (d.KX / 32 + ks - 1) / ks)
+      return (int)i;
+  }
+  return -1;
+}
+
+bool can_run_forward_chain(const Dims& d) { return resident_config(d) >= 0; }
+int forward_chain_max_steps() { return RES_MAX_STEPS; }
+size_t forward_chain_ring_bytes(const Dims& d) { return (size_t)RES_RING * d.BP * d.KH * sizeof(__bf16); }
+#ifdef MEBPTT_CHAIN_TIMELINE
+size_t forward_chain_sync_bytes() { return (1088 + 2 * 9 * RES_WGS) * sizeof(unsigned); }
+#else
+size_t forward_chain_sync_bytes() { return (1024 + 64) * sizeof(unsigned); }
+#endif
+size_t forward_chain_status_offset() { return 1024 * sizeof(unsigned); }
+unsigned forward_chain_arrivals(int steps) { return steps > 1 ? (unsigned)(steps - 1) * RES_MEMBERS : 0u; }
+
+template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
+static hipError_t launch_chain_cfg(const ResParams& p, hipStream_t st) {
+  const size_t lds = (size_t)KS * NRT * NBT * 4 * 64 * sizeof(float) + (size_t)KS * NRT * NSL * 64 * 8 * sizeof(__bf16);
+  static bool configured = false;   // per instantiation; the attribute only has to be set once
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW><<<dim3(RES_WGS), dim3(64 * KS), lds, st>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, const float* x_first, const float* src_unit,
+                                const ChainStep* steps, int count, void* ring, unsigned* sync, unsigned base,
+                                unsigned launch, hipStream_t st) {
+  const int cfg = resident_config(d);
+  if (cfg < 0 || count < 1 || count > RES_MAX_STEPS) return hipErrorInvalidValue;
+  ResParams p{};
+  p.Wp = Wp;
+  p.bp = bp;
+  p.x0 = x_first;
+  p.src = src_unit;
+  p.ring = ring;
+  p.sync = sync;
+  p.base = base;
+  p.launch = launch;
+  p.count = count;
+  p.B = d.B;
+  p.I = d.I;
+  p.H = d.H;
+  p.KX = d.KX;
+  p.KH = d.KH;
+  p.BP = d.BP;
+  p.nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  p.unit = d.unit;
+  for (int j = 0; j < count; ++j) p.step[j] = ResStep{steps[j].out, steps[j].gates};
+  switch (cfg) {
+    case 0: return launch_chain_cfg<8, 5, 1, 8, 1, 1>(p, st);
+    case 1: return launch_chain_cfg<4, 5, 0, 4, 1, 1>(p, st);
+    case 2: return launch_chain_cfg<4, 5, 0, 4, 2, 1>(p, st);
+    case 3: return launch_chain_cfg<2, 4, 0, 4, 1, 2>(p, st);
+    case 4: return launch_chain_cfg<2, 4, 0, 4, 2, 2>(p, st);
+    case 5: return launch_chain_cfg<1, 2, 0, 4, 1, 1>(p, st);
+    default: return launch_chain_cfg<1, 2, 0, 4, 2, 1>(p, st);
+  }
 }
 
 // ---- data-gradient GEMM: out[row][n] = sum_k dG[row][k] * WT[n][k] ---------------------------

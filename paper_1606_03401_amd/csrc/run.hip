@@ -28,7 +28,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Workspace {
-  size_t Wp, bp, WTh, WTx, state, dWacc, dc, dG[2], dGT[2], aT[2], total;
+  size_t Wp, bp, WTh, WTx, state, dWacc, dc, sync, dG[2], dGT[2], aT[2], ring, total;
 };
 
 Workspace layout(const Dims& d) {
@@ -48,9 +48,11 @@ Workspace layout(const Dims& d) {
   w.state = take(9 * unit);   // T0 | T1 | core A (3 units) | copy of (h0,c0) | core B (3 units)
   w.dWacc = take(wgrad_accumulator_bytes(d));
   w.dc = take((size_t)d.B * d.H * sizeof(float));
+  w.sync = take(forward_chain_sync_bytes());   // counters and status word of the forward-chain launches: cleared with dc
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
   for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)d.NA * d.KC * op);
+  w.ring = take(can_run_forward_chain(d) ? forward_chain_ring_bytes(d) : 0);
   w.total = off;
   return w;
 }
@@ -132,6 +134,12 @@ struct SideStream {
 };
 SideStream g_side[MAX_DEVICES];
 std::mutex g_run_mutex;
+// Forward-chain launches want every compute unit of the device; two of them from different streams
+// would each hold a part of the chip and wait for the rest.  The last run that used them records
+// this event when its work is enqueued and the next such run makes its stream wait for it.
+bool g_chain_enabled = true;
+hipEvent_t g_chain_done[MAX_DEVICES] = {};
+bool g_chain_recorded[MAX_DEVICES] = {};
 
 hipError_t get_side_stream(SideStream** out) {
   int dev = 0;
@@ -251,6 +259,9 @@ int mebptt_profile_collect(mebptt_profile* out) {
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, s.start, s.stop);
     if (e != hipSuccess) {
       rc = set_error(MEBPTT_EHIP, "event timing failed: %s", hipGetErrorString(e));
+    } else if (s.cls == MEBPTT_K_CHAIN) {
+      out->chain_steps += s.launches;
+      out->chain_ms += ms;
     } else {
       out->forward_run_launches += s.launches;
       out->forward_run_ms += ms;
@@ -339,6 +350,36 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
                   workspace_bytes, dW_ih, dW_hh, db, dh0, dc0, dx, y_out, stats, stream);
 }
 
+int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_t workspace_bytes, void* stream,
+                      int32_t* status) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!status) return set_error(MEBPTT_EINVAL, "status is NULL");
+  if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
+  const Workspace w = layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell));
+  if (workspace_bytes < w.total)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  HIP_TRY(hipStreamSynchronize(st));
+  unsigned word = 0;
+  HIP_TRY(hipMemcpy(&word, reinterpret_cast<const char*>(workspace) + w.sync + forward_chain_status_offset(), sizeof word,
+                    hipMemcpyDeviceToHost));
+  *status = (int32_t)word;
+  return MEBPTT_OK;
+}
+
+#ifdef MEBPTT_CHAIN_TIMELINE
+size_t mebptt_debug_sync_offset(const mebptt_lstm_desc* desc) {
+  return layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).sync;
+}
+#endif
+
+int mebptt_forward_chain_enable(int32_t on) {
+  std::lock_guard<std::mutex> lock(g_run_mutex);
+  g_chain_enabled = on != 0;
+  return MEBPTT_OK;
+}
+
 int mebptt_shutdown(void) {
   std::lock_guard<std::mutex> lock(g_run_mutex);
   int rc = MEBPTT_OK;
@@ -358,6 +399,11 @@ int mebptt_shutdown(void) {
     }
     drop(hipStreamDestroy(s.stream));
     s = SideStream{};
+  }
+  for (int dev = 0; dev < MAX_DEVICES; ++dev) {
+    if (g_chain_done[dev]) drop(hipEventDestroy(g_chain_done[dev]));
+    g_chain_done[dev] = nullptr;
+    g_chain_recorded[dev] = false;
   }
   if (have_dev) drop(hipSetDevice(cur));
   Profiler& p = g_prof;
@@ -553,6 +599,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   bool have_pending = false;
   BackwardArgs pend{};
   int pend_step = 0;
+  int chain_order_dev = -1;   // device whose chain-ordering event this run waits for and records
 
   // Launches the held-back backward step, alone or fused with one forward operation, then the
   // time-batched work of its chunk if the step completed one.
@@ -595,54 +642,135 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     return MEBPTT_OK;
   };
 
-  for (const mebptt_op& op : plan->ops) {
+  // Forward operations that follow each other (a forward run, or consecutive runs each starting
+  // from the state the one before left) form a chain; on shapes whose weights fit on the chip a
+  // chain goes out as forward-chain launches of up to forward_chain_max_steps() steps instead of
+  // one launch per step.  Not in the no-allocation path, which owns no event to keep two such runs
+  // from overlapping on the device.
+  const bool chain_ok = mode != RUN_STATIC && g_chain_enabled && can_run_forward_chain(d);
+  constexpr int CHAIN_MIN_STEPS = 3;
+  unsigned chain_base = 0;        // arrivals left in the group counters by this run's earlier chain launches
+  unsigned chain_launches = 0;    // chain launches of this run so far
+  bool chain_used = false;
+  struct FStep {
+    int step;
+    float* dst;      // where the per-step path writes the state (a transient unit for intermediate steps)
+    float* gates;
+    bool wanted;     // a later launch reads this state; the others need not leave the chip
+  };
+  std::vector<FStep> fsteps;
+  const std::vector<mebptt_op>& ops = plan->ops;
+
+  for (size_t oi = 0; oi < ops.size();) {
+    const mebptt_op& op = ops[oi];
     if (op.op == MEBPTT_OP_FWD_RUN) {
-      if (op.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
+      size_t oe = oi + 1;
+      if (chain_ok)
+        while (oe < ops.size() && ops[oe].op == MEBPTT_OP_FWD_RUN && ops[oe].src == ops[oe - 1].dst &&
+               ops[oe - 1].dst != MEBPTT_LOC_CORE)
+          ++oe;
+      fsteps.clear();
+      for (size_t k = oi; k < oe; ++k) {
+        const mebptt_op& o = ops[k];
+        if (o.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
+        touch(o.src, 1);
+        touch(o.dst, o.keep ? 3 : 1);
+        if (o.count > 1) touch(o.prev, 1);
+        for (int j = 1; j <= o.count; ++j) {
+          float* dst = (j == o.count) ? loc(o.dst)
+                                      : (j == o.count - 1 ? loc(o.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
+          fsteps.push_back(FStep{o.step + j - 1, dst, (j == o.count && o.keep) ? dst + unit : nullptr, j >= o.count - 1});
+        }
+      }
       const float* cur = loc(op.src);
-      touch(op.src, 1);
-      touch(op.dst, op.keep ? 3 : 1);
-      if (op.count > 1) touch(op.prev, 1);
-      // Measurement hook: one event pair around the back-to-back launches of a long run (all but
-      // its first step, which may share a launch with a backward step).
-      const bool bracket = use_profiler && g_prof.every_n > 0 && op.count >= 9 && g_prof.runs.size() < 100000;
-      Sample run_sample{MEBPTT_K_FORWARD, nullptr, nullptr, op.count - 1};
-      for (int j = 1; j <= op.count; ++j) {
-        if (bracket && j == 2) {
+      size_t fi = 0;
+      const size_t total = fsteps.size();
+      auto x_of = [&](int step) { return x + (size_t)(step - 1) * d.B * d.I; };
+      if (have_pending) {
+        // units written by the first forward step vs units read by the held-back backward step
+        const FStep& f = fsteps[0];
+        const float* w_lo = f.dst;
+        const float* w_hi = f.dst + (f.gates ? 3 : 1) * unit;
+        const bool clash = (w_lo < pend.state + 3 * unit && pend.state < w_hi) ||
+                           (w_lo < pend.prev + unit && pend.prev < w_hi);
+        if (fuse && !clash) {
+          rc = flush_backward(x_of(f.step), cur, f.dst, f.gates);
+          if (rc) return rc;
+          cur = f.dst;
+          fi = 1;
+        } else {
+          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+          if (rc) return rc;
+        }
+      }
+      if (chain_ok && total - fi >= (size_t)CHAIN_MIN_STEPS) {
+        if (!chain_used) {
+          chain_used = true;
+          int dev = 0;
+          HIP_TRY(hipGetDevice(&dev));
+          hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+          HIP_TRY(hipStreamIsCapturing(st, &cap));
+          chain_order_dev = (cap == hipStreamCaptureStatusNone && dev >= 0 && dev < MAX_DEVICES) ? dev : -1;
+          if (chain_order_dev >= 0 && g_chain_recorded[chain_order_dev])
+            HIP_TRY(hipStreamWaitEvent(st, g_chain_done[chain_order_dev], 0));
+        }
+        const int max_steps = forward_chain_max_steps();
+        ChainStep cs[64];
+        while (fi < total) {
+          const int n = (int)std::min<size_t>(total - fi, (size_t)max_steps);
+          for (int j = 0; j < n; ++j) {
+            const FStep& f = fsteps[fi + j];
+            const bool keep_state = f.wanted || j == n - 1;   // the last state of a launch feeds the next launch
+            cs[j] = ChainStep{keep_state ? f.dst : nullptr, f.gates};
+          }
+          const float* x_first = x_of(fsteps[fi].step);
+          // Measurement hook: every chain launch is bracketed (they are few), with its step count.
+          const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+          Sample smp{MEBPTT_K_CHAIN, nullptr, nullptr, n};
+          if (bracket) {
+            smp.start = g_prof.get();
+            smp.stop = g_prof.get();
+            if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+            HIP_TRY(hipEventRecord(smp.start, st));
+          }
+          HIP_TRY(launch_forward_chain(d, Wp, bp, x_first, cur, cs, n, ws + w.ring,
+                                       reinterpret_cast<unsigned*>(ws + w.sync), chain_base, chain_launches, st));
+          ++chain_launches;
+          if (bracket) {
+            HIP_TRY(hipEventRecord(smp.stop, st));
+            g_prof.runs.push_back(smp);
+          }
+          if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_CHAIN];
+          chain_base += forward_chain_arrivals(n);
+          cur = fsteps[fi + n - 1].dst;
+          fi += n;
+          fwd += n;
+        }
+      } else {
+        // Measurement hook: one event pair around the back-to-back launches of a long run.
+        const bool bracket = use_profiler && g_prof.every_n > 0 && total - fi >= 8 && g_prof.runs.size() < 100000;
+        Sample run_sample{MEBPTT_K_FORWARD, nullptr, nullptr, (int64_t)(total - fi)};
+        if (bracket) {
           run_sample.start = g_prof.get();
           run_sample.stop = g_prof.get();
           if (!run_sample.start || !run_sample.stop) return set_error(MEBPTT_EHIP, "event creation failed");
           HIP_TRY(hipEventRecord(run_sample.start, st));
           g_prof.in_run = true;
         }
-        const int step = op.step + j - 1;
-        float* dst = (j == op.count) ? loc(op.dst)
-                                     : (j == op.count - 1 ? loc(op.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
-        float* gates = (j == op.count && op.keep) ? dst + unit : nullptr;
-        const float* x_s = x + (size_t)(step - 1) * d.B * d.I;
-        if (have_pending) {
-          // units written by this forward step vs units read by the held-back backward step
-          const float* w_lo = dst;
-          const float* w_hi = dst + (gates ? 3 : 1) * unit;
-          const bool clash = (w_lo < pend.state + 3 * unit && pend.state < w_hi) ||
-                             (w_lo < pend.prev + unit && pend.prev < w_hi);
-          if (fuse && !clash) {
-            rc = flush_backward(x_s, cur, dst, gates);
-            if (rc) return rc;
-            cur = dst;
-            continue;
-          }
-          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
-          if (rc) return rc;
+        for (; fi < total; ++fi) {
+          const FStep& f = fsteps[fi];
+          HIP_TRY(tm(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_of(f.step), cur, f.dst, f.gates, st); }));
+          cur = f.dst;
+          ++fwd;
         }
-        HIP_TRY(tm(MEBPTT_K_FORWARD, st, [&] { return launch_forward(d, Wp, bp, x_s, cur, dst, gates, st); }));
-        cur = dst;
-        ++fwd;
+        if (bracket) {
+          g_prof.in_run = false;
+          HIP_TRY(hipEventRecord(run_sample.stop, st));
+          g_prof.runs.push_back(run_sample);
+        }
       }
-      if (bracket) {
-        g_prof.in_run = false;
-        HIP_TRY(hipEventRecord(run_sample.stop, st));
-        g_prof.runs.push_back(run_sample);
-      }
+      oi = oe;
+      continue;
     } else if (op.op == MEBPTT_OP_BWD) {
       if (have_pending) {
         rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
@@ -677,6 +805,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     } else {
       return set_error(MEBPTT_EINVAL, "unknown schedule entry %d", op.op);
     }
+    ++oi;
   }
   if (have_pending) {
     rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
@@ -696,6 +825,13 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   HIP_TRY(tm(MEBPTT_K_WGRAD, st, [&] {
     return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, db, st);
   }));
+
+  if (chain_used && chain_order_dev >= 0) {
+    if (!g_chain_done[chain_order_dev])
+      HIP_TRY(hipEventCreateWithFlags(&g_chain_done[chain_order_dev], hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(g_chain_done[chain_order_dev], st));
+    g_chain_recorded[chain_order_dev] = true;
+  }
 
   if (stats) {
     stats->forward_ops = fwd;

@@ -107,8 +107,17 @@ class Session:
     def replay(self) -> None:
         self._graph.replay()
 
+    def check_status(self) -> None:
+        """Raises if a launch of the last run gave up (see mebptt_run_status)."""
+        if self.workspace is None:
+            return
+        status = mb.mebptt_run_status(self.desc, self.workspace)
+        if status:
+            raise RuntimeError(f"mebptt run gave up with status {status}: outputs are invalid")
+
     def fetch(self, stats=None) -> Outputs:
         torch.cuda.synchronize(self.dev)
+        self.check_status()
         dn = lambda t: None if t is None else t.cpu().numpy()
         return Outputs(dn(self.dW_ih), dn(self.dW_hh), dn(self.db), dn(self.dh0), dn(self.dc0), dn(self.dx),
                        dn(self.y), stats)
@@ -116,6 +125,7 @@ class Session:
     def run_and_fetch(self) -> Outputs:
         stats = self.run()
         torch.cuda.synchronize(self.dev)
+        self.check_status()
         dn = lambda t: None if t is None else t.cpu().numpy()
         return Outputs(dn(self.dW_ih), dn(self.dW_hh), dn(self.db), dn(self.dh0), dn(self.dc0), dn(self.dx),
                        dn(self.y), stats)

@@ -1,0 +1,123 @@
+"""GPU tests of the forward-chain launches (a chain of forward operations in one launch, gate
+weights resident on the chip, the batch split over the XCDs): against the float64 oracle, bit for
+bit against the launch-per-step path on the same inputs, for every strategy and many budgets, on
+every shape class the kernel is instantiated for, with ragged batches, and from two host threads
+at once."""
+import threading
+
+import numpy as np
+import pytest
+
+from oracle import lstm_bptt as ob
+from paper_1606_03401_amd import binding as mb
+from paper_1606_03401_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+FIELDS = ("dW_ih", "dW_hh", "db", "dh0", "dc0", "dx", "y")
+
+
+def _same(a, b, what=""):
+    for f in FIELDS:
+        assert np.array_equal(getattr(a, f), getattr(b, f)), (what, f)
+
+
+def _run(w, inp, kind, m, chain):
+    from paper_1606_03401_amd.session import Session
+    mb.mebptt_forward_chain_enable(chain)
+    try:
+        s = Session(w, inp, kind=kind, m=m)
+        out = s.run_and_fetch()          # raises if a chain launch gave up
+    finally:
+        mb.mebptt_forward_chain_enable(True)
+    return out
+
+
+SHAPES = [
+    # B, I, H, t: (H/128, steps per wave, K split, batch tiles per XCD) in the comment
+    (64, 128, 128, 40),     # (1, 2, 4, 1)
+    (37, 100, 128, 33),     # (1, 2, 4, 2): ragged batch, groups straddle tiles, ragged I
+    (5, 128, 128, 20),      # fewer sequences than XCDs
+    (64, 256, 256, 60),     # (2, 4, 4, 1): the paper's experiment
+    (150, 250, 256, 25),    # (2, 4, 4, 2)
+    (256, 128, 512, 30),    # (4, 5, 4, 2): configuration 4's shape
+    (100, 128, 512, 30),    # (4, 5, 4, 1)
+    (64, 256, 1024, 60),    # (8, 5, 8, 1): configuration 2's shape
+    (40, 250, 1024, 20),    # same class, ragged batch and input width
+]
+
+
+@pytest.mark.parametrize("B,I,H,t", SHAPES)
+def test_chain_matches_per_step_path_and_oracle(B, I, H, t):
+    from test_gpu_parity import TOL, check_against_oracle
+    w = wl.Workload("chain", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=4, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, dy_first_step=2, seed=900 + B + H)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+    base = _run(w, inp, wl.KIND_HSM, 3, chain=False)
+    check_against_oracle(w, inp, base, ref, TOL[w.gemm_dtype], label=f"chain {B}x{I}x{H} per-step: ")
+    cases = [(wl.KIND_HSM, 1), (wl.KIND_HSM, 2), (wl.KIND_HSM, 3), (wl.KIND_HSM, 7), (wl.KIND_HSM, t),
+             (wl.KIND_ISM, 1), (wl.KIND_ISM, 3), (wl.KIND_ISM, t), (wl.KIND_MSM, 2), (wl.KIND_MSM, 9), (wl.KIND_MSM, 4 * t)]
+    for kind, m in cases:
+        out = _run(w, inp, kind, m, chain=True)
+        _same(out, base, (kind, m))
+        assert out.stats.backward_ops == t
+
+
+def test_chain_launch_count_and_status():
+    """The launches really are chains: with the chain path on, a store-everything HSM plan of a
+    long sequence needs far fewer forward launches than forward operations, and the status word
+    stays clear."""
+    from paper_1606_03401_amd.session import Session
+    w = wl.Workload("chain-count", B=64, I=128, H=128, t=200, kind=wl.KIND_HSM, m=200, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, seed=31)
+    inp = wl.make_inputs(w)
+    s = Session(w, inp)
+    mb.mebptt_profile_enable(1)
+    out = s.run_and_fetch()
+    prof = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+    assert out.stats.forward_ops == 2 * w.t - 1
+    assert prof.chain_steps >= w.t - 2                     # the initial sweep went out as chains
+    assert prof.launches[mb.K_CHAIN] <= (w.t + 47) // 48 + 1
+    assert prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps == out.stats.forward_ops
+
+
+def test_chains_from_two_host_threads():
+    """Two host threads with their own streams run chain-eligible workloads at the same time: the
+    library orders the two runs on the device (each chain launch wants the whole chip) and both
+    give the single-threaded result."""
+    import torch
+    from paper_1606_03401_amd.session import Session
+    ws = [wl.Workload("cthr-a", B=64, I=128, H=128, t=90, kind=wl.KIND_HSM, m=6, gemm_dtype=wl.GEMM_BF16,
+                      loss=wl.LOSS_EXTERNAL_DY, seed=81),
+          wl.Workload("cthr-b", B=64, I=256, H=256, t=70, kind=wl.KIND_MSM, m=12, gemm_dtype=wl.GEMM_BF16,
+                      loss=wl.LOSS_EXTERNAL_DY, seed=82)]
+    inps = [wl.make_inputs(w, nonzero_state=True) for w in ws]
+    want = [Session(w, i).run_and_fetch() for w, i in zip(ws, inps)]
+    sessions = [Session(w, i) for w, i in zip(ws, inps)]
+    streams = [torch.cuda.Stream() for _ in ws]
+    torch.cuda.synchronize()
+    errors, results = [], [[], []]
+
+    def worker(k):
+        try:
+            for _ in range(5):
+                sessions[k].run(stream=streams[k].cuda_stream)
+                streams[k].synchronize()
+                results[k].append(sessions[k].fetch())
+        except Exception as exc:   # noqa: BLE001 - reported by the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not errors, errors
+    assert all(not th.is_alive() for th in threads)
+    for k in range(2):
+        assert len(results[k]) == 5
+        for got in results[k]:
+            _same(got, want[k])
