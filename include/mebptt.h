@@ -151,7 +151,7 @@ int32_t mebptt_plan_peak(const mebptt_plan_t* plan);
 /* The flat schedule; *n receives the number of entries. */
 const mebptt_op* mebptt_plan_schedule(const mebptt_plan_t* plan, size_t* n);
 
-/* ---- non-homogeneous chains (planning only) ----------------------------------------------------
+/* ---- non-homogeneous chains ---------------------------------------------------------------------
  * Appendix "Generalizing to deep feed-forward networks": the policy for a linear chain whose
  * layers differ in forward cost u_i, output size s_i and working-memory size p_i (memory in
  * arbitrary integer units; the network input is always available and not counted).
@@ -161,8 +161,8 @@ const mebptt_op* mebptt_plan_schedule(const mebptt_plan_t* plan, size_t* n);
  * Readings: one layer costs u if p fits; at every node the sub-chain may also be processed
  * without memorising anything (re-run from its input before each backward step), recorded as
  * D = 0; a tie goes to the memorisation.  With u = s = 1, p = 0 this is BPTT-HSM with the start
- * state outside the budget.  There is no GPU executor for such chains in this library: the plan,
- * its tables and its schedule are the product. */
+ * state outside the budget.  mebptt_chain_run (below) executes such a plan on a stack of dense
+ * tanh layers of differing widths. */
 typedef struct {
   int64_t cost;        /* u_i >= 1 */
   int32_t state_units; /* s_i >= 1: size of the layer's output */
@@ -197,6 +197,45 @@ int32_t mebptt_chain_split(const mebptt_chain_plan_t* plan, int32_t t, int32_t m
 int64_t mebptt_chain_plan_forward_cost(const mebptt_chain_plan_t* plan);
 int32_t mebptt_chain_plan_peak(const mebptt_chain_plan_t* plan);
 const mebptt_chain_op* mebptt_chain_plan_schedule(const mebptt_chain_plan_t* plan, size_t* n);
+/* The plan's copy of the layer table; *n receives the number of layers. */
+const mebptt_layer* mebptt_chain_plan_layers(const mebptt_chain_plan_t* plan, int32_t* n);
+
+/* Execution of a chain plan on the GPU (the appendix's generalisation, smallest honest instance):
+ * n dense layers y_i = tanh(y_{i-1} W_i^T + b_i), W_i [d_i, d_{i-1}], batch B, widths d_0 .. d_n
+ * that differ from layer to layer, fp32 throughout (fp32 MFMA tiles, fp32 accumulate).  Memory is
+ * counted in units of unit_bytes: the output of layer i takes ceil(B d_i 4 / unit_bytes) units, its
+ * forward cost is d_{i-1} d_i (multiply-adds per sequence), and the working memory of an operation
+ * (two activations, the gradient passed down, one dz) is the caller's workspace, outside the
+ * budget (work_units = 0) -- the same accounting as the LSTM path's working core.
+ * mebptt_chain_layers fills `out` (host, n entries) with that table for mebptt_chain_plan. */
+typedef struct {
+  int32_t n, B;
+  const int32_t* widths; /* host, n + 1 entries d_0 .. d_n */
+  size_t unit_bytes;     /* bytes of one memory unit, a multiple of 4 */
+} mebptt_chain_desc;
+typedef struct {
+  int64_t forward_cost; /* sum of the forward costs of the forward operations launched (== C(n, m, 0)) */
+  int64_t backward_ops; /* == n */
+  int32_t peak_units;   /* highest pool unit any launch was handed (<= m) */
+  int32_t reserved;
+} mebptt_chain_stats;
+int mebptt_chain_layers(const mebptt_chain_desc* desc, mebptt_layer* out);
+size_t mebptt_chain_workspace_bytes(const mebptt_chain_desc* desc);
+/* One gradient step of the chain under `plan` (made by mebptt_chain_plan from mebptt_chain_layers
+ * of the same desc, else ESHAPE), the loss gradient arriving at the last layer's output.
+ * host arrays of n device pointers: W (W_i [d_i, d_{i-1}] row-major), b (b_i [d_i] or NULL entries
+ *   for zero), dW, db (written, same shapes).
+ * device, read:  x0 [B, d_0], dy [B, d_n] = dL/dy_n.
+ * device, r/w:   pool (>= m * unit_bytes, 256-byte aligned; may be NULL when m = 0), workspace
+ *                (>= mebptt_chain_workspace_bytes, 256-byte aligned).
+ * device, write: dx0 [B, d_0] and y_out [B, d_n] (either may be NULL).
+ * host, write:   stats (may be NULL).  The call only enqueues work on `stream`.
+ * Errors: EINVAL, ESHAPE, ENOMEM_SLOTS, EWORKSPACE, EHIP; nothing is enqueued on a validation error. */
+int mebptt_chain_run(const mebptt_chain_desc* desc, const mebptt_chain_plan_t* plan,
+                     const float* const* W, const float* const* b, const float* x0, const float* dy,
+                     void* pool, size_t pool_bytes, void* workspace, size_t workspace_bytes,
+                     float* const* dW, float* const* db, float* dx0, float* y_out,
+                     mebptt_chain_stats* stats, void* stream);
 
 /* ---- LSTM execution ---------------------------------------------------------------------- */
 

@@ -48,6 +48,15 @@ class mebptt_chain_op(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("op", "layer", "count", "src", "dst")]
 
 
+class mebptt_chain_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("B", C.c_int32), ("widths", C.POINTER(C.c_int32)), ("unit_bytes", C.c_size_t)]
+
+
+class mebptt_chain_stats(C.Structure):
+    _fields_ = [("forward_cost", C.c_int64), ("backward_ops", C.c_int64), ("peak_units", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
 CHAIN_FORWARD, CHAIN_BACKWARD = 1, 2
 CHAIN_INPUT, CHAIN_WORKING = -1, -2
 
@@ -91,6 +100,11 @@ SIGNATURES = {
     "mebptt_chain_plan_forward_cost": (C.c_int64, [_P]),
     "mebptt_chain_plan_peak": (C.c_int32, [_P]),
     "mebptt_chain_plan_schedule": (C.POINTER(mebptt_chain_op), [_P, C.POINTER(C.c_size_t)]),
+    "mebptt_chain_plan_layers": (C.POINTER(mebptt_layer), [_P, C.POINTER(C.c_int32)]),
+    "mebptt_chain_layers": (C.c_int, [C.POINTER(mebptt_chain_desc), C.POINTER(mebptt_layer)]),
+    "mebptt_chain_workspace_bytes": (C.c_size_t, [C.POINTER(mebptt_chain_desc)]),
+    "mebptt_chain_run": (C.c_int, [C.POINTER(mebptt_chain_desc), _P, C.POINTER(_P), C.POINTER(_P), _P, _P, _P, C.c_size_t,
+                                   _P, C.c_size_t, C.POINTER(_P), C.POINTER(_P), _P, _P, C.POINTER(mebptt_chain_stats), _P]),
     "mebptt_plan_cost": (C.POINTER(C.c_int64), [_P, C.c_int32]),
     "mebptt_plan_split": (C.POINTER(C.c_int32), [_P, C.c_int32]),
     "mebptt_plan_choice": (C.POINTER(C.c_uint8), [_P]),
@@ -399,3 +413,36 @@ def mebptt_null_launch_us(launches: int = 2000, stream: Optional[int] = None) ->
     out = C.c_double(0.0)
     _check(lib().mebptt_null_launch_us(launches, _stream(stream), C.byref(out)))
     return out.value
+
+
+def make_chain_desc(widths, B: int, unit_bytes: int) -> mebptt_chain_desc:
+    """Descriptor of a chain of dense tanh layers; keeps the widths array alive on the object."""
+    arr = (C.c_int32 * len(widths))(*[int(v) for v in widths])
+    d = mebptt_chain_desc(len(widths) - 1, B, arr, unit_bytes)
+    d._widths_keepalive = arr
+    return d
+
+
+def mebptt_chain_layers(desc: mebptt_chain_desc):
+    """The (cost, state_units, work_units) table of the chain, as mebptt_chain_plan takes it."""
+    out = (mebptt_layer * desc.n)()
+    _check(lib().mebptt_chain_layers(C.byref(desc), out))
+    return [(l.cost, l.state_units, l.work_units) for l in out]
+
+
+def mebptt_chain_workspace_bytes(desc: mebptt_chain_desc) -> int:
+    return lib().mebptt_chain_workspace_bytes(C.byref(desc))
+
+
+def mebptt_chain_run(desc: mebptt_chain_desc, plan: ChainPlan, W, b, x0, dy, pool, workspace, dW, db, dx0=None,
+                     y_out=None, stream: Optional[int] = None) -> mebptt_chain_stats:
+    """Enqueues one gradient step of the chain.  W, b, dW, db: lists of n torch tensors (b entries
+    may be None); the others torch tensors; `pool` may be None when the plan memorises nothing."""
+    n = desc.n
+    arr = lambda ts: (_P * n)(*[_ptr(t) for t in ts])
+    stats = mebptt_chain_stats()
+    rc = lib().mebptt_chain_run(C.byref(desc), plan.handle, arr(W), arr(b), _ptr(x0), _ptr(dy), _ptr(pool),
+                                0 if pool is None else _nbytes(pool), _ptr(workspace), _nbytes(workspace), arr(dW),
+                                arr(db), _ptr(dx0), _ptr(y_out), C.byref(stats), _stream(stream))
+    _check(rc)
+    return stats

@@ -216,6 +216,11 @@ int32_t mebptt_chain_split(const mebptt_chain_plan_t* p, int32_t t, int32_t m, i
 int64_t mebptt_chain_plan_forward_cost(const mebptt_chain_plan_t* p) { return p ? p->forward_cost : 0; }
 int32_t mebptt_chain_plan_peak(const mebptt_chain_plan_t* p) { return p ? p->peak : 0; }
 
+const mebptt_layer* mebptt_chain_plan_layers(const mebptt_chain_plan_t* p, int32_t* n) {
+  if (n) *n = p ? p->n : 0;
+  return p ? p->layers.data() : nullptr;
+}
+
 const mebptt_chain_op* mebptt_chain_plan_schedule(const mebptt_chain_plan_t* p, size_t* n) {
   if (n) *n = p ? p->ops.size() : 0;
   return p ? p->ops.data() : nullptr;
