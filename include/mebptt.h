@@ -420,6 +420,14 @@ int mebptt_profile_collect(mebptt_profile* out);
  * sequential chain pays on this machine.  Synchronises the stream.  Errors: EINVAL, EHIP. */
 int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us);
 
+/* The two time-batched GEMMs of one full chunk of this shape (dW/db accumulation, K = CH*B; dx,
+ * K = 4H), each launched `reps` times back to back on `stream` with nothing else on the device,
+ * on the staging buffers inside `workspace` as they are (the arithmetic is data-independent;
+ * contents are not checked) -- their time alone, in microseconds per launch (host memory).
+ * Synchronises the stream.  Errors: EINVAL, EWORKSPACE, EHIP. */
+int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
+                         void* stream, double* wgrad_us, double* dgrad_us);
+
 const char* mebptt_last_error(void);
 /* Library version string, e.g. "mebptt 0.1 (gfx950)". */
 const char* mebptt_version(void);

@@ -130,6 +130,7 @@ SIGNATURES = {
     "mebptt_forward_chain_enable": (C.c_int, [C.c_int32]),
     "mebptt_shutdown": (C.c_int, []),
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
+    "mebptt_measure_gemms": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
     "mebptt_profile_collect": (C.c_int, [C.POINTER(mebptt_profile)]),
     "mebptt_last_error": (C.c_char_p, []),
@@ -446,3 +447,11 @@ def mebptt_chain_run(desc: mebptt_chain_desc, plan: ChainPlan, W, b, x0, dy, poo
                                 arr(db), _ptr(dx0), _ptr(y_out), C.byref(stats), _stream(stream))
     _check(rc)
     return stats
+
+
+def mebptt_measure_gemms(desc: mebptt_lstm_desc, workspace, reps: int = 20, stream: Optional[int] = None):
+    """(wgrad_us, dgrad_us): the two time-batched GEMMs of one full chunk, alone on the device."""
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().mebptt_measure_gemms(C.byref(desc), _ptr(workspace), _nbytes(workspace), reps, _stream(stream),
+                                      C.byref(a), C.byref(b)))
+    return a.value, b.value

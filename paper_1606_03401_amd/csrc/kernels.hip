@@ -37,12 +37,15 @@ Dims make_dims(int B, int I, int H, int dtype, int cell) {
   d.BP = round_up(B, 16);
   d.G4 = 4 * d.HP;
   d.NA = d.NX + d.HP + 16;
-  // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 32 MiB (the
+  // Steps per weight-gradient chunk: as many as keep one dG chunk buffer within 64 MiB (the
   // staging is t-independent workspace), at least 2 and at most 32.  Every chunk costs one
   // read-modify-write of the whole dW accumulator, so longer chunks are cheaper per step.
+  // Small batches get up to 64 steps (K = CH*B of at least 2048 where 64 MiB allow it): the dW
+  // accumulator pass of a chunk otherwise outweighs its GEMM.
   const size_t step_bytes = (size_t)d.BP * d.G4 * (dtype ? 2 : 4);
-  size_t ch = ((size_t)32 << 20) / step_bytes;
+  size_t ch = ((size_t)64 << 20) / step_bytes;
   d.CH = ch < 2 ? 2 : (ch > 32 ? 32 : (int)ch);
+  if (d.CH == 32 && B <= 32 && ((size_t)64 << 20) / step_bytes >= 64) d.CH = 64;
   d.hplane = dtype ? (size_t)d.BP * d.KH : (size_t)B * H;
   d.unit = (d.hplane + (size_t)B * H + 63) / 64 * 64;
   d.KC = round_up(d.CH * B, 32);
@@ -1429,6 +1432,184 @@ hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* d
   return hipGetLastError();
 }
 
+// ---- time-batched GEMM on 256 x 256 workgroup tiles --------------------------------------------
+// D[i][j] (+)= sum_k A[i][k] B[j][k] for the weight gradient over a chunk of steps (K = CH*B), used
+// when dW has enough 256 x 256 tiles to fill the chip (the dx GEMM's output never has).  Both operands are fragment-tiled, so a 16-row tile of
+// one macro step is a contiguous 1 KiB block.  A workgroup of 8 waves (2 along i, 4 along j) owns
+// 256 x 256 outputs, each wave 128 x 64 (8 x 4 MFMA tiles, 128 accumulator registers); two waves
+// share a SIMD, so one wave's LDS reads hide behind the other's MFMAs.  Per round of two macro
+// steps (K = 64) the workgroup copies 32 + 32 operand fragments (64 KiB) from L2 into one of two
+// LDS stages -- fetched into registers one round ahead -- and every wave reads the 8 + 4
+// fragments per macro step it needs: each operand byte enters the compute unit once per
+// workgroup, and there is one barrier per 64 of K.
+// Workgroup ids are re-mapped so that the workgroups sharing an XCD (ids equal modulo 8) work
+// through a contiguous range of (i-block, j-block) pairs, j fastest: they stream the same A panel
+// through the L2 they share.
+struct TgemmParams {
+  const void* A;      // rows i: mt_total 16-row tiles, a_steps macro steps per tile
+  const void* B;      // rows j
+  int mt_total, nt_total, a_steps, b_steps;
+  int nk;             // macro steps to contract over (from step 0)
+  int gx, gy;         // workgroup grid: i-blocks, j-blocks
+  float* acc;         // tile-ordered accumulator
+  int accumulate;     // 0: overwrite it, 1: add to it
+};
+
+template <class T>
+__global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
+  using M = Mma<T>;
+  constexpr int VEC = M::VEC, FRAG = 64 * VEC;
+  constexpr int TI = 8, TJ = 4;           // MFMA tiles per wave along i and j
+  constexpr int WGT = 16;                 // 16-row tiles per workgroup along each axis
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  T* lds = reinterpret_cast<T*>(smem);    // [stage 2][macro step 2][16 tiles of A][FRAG]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wi = wave & 1, wj = wave >> 1;
+  const int total = p.gx * p.gy, id = (int)blockIdx.x;
+  const int xcd = id & 7;
+  const int work = xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3);
+  const int bx = work / p.gy, by = work % p.gy;
+  const int nrounds = (p.nk + 1) >> 1;
+  // A (the i operand, shared by the four waves of a row) goes L2 -> registers -> LDS: this wave
+  // copies fragments f = wave*4 .. +4 of every round, f = ks * 16 + tile.  B (the j operand,
+  // shared by two waves only) is fetched by each wave straight into its MFMA registers: LDS
+  // carries 2/3 of the reads and half of the writes it would carry for both operands.
+  const T* srcA[4];
+  int ks_of[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int f = wave * 4 + q, ks = f >> 4, tile = f & 15;
+    ks_of[q] = ks;
+    srcA[q] = reinterpret_cast<const T*>(p.A) + ((size_t)min(bx * WGT + tile, p.mt_total - 1) * p.a_steps * 64 + lane) * VEC;
+  }
+  const T* srcB[TJ];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j)
+    srcB[j] = reinterpret_cast<const T*>(p.B) + ((size_t)min(by * WGT + wj * TJ + j, p.nt_total - 1) * p.b_steps * 64 + lane) * VEC;
+  u32x4 ringA[2][4];
+  typename M::Frag ringB[2][2][TJ];   // [set][macro step of the round][tile]
+  auto fetch = [&](int set, int round) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int s = min(round * 2 + ks_of[q], p.nk - 1);   // a macro step past the end is fetched (clamped) and never used
+      ringA[set][q] = *reinterpret_cast<const u32x4*>(srcA[q] + (size_t)s * FRAG);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int s = min(round * 2 + ks, p.nk - 1);
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) ringB[set][ks][j] = M::load(srcB[j] + (size_t)s * FRAG);
+    }
+  };
+  auto stash = [&](int set, int stage) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<u32x4*>(&lds[((size_t)stage * 32 + wave * 4 + q) * FRAG + lane * VEC]) = ringA[set][q];
+  };
+  f32x4 acc[TI][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  auto compute = [&](int r, int stage, int set) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if (r * 2 + ks < p.nk) {   // uniform
+        const T* base = &lds[((size_t)stage * 32 + ks * 16) * FRAG + lane * VEC];
+        // A fragments two at a time, the next pair requested before the current pair's eight
+        // MFMAs are issued, so that the LDS latency of a pair hides behind the pair before it
+        typename M::Frag a_cur[2], a_nxt[2];
+        a_cur[0] = M::load(base + (size_t)(wi * TI) * FRAG);
+        a_cur[1] = M::load(base + (size_t)(wi * TI + 1) * FRAG);
+#pragma unroll
+        for (int ip = 0; ip < TI / 2; ++ip) {
+          if (ip + 1 < TI / 2) {
+            a_nxt[0] = M::load(base + (size_t)(wi * TI + 2 * ip + 2) * FRAG);
+            a_nxt[1] = M::load(base + (size_t)(wi * TI + 2 * ip + 3) * FRAG);
+          }
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) acc[2 * ip + h][j] = M::mma(a_cur[h], ringB[set][ks][j], acc[2 * ip + h][j]);
+          a_cur[0] = a_nxt[0];
+          a_cur[1] = a_nxt[1];
+        }
+      }
+    }
+  };
+
+  if (nrounds > 0) {
+    // Register set r & 1 holds round r: its A part is moved to LDS stage r & 1 one round early, its
+    // B part is consumed in place; the set is refilled with round r + 2 once round r is computed.
+    fetch(0, 0);
+    fetch(1, 1);           // clamped when there is a single round
+    stash(0, 0);
+    __syncthreads();
+    for (int r = 0; r < nrounds; r += 2) {   // unrolled by two so that sets and stages are static
+      if (r + 1 < nrounds) stash(1, 1);
+      compute(r, 0, 0);
+      fetch(0, r + 2);
+      __syncthreads();
+      if (r + 1 < nrounds) {
+        if (r + 2 < nrounds) stash(0, 0);
+        compute(r + 1, 1, 1);
+        fetch(1, r + 3);
+        __syncthreads();
+      }
+    }
+  }
+
+  // Running sum in a tile-ordered accumulator: a wave's 32 tiles are one contiguous run and a
+  // lane's four rows one float4, so the read-modify-write of every chunk is fully coalesced;
+  // wgrad_finish_kernel converts it to the caller's row-major dW once at the end of the run.
+  float4* accp = reinterpret_cast<float4*>(p.acc) + (((size_t)(bx * p.gy + by) * 8 + wave) * (TI * TJ)) * 64 + lane;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {   // two batches of 16 tiles: the old values pass through few registers
+    float4 old[TI * TJ / 2];
+    if (p.accumulate) {
+#pragma unroll
+      for (int q = 0; q < TI * TJ / 2; ++q) old[q] = accp[(size_t)(half * (TI * TJ / 2) + q) * 64];
+    }
+#pragma unroll
+    for (int q = 0; q < TI * TJ / 2; ++q) {
+      const int t = half * (TI * TJ / 2) + q;
+      f32x4 v = acc[t / TJ][t % TJ];
+      if (p.accumulate) {
+        v[0] += old[q].x;
+        v[1] += old[q].y;
+        v[2] += old[q].z;
+        v[3] += old[q].w;
+      }
+      accp[(size_t)t * 64] = float4{v[0], v[1], v[2], v[3]};
+    }
+  }
+}
+
+constexpr int TGEMM_LDS_BYTES = 2 * 32 * 1024;
+constexpr int TGEMM_MIN_TILES = 192;   // below this the output does not fill the chip with 256 x 256 tiles
+
+template <class T>
+static hipError_t launch_tgemm(const TgemmParams& p, hipStream_t st) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tgemm_kernel<T>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, TGEMM_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  tgemm_kernel<T><<<dim3(p.gx * p.gy), dim3(512), TGEMM_LDS_BYTES, st>>>(p);
+  return hipGetLastError();
+}
+
+// The weight gradient runs on the 256 x 256 tiles when the operands are bf16 and dW has enough tiles.
+static bool wgrad_uses_big_tiles(const Dims& d) {
+  if (!d.dtype) return false;
+  const int gx = (d.G4 / 16 + 15) / 16, gy = (d.NA / 16 + 15) / 16;
+  return gx * gy >= TGEMM_MIN_TILES;
+}
+
 // ---- x transposed into the weight-gradient operand ----------------------------------------------
 
 template <class T>
@@ -1637,10 +1818,16 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int
     const int mp = 4 * u + prow;
     const int mt = mp >> 4, lq = (mp & 15) >> 2, r = mp & 3;
     const int nt = np >> 4, lrow = np & 15;
-    const int wgx = mt / (2 * WT), wm = (mt % (2 * WT)) / WT, i = mt % WT;
-    const int wgy = nt / (2 * WT), wn = (nt % (2 * WT)) / WT, jj = nt % WT;
-    const size_t off =
-        ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * (WT * WT) + (i * WT + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+    size_t off;
+    if (WT == 0) {   // tgemm_kernel's blocks: 2 x 4 waves of 8 x 4 tiles per 256 x 256 workgroup
+      const int wgx = mt >> 4, wi = (mt & 15) >> 3, ti = mt & 7;
+      const int wgy = nt >> 4, wj = (nt & 15) >> 2, tj = nt & 3;
+      off = ((((size_t)(wgx * grid_y + wgy) * 8 + (wi + 2 * wj)) * 32 + (ti * 4 + tj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+    } else {
+      const int wgx = mt / (2 * WT), wm = (mt % (2 * WT)) / WT, i = mt % WT;
+      const int wgy = nt / (2 * WT), wn = (nt % (2 * WT)) / WT, jj = nt % WT;
+      off = ((((size_t)(wgx * grid_y + wgy) * 4 + (wm + 2 * wn)) * (WT * WT) + (i * WT + jj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+    }
     float v = dWacc[off];
     for (int sp = 1; sp < nsplit; ++sp) v += dWacc[(size_t)sp * split_stride + off];   // partial sums, fixed order
     *dst = v;
@@ -1667,7 +1854,13 @@ static size_t wgrad_partial_floats(const Dims& d) {   // one partial accumulator
   return gx * gy * 4 * WT * WT * 64 * 4;
 }
 
-size_t wgrad_accumulator_bytes(const Dims& d) { return wgrad_partial_floats(d) * wgrad_splits(d) * sizeof(float); }
+size_t wgrad_accumulator_bytes(const Dims& d) {
+  if (wgrad_uses_big_tiles(d)) {   // one padded 256 x 256 block per workgroup
+    const size_t gx = (d.G4 / 16 + 15) / 16, gy = (d.NA / 16 + 15) / 16;
+    return gx * gy * 256 * 256 * sizeof(float);
+  }
+  return wgrad_partial_floats(d) * wgrad_splits(d) * sizeof(float);
+}
 
 template <class T>
 static void launch_wgrad_t(const Dims& d, const void* dGT, const void* aT, int K, int accumulate, float* dWacc,
@@ -1684,6 +1877,20 @@ hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslo
                         hipStream_t st) {
   const int kstep = d.dtype ? 32 : 16;
   const int K = round_up(nslots * d.B, kstep);   // columns past nslots*B are zero
+  if (wgrad_uses_big_tiles(d)) {
+    TgemmParams p{};
+    p.A = dGT;
+    p.B = aT;
+    p.mt_total = d.G4 / 16;
+    p.nt_total = d.NA / 16;
+    p.a_steps = p.b_steps = d.KC / 32;
+    p.nk = K / 32;
+    p.gx = (p.mt_total + 15) / 16;
+    p.gy = (p.nt_total + 15) / 16;
+    p.acc = dWacc;
+    p.accumulate = accumulate;
+    return launch_tgemm<__bf16>(p, st);
+  }
   if (d.dtype)
     launch_wgrad_t<__bf16>(d, dGT, aT, K, accumulate, dWacc, st);
   else
@@ -1693,6 +1900,11 @@ hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslo
 
 hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, float* db,
                                hipStream_t st) {
+  if (wgrad_uses_big_tiles(d)) {
+    wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, 0, (d.NA / 16 + 15) / 16, 1, 0, d.NX, d.HP, d.I, d.H, d.cell,
+                                                          dW_ih, dW_hh, db);
+    return hipGetLastError();
+  }
   const int WT = wgrad_wave_tile(d);
   const int grid_y = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
   wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, wgrad_splits(d), wgrad_partial_floats(d), d.NX, d.HP,

@@ -454,6 +454,45 @@ int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us) {
   return MEBPTT_OK;
 }
 
+int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
+                         void* stream, double* wgrad_us, double* dgrad_us) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (reps < 1 || reps > 10000 || !wgrad_us || !dgrad_us) return set_error(MEBPTT_EINVAL, "reps must be in [1, 10000] and the outputs non-NULL");
+  if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
+  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell);
+  const Workspace w = layout(d);
+  if (workspace_bytes < w.total)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  if (misaligned(workspace, ALIGN)) return set_error(MEBPTT_EWORKSPACE, "workspace must be 256-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  std::lock_guard<std::mutex> lock(g_run_mutex);
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  for (hipEvent_t& e : ev) HIP_TRY(hipEventCreate(&e));
+  // dx goes to the dG buffer the GEMM does not read (scratch of sufficient size: CH*B*I floats <= CH*BP*G4 operand bytes)
+  float* dx_scratch = reinterpret_cast<float*>(ws + w.dG[1]);
+  hipError_t e = hipSuccess;
+  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {   // first pass warms up
+    e = hipEventRecord(ev[0], st);
+    for (int i = 0; i < reps && e == hipSuccess; ++i)
+      e = launch_wgrad(d, ws + w.dGT[0], ws + w.aT[0], d.CH, 1, reinterpret_cast<float*>(ws + w.dWacc), st);
+    if (e == hipSuccess) e = hipEventRecord(ev[1], st);
+    for (int i = 0; i < reps && e == hipSuccess; ++i)
+      e = launch_dgrad_gemm(d, ws + w.WTx, d.I, ws + w.dG[0], d.CH, dx_scratch, d.I, st);
+    if (e == hipSuccess) e = hipEventRecord(ev[2], st);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[2]);
+  }
+  float ms_w = 0.0f, ms_d = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms_w, ev[0], ev[1]);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms_d, ev[1], ev[2]);
+  for (hipEvent_t& x : ev) (void)hipEventDestroy(x);
+  if (e != hipSuccess) return set_error(MEBPTT_EHIP, "GEMM timing failed: %s", hipGetErrorString(e));
+  *wgrad_us = (double)ms_w * 1e3 / reps;
+  *dgrad_us = (double)ms_d * 1e3 / reps;
+  return MEBPTT_OK;
+}
+
 size_t mebptt_static_workspace_bytes(void) { return MEBPTT_STATIC_WORKSPACE_BYTES; }
 
 int mebptt_run_static(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih, const float* W_hh,
