@@ -338,8 +338,11 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
  * launches where the shape allows it (bf16 operands, LSTM, H a multiple of 128 and gate weights
  * that fit into the registers and LDS of one XCD's compute units): one launch then carries up to
  * 48 steps, keeps the gate weights on the chip, splits the batch over the 8 XCDs and lets the 32
- * compute units of an XCD exchange h through their shared L2.  Results are bit-identical to the
- * launch-per-step path.  Such a launch assumes that its 256 workgroups are all resident and dealt
+ * compute units of an XCD exchange h through their shared L2.  Where the transposed recurrent
+ * weights fit as well (H = 128, 256, 512 with I <= H/4 .. H), the runs of "forward operation keeping
+ * the internal state, then backward operation" that end every sub-sequence are issued the same way
+ * ("sweep" launches, up to 32 pairs, internal states never leaving the registers).  Results are
+ * bit-identical to the launch-per-step path.  Such a launch assumes that its 256 workgroups are all resident and dealt
  * round-robin to the XCDs; each workgroup checks this, every wait inside is bounded by a wall
  * clock, and a launch that cannot proceed gives up and raises a status word in the workspace
  * instead of hanging.  mebptt_run_status copies that word to *status (host) after waiting for
@@ -352,7 +355,8 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
 int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_t workspace_bytes, void* stream,
                       int32_t* status);
 
-/* on = 0: from now on every forward operation gets a launch of its own, whatever the shape (the
+/* on = 0: from now on every forward and backward operation gets a launch of its own (or shares a
+ * pair launch), whatever the shape (the
  * path the forward-chain launches are checked against, and the "before" of their measurement);
  * on != 0 (the default) restores them.  Process-wide; not to be toggled while a run is enqueued. */
 int mebptt_forward_chain_enable(int32_t on);
@@ -392,7 +396,8 @@ enum {
   MEBPTT_K_SETUP = 4,    /* operand copies of the weights, zero fills, start-state copy       */
   MEBPTT_K_PAIR = 5,     /* one launch carrying a backward step and an independent forward op */
   MEBPTT_K_CHAIN = 6,    /* one launch carrying a chain of forward operations, weights resident  */
-  MEBPTT_K_CLASSES = 7
+  MEBPTT_K_SWEEP = 7,    /* one launch carrying a run of (forward, backward) pairs, weights resident */
+  MEBPTT_K_CLASSES = 8
 };
 typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
@@ -406,6 +411,9 @@ typedef struct {
   /* Forward-chain launches are all bracketed: forward operations they carried, and their time. */
   int64_t chain_steps;
   double chain_ms;
+  /* Likewise the sweep launches: (forward, backward) pairs they carried, and their time. */
+  int64_t sweep_steps;
+  double sweep_ms;
 } mebptt_profile;
 /* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
  * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;

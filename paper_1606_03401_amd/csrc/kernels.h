@@ -116,6 +116,35 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
                                 const ChainStep* steps, int count, void* ring, unsigned* sync, unsigned base,
                                 unsigned launch, hipStream_t st);
 
+// A run of (forward operation keeping the internal state, backward operation) pairs for steps
+// s_hi, s_hi - 1, ..., all inside one weight-gradient chunk, in one launch with both weight
+// operands resident on the chip (shapes for which can_run_sweep() holds).  src[j] is the unit
+// holding the state before step s_hi - j; the internal states never reach memory; everything a
+// backward step writes (dG, its transposed copies, y_out, the running dc) is written as by
+// launch_backward.  sync/base/launch as for launch_forward_chain, whose counters it shares: a
+// launch of n steps leaves forward_chain_arrivals(n) arrivals.
+struct SweepArgs {
+  const void* Wp;
+  const void* WTh;
+  const float* bp;
+  const float* x;          // x of step 1
+  const float* dy;         // plane of step dy_first first, or NULL
+  int dy_first, dy_is_h;
+  float* dc;
+  float* y_out;            // plane of step 1 first, or NULL
+  const void* dG_next;     // dG block of step s_hi + 1, or NULL for the last step of the sequence
+  void* dG_chunk;
+  void* dGT;
+  void* aT;
+  unsigned* sync;
+  unsigned base, launch;
+  int s_hi, count;
+  const float* const* src;
+};
+bool can_run_sweep(const Dims& d);
+int sweep_max_steps();
+hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st);
+
 // out[slot*B + b][n] = sum_k dG[slot*BP + b][k] * WT[n][k] for slot < nslots, b < B, n < N;
 // ld_out = row stride of out.  Used for dx (WT = WTx, N = I) and for dh_0 (WT = WTh, N = H).
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,

@@ -332,6 +332,22 @@ __device__ inline float cell_forward(const float (&G)[4], const float4& bias, fl
   }
 }
 
+// Pointwise backward step of one (sequence, hidden unit) of the LSTM: from dh_s (recurrent part
+// plus injected loss gradient), the running dc, the internal state (i, f, g, o, c_s) and c_{s-1}
+// to the four gate pre-activation gradients and dc_{s-1}.  One function, multiply-adds spelled
+// out, for every kernel that runs a backward step: the same bits whichever kernel ran it.
+__device__ inline void lstm_backward_point(float dh, float dc_in, float gi, float gf, float gg, float go, float c_s,
+                                           float c_prev, float (&dG)[4], float& dc_out) {
+  const float tc = tanhf_(c_s);
+  const float d_o = __fmul_rn(dh, tc);
+  const float dct = __fmaf_rn(__fmul_rn(dh, go), __fmaf_rn(-tc, tc, 1.0f), dc_in);
+  dG[0] = __fmul_rn(__fmul_rn(__fmul_rn(dct, gg), gi), __fsub_rn(1.0f, gi));
+  dG[1] = __fmul_rn(__fmul_rn(__fmul_rn(dct, c_prev), gf), __fsub_rn(1.0f, gf));
+  dG[2] = __fmul_rn(__fmul_rn(dct, gi), __fmaf_rn(-gg, gg, 1.0f));
+  dG[3] = __fmul_rn(__fmul_rn(d_o, go), __fsub_rn(1.0f, go));
+  dc_out = __fmul_rn(dct, gf);
+}
+
 // ---- forward step: gate GEMM + LSTM pointwise -------------------------------------------------
 
 struct FwdParams {
@@ -671,14 +687,13 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
     if (p.y_out_s) p.y_out_s[e] = h[q];
     float dGi, dGf, dGg, dGo;
     if (p.cell == 0) {
-      const float tc = tanhf_(c_s[q]);
-      const float d_o = dh * tc;
-      const float dct = dc_in[q] + dh * go[q] * (1.0f - tc * tc);
-      dGi = dct * gg[q] * gi[q] * (1.0f - gi[q]);
-      dGf = dct * c_prev[q] * gf[q] * (1.0f - gf[q]);
-      dGg = dct * gi[q] * (1.0f - gg[q] * gg[q]);
-      dGo = d_o * go[q] * (1.0f - go[q]);
-      p.dc[e] = dct * gf[q];
+      float dG[4], dc_out;
+      lstm_backward_point(dh, dc_in[q], gi[q], gf[q], gg[q], go[q], c_s[q], c_prev[q], dG, dc_out);
+      dGi = dG[0];
+      dGf = dG[1];
+      dGg = dG[2];
+      dGo = dG[3];
+      p.dc[e] = dc_out;
     } else {
       // GRU: r = gi, z = gf, n = gg, n_h = c_s, h_{s-1} = c_prev.  The running plane `dc` carries
       // the part of dL/dh_{s-1} that bypasses the GEMM: dh_s * z_s.
@@ -1323,6 +1338,428 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
     case 4: return launch_chain_cfg<2, 4, 0, 4, 2, 2>(p, st);
     case 5: return launch_chain_cfg<1, 2, 0, 4, 1, 1>(p, st);
     default: return launch_chain_cfg<1, 2, 0, 4, 2, 1>(p, st);
+  }
+}
+
+// ---- backward sweep with resident weights ------------------------------------------------------
+// Where a sub-sequence fits into memory the schedule alternates "forward operation of step s from
+// the memorised h_{s-1}, keeping the internal state" and "backward operation of step s", s going
+// down.  On shapes whose gate weights AND their transpose fit on the chip such a run of pairs goes
+// out as one launch per chunk of steps, organised like the forward chain (batch split over the
+// XCDs, hidden units over the 32 compute units of an XCD, weights in registers):
+//   * the forward operation of a step needs nothing from other compute units (its input state was
+//     memorised by an earlier launch), and its internal state never leaves the registers of the
+//     thread that owns the (sequence, unit);
+//   * the backward operation needs dG of the step after, all 4H columns of it, for the XCD's
+//     sequences: the compute units publish their columns in the chunk's dG staging buffer (which
+//     is already laid out as that GEMM's operand) and meet at the XCD's arrival counter;
+//   * while the counter fills, every compute unit already runs the forward operation of the next
+//     lower step, so the wait is mostly hidden.
+// K splits and summation orders are those of forward_body and backward_body for the shape, the
+// pointwise steps are the shared functions: bit-identical to the launch-per-step path.
+constexpr int SWEEP_MAX_STEPS = 32;
+struct SweepParams {
+  const void* Wp;
+  const void* WTh;
+  const float* bp;
+  const float* x;        // x of step 1 (step s reads x + (s-1)*B*I)
+  const float* dy;       // upstream gradients, first plane = step dy_first; NULL with dy_is_h
+  int dy_first, dy_is_h;
+  float* dc;             // running cell-state gradient plane
+  float* y_out;          // outputs, plane of step 1 first, or NULL
+  const void* dG_next;   // dG block of step s_hi + 1, or NULL when s_hi is the last step of the sequence
+  void* dG_chunk;        // this chunk's dG buffer (block of step s at slot (s-1) % CH)
+  void* dGT;
+  void* aT;
+  unsigned* sync;
+  unsigned base, launch;
+  int s_hi, count;       // steps s_hi, s_hi - 1, ..., s_hi - count + 1 (all in one chunk)
+  int B, I, H, KX, KH, BP, nb, G4, NX, KC, CH;
+  size_t unit;
+  const float* src[SWEEP_MAX_STEPS];   // src[j]: unit holding the state before step s_hi - j
+};
+
+template <int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+__global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
+  using T = __bf16;
+  using M = Mma<T>;
+  constexpr int VEC = 8, KSTEP = 32, FRAG = 64 * VEC;
+  constexpr int FT = 8 / KSF;                       // groups of waves that split the forward row tiles
+  constexpr int NRTW = (NRT + FT - 1) / FT;         // forward row tiles per wave
+  constexpr int UW = NRT * 4;                       // hidden units per workgroup
+  constexpr int NTB = (UW + 15) / 16;               // 16-unit tiles of the dh GEMM that cover them
+  constexpr int NTF = NRT * NBT, NTBT = NTB * NBT;
+  constexpr int ITEMS = NRT * NBT * 64, IPT = (ITEMS + 511) / 512;
+  constexpr int nstepsF = KSF * NSWF, nstepsB = KSB * NSWB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* redF = reinterpret_cast<float*>(smem);                       // [KSF][NTF][4][64]
+  float* redB = redF + (size_t)KSF * NTF * 4 * 64;                    // [KSB][NTBT][4][64]
+  __shared__ int s_go, s_g, s_rank;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lrow = lane & 15, lq = lane >> 4;
+  if (threadIdx.x == 0) {
+    const unsigned xcc = xcc_id();
+    int ok = xcc < (unsigned)RES_GROUPS;
+    unsigned ticket = 0;
+    if (ok) {
+      ticket = __hip_atomic_fetch_add(p.sync + 512 + xcc * 64, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ok = ticket / RES_MEMBERS == p.launch;
+    }
+    if (!ok) __hip_atomic_store(p.sync + 1024, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_go = ok;
+    s_g = ok ? (int)xcc : 0;
+    s_rank = (int)(ticket % RES_MEMBERS);
+  }
+  __syncthreads();
+  if (!s_go) return;
+  const int g = s_g, rank = s_rank;
+  const int nsx = p.KX / KSTEP, nsh = p.KH / KSTEP;
+  const size_t hhalf = (size_t)p.BP * p.KH, plane = (size_t)p.B * p.H;
+  const int b_lo = g * p.nb, b_hi = min(p.B, b_lo + p.nb);
+  const int nbt_all = p.BP / 16;
+  const int ct0 = min(b_lo / 16, nbt_all - 1);
+  unsigned* ctr = p.sync + g * 64;
+  unsigned* status = p.sync + 1024;
+  const int fk = wave % KSF, fg = wave / KSF;       // forward: K part and row-tile group of this wave
+  const bool bwd_wave = wave < KSB;
+  const int nt0 = (rank * UW) / 16;                 // first 16-unit tile of the dh GEMM
+
+  // resident weights: forward rows of this workgroup's units, and the rows of W_hh^T for the same units
+  typename M::Frag wf[NRTW][NSWF], wb[NTB][NSWB];
+#pragma unroll
+  for (int i = 0; i < NRTW; ++i) {
+    const int rt = min(fg * NRTW + i, NRT - 1);
+#pragma unroll
+    for (int k = 0; k < NSWF; ++k)
+      wf[i][k] = M::load(reinterpret_cast<const T*>(p.Wp) +
+                         (((size_t)(rank * NRT + rt) * nstepsF + fk + KSF * k) * 64 + lane) * VEC);
+  }
+#pragma unroll
+  for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+    for (int k = 0; k < NSWB; ++k)
+      wb[tb][k] = M::load(reinterpret_cast<const T*>(p.WTh) +
+                          (((size_t)(nt0 + tb) * nstepsB + min(wave, KSB - 1) + KSB * k) * 64 + lane) * VEC);
+
+  // items: (output tile, lane of the forward MFMA layout) = (sequence, unit)
+  bool mine[IPT];
+  int ib[IPT], iu[IPT], icellF[IPT], icellB[IPT];
+  float4 bias[IPT];
+  float dc_run[IPT];
+  // internal state of the step whose backward operation comes next, and its input state
+  float st_gate[IPT][4], st_c[IPT], st_h[IPT], st_cprev[IPT], st_hprev[IPT];
+#pragma unroll
+  for (int q = 0; q < IPT; ++q) {
+    const int item = (int)threadIdx.x + q * 512;
+    const int tile = item >> 6, il = item & 63;
+    const int rt = tile / NBT, bt = tile % NBT;
+    const int b = (ct0 + bt) * 16 + (il & 15), u = rank * UW + rt * 4 + (il >> 4);
+    mine[q] = item < ITEMS && b >= b_lo && b < b_hi;
+    ib[q] = b;
+    iu[q] = u;
+    icellF[q] = tile * 4 * 64 + il;
+    // dh of unit u: row u % 16 of tile u / 16 of the dh GEMM, i.e. lane (u%16/4)*16 + b%16, register u%4
+    icellB[q] = (((u / 16 - nt0) * NBT + bt) * 4 + (u & 3)) * 64 + ((u & 15) >> 2) * 16 + (il & 15);
+    bias[q] = float4{0.f, 0.f, 0.f, 0.f};
+    dc_run[q] = 0.0f;
+    if (mine[q]) {
+      bias[q] = *reinterpret_cast<const float4*>(p.bp + 4 * u);
+      dc_run[q] = p.dc[(size_t)b * p.H + u];
+    }
+  }
+  const bool x_vec = (p.I & 3) == 0;
+
+  // operands of a forward operation, requested a step ahead: raw x values, h fragments, c_{s-1}, h_{s-1}
+  RawAct<VEC> xraw[NSXW][NBT];
+  typename M::Frag hfr[NSWF][NBT];
+  float pf_cprev[IPT], pf_hprev[IPT];
+  auto fetch_fwd = [&](int j) {
+    const int s = p.s_hi - j;
+    const float* x_s = p.x + (size_t)(s - 1) * p.B * p.I;
+    const float* src = p.src[j];
+#pragma unroll
+    for (int k = 0; k < NSWF; ++k) {
+      const int ms = fk + KSF * k;
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) {
+        const int tile = min(ct0 + bt, nbt_all - 1);
+        if (ms < nsx) {
+          if (k < NSXW) xraw[k < NSXW ? k : 0][bt] = load_raw<VEC>(x_s + (size_t)min(tile * 16 + lrow, p.B - 1) * p.I,
+                                                                   ms * KSTEP + VEC * lq, p.I, x_vec);
+        } else {
+          hfr[k][bt] = M::load(reinterpret_cast<const T*>(src) + (((size_t)tile * nsh + (ms - nsx)) * 64 + lane) * VEC);
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < IPT; ++q) {
+      pf_cprev[q] = pf_hprev[q] = 0.0f;
+      if (mine[q]) {
+        pf_cprev[q] = src[hhalf + (size_t)ib[q] * p.H + iu[q]];
+        pf_hprev[q] = (float)HPlane<T>::as_operand(src, ib[q], iu[q], nsh, p.H, hhalf);
+      }
+    }
+  };
+  // forward operation of step s_hi - j from the fetched operands; leaves the internal state in st_*
+  auto forward = [&](int j) {
+    f32x4 acc[NRTW][NBT];
+#pragma unroll
+    for (int i = 0; i < NRTW; ++i)
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) acc[i][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < NSWF; ++k) {
+      const int ms = fk + KSF * k;
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) {
+        const typename M::Frag bfr = (k < NSXW && ms < nsx) ? M::from_f32(xraw[k < NSXW ? k : 0][bt].v) : hfr[k][bt];
+#pragma unroll
+        for (int i = 0; i < NRTW; ++i) acc[i][bt] = M::mma(wf[i][k], bfr, acc[i][bt]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NRTW; ++i) {
+      const int rt = fg * NRTW + i;
+      if (rt < NRT) {
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) redF[((fk * NTF + rt * NBT + bt) * 4 + r) * 64 + lane] = acc[i][bt][r];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < IPT; ++q) {
+      if (!mine[q]) continue;
+      float G[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < KSF; ++w)   // fixed order, as in forward_body
+#pragma unroll
+        for (int r = 0; r < 4; ++r) G[r] += redF[w * NTF * 4 * 64 + icellF[q] + r * 64];
+      float second;
+      st_h[q] = cell_forward<0>(G, bias[q], pf_cprev[q], second, st_gate[q]);
+      st_c[q] = second;
+      st_cprev[q] = pf_cprev[q];
+      st_hprev[q] = pf_hprev[q];
+    }
+  };
+
+  fetch_fwd(0);
+  forward(0);
+  if (p.count > 1) fetch_fwd(1);
+
+  for (int j = 0; j < p.count; ++j) {
+    const int s = p.s_hi - j;                       // the step back-propagated now
+    const int slot = (s - 1) % p.CH;
+    const size_t dG_step = (size_t)p.BP * p.G4;     // elements of one step's dG block
+    const T* dG_next = (j == 0) ? reinterpret_cast<const T*>(p.dG_next)
+                                : reinterpret_cast<const T*>(p.dG_chunk) + (size_t)(slot + 1) * dG_step;
+    if (j > 0) {
+      // all 32 workgroups of this XCD have published their columns of dG of step s + 1?
+      if (threadIdx.x == 0) {
+        const unsigned target = p.base + (unsigned)j * RES_MEMBERS;
+        int ok = 1, polls = 0;
+        long long t0 = 0;
+        while ((int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+          if ((++polls & 15) == 0) {
+            const long long now = wall_clock64();
+            if (t0 == 0) t0 = now;
+            if (now - t0 > RES_WAIT_TICKS ||
+                __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+              __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              ok = 0;
+              break;
+            }
+          }
+        }
+        s_go = ok;
+      }
+      __syncthreads();
+      if (!s_go) return;
+    }
+    // dh = dG_{s+1} W_hh for this workgroup's units
+    if (dG_next != nullptr) {
+      if (bwd_wave) {
+        f32x4 acc[NTB][NBT];
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt) acc[tb][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        typename M::Frag gfr[NSWB][NBT];
+#pragma unroll
+        for (int k = 0; k < NSWB; ++k)
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt) {
+            const T* fp = dG_next + (((size_t)min(ct0 + bt, nbt_all - 1) * nstepsB + wave + KSB * k) * 64 + lane) * VEC;
+            // agent-scope loads: served by the XCD's L2, never by this compute unit's vector cache
+            union { unsigned long long q[2]; typename M::Frag f; } cv;
+            const unsigned long long* qp = reinterpret_cast<const unsigned long long*>(fp);
+            cv.q[0] = __hip_atomic_load(qp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            cv.q[1] = __hip_atomic_load(qp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            gfr[k][bt] = cv.f;
+          }
+#pragma unroll
+        for (int k = 0; k < NSWB; ++k)
+#pragma unroll
+          for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+            for (int bt = 0; bt < NBT; ++bt) acc[tb][bt] = M::mma(wb[tb][k], gfr[k][bt], acc[tb][bt]);
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) redB[((wave * NTBT + tb * NBT + bt) * 4 + r) * 64 + lane] = acc[tb][bt][r];
+      }
+      __syncthreads();
+    }
+    // pointwise backward of step s on the internal state held in registers
+    const bool publish = j + 1 < p.count;
+    T* dG_cur = reinterpret_cast<T*>(p.dG_chunk) + (size_t)slot * dG_step;
+    const int ncs = p.KC / KSTEP, col0 = slot * p.B;
+#pragma unroll
+    for (int q = 0; q < IPT; ++q) {
+      if (!mine[q]) continue;
+      const int b = ib[q], n = iu[q];
+      const size_t e = (size_t)b * p.H + n;
+      float dh = 0.0f;
+      if (dG_next != nullptr)
+        for (int w = 0; w < KSB; ++w) dh += redB[w * NTBT * 4 * 64 + icellB[q]];   // fixed order, as in backward_body
+      float dyv = 0.0f;
+      if (p.dy_is_h)
+        dyv = st_h[q];
+      else if (p.dy != nullptr && s >= p.dy_first)
+        dyv = p.dy[(size_t)(s - p.dy_first) * plane + e];
+      dh += dyv;
+      if (p.y_out) p.y_out[(size_t)(s - 1) * plane + e] = st_h[q];
+      float dG[4], dc_out;
+      lstm_backward_point(dh, dc_run[q], st_gate[q][0], st_gate[q][1], st_gate[q][2], st_gate[q][3], st_c[q], st_cprev[q],
+                          dG, dc_out);
+      dc_run[q] = dc_out;
+      const T q0 = (T)dG[0], q1 = (T)dG[1], q2 = (T)dG[2], q3 = (T)dG[3];
+      // the four gates of a unit are consecutive in dG: one 8-byte store (what other compute units
+      // fetch next must not be written in pieces smaller than a dword)
+      union { T t[4]; unsigned long long v; } pk;
+      pk.t[0] = q0;
+      pk.t[1] = q1;
+      pk.t[2] = q2;
+      pk.t[3] = q3;
+      *reinterpret_cast<unsigned long long*>(dG_cur + ft_offset<T>(b, 4 * n, nstepsB)) = pk.v;
+      const int col = col0 + b;
+      T* dGT = reinterpret_cast<T*>(p.dGT);
+      dGT[ft_offset<T>(4 * n + 0, col, ncs)] = q0;
+      dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
+      dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
+      dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
+      reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)st_hprev[q];
+    }
+    if (publish) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's columns of dG have reached the L2
+      __syncthreads();
+      if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // the forward operation of the next lower step runs while the other workgroups arrive
+      forward(j + 1);
+      if (j + 2 < p.count) fetch_fwd(j + 2);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < IPT; ++q)
+    if (mine[q]) p.dc[(size_t)ib[q] * p.H + iu[q]] = dc_run[q];
+}
+
+struct SweepConfig {
+  int nrt, nswf, ksf, nswb, ksb, nbt, nsxw;
+};
+static const SweepConfig SWEEP_CONFIGS[] = {
+    {4, 5, 4, 8, 8, 1, 1}, {4, 5, 4, 8, 8, 2, 1},   // H = 512, I <= 128
+    {2, 4, 4, 4, 8, 1, 2}, {2, 4, 4, 4, 8, 2, 2},   // H = 256, 128 < I <= 256
+    {1, 2, 4, 4, 4, 1, 1}, {1, 2, 4, 4, 4, 2, 1},   // H = 128, I <= 128
+};
+
+static int sweep_config(const Dims& d) {
+  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;
+  const int nstepsF = d.KP / 32, nstepsB = d.G4 / 32;
+  const FwdConfig fc = forward_config<__bf16>(d);
+  const int ksf = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;
+  const int ksb = backward_config<__bf16>(d) == BWD_SMALLK ? 4 : 8;
+  if (nstepsF % ksf != 0 || nstepsB % ksb != 0) return -1;
+  const int nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  int nbt = 1;
+  for (int g = 0; g < RES_GROUPS; ++g) {
+    const int lo = g * nb, hi = (lo + nb < d.B ? lo + nb : d.B);
+    if (lo >= d.B) break;
+    const int span = (hi - 1) / 16 - lo / 16 + 1;
+    nbt = span > nbt ? span : nbt;
+  }
+  for (size_t i = 0; i < sizeof SWEEP_CONFIGS / sizeof SWEEP_CONFIGS[0]; ++i) {
+    const SweepConfig& c = SWEEP_CONFIGS[i];
+    if (c.nrt == d.H / 128 && c.ksf == ksf && c.nswf == nstepsF / ksf && c.ksb == ksb && c.nswb == nstepsB / ksb &&
+        c.nbt == nbt && c.nsxw == (d.KX / 32 + ksf - 1) / ksf)
+      return (int)i;
+  }
+  return -1;
+}
+
+bool can_run_sweep(const Dims& d) { return sweep_config(d) >= 0; }
+int sweep_max_steps() { return SWEEP_MAX_STEPS; }
+
+template <int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+static hipError_t launch_sweep_cfg(const SweepParams& p, hipStream_t st) {
+  constexpr int NTB = (NRT * 4 + 15) / 16;
+  const size_t lds = ((size_t)KSF * NRT * NBT + (size_t)KSB * NTB * NBT) * 4 * 64 * sizeof(float);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_kernel<NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  sweep_kernel<NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW><<<dim3(RES_WGS), dim3(512), lds, st>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
+  const int cfg = sweep_config(d);
+  if (cfg < 0 || a.count < 1 || a.count > SWEEP_MAX_STEPS) return hipErrorInvalidValue;
+  if ((a.s_hi - 1) / d.CH != (a.s_hi - a.count) / d.CH) return hipErrorInvalidValue;   // one chunk per launch
+  SweepParams p{};
+  p.Wp = a.Wp;
+  p.WTh = a.WTh;
+  p.bp = a.bp;
+  p.x = a.x;
+  p.dy = a.dy;
+  p.dy_first = a.dy_first;
+  p.dy_is_h = a.dy_is_h;
+  p.dc = a.dc;
+  p.y_out = a.y_out;
+  p.dG_next = a.dG_next;
+  p.dG_chunk = a.dG_chunk;
+  p.dGT = a.dGT;
+  p.aT = a.aT;
+  p.sync = a.sync;
+  p.base = a.base;
+  p.launch = a.launch;
+  p.s_hi = a.s_hi;
+  p.count = a.count;
+  p.B = d.B;
+  p.I = d.I;
+  p.H = d.H;
+  p.KX = d.KX;
+  p.KH = d.KH;
+  p.BP = d.BP;
+  p.nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  p.G4 = d.G4;
+  p.NX = d.NX;
+  p.KC = d.KC;
+  p.CH = d.CH;
+  p.unit = d.unit;
+  for (int j = 0; j < a.count; ++j) p.src[j] = a.src[j];
+  switch (cfg) {
+    case 0: return launch_sweep_cfg<4, 5, 4, 8, 8, 1, 1>(p, st);
+    case 1: return launch_sweep_cfg<4, 5, 4, 8, 8, 2, 1>(p, st);
+    case 2: return launch_sweep_cfg<2, 4, 4, 4, 8, 1, 2>(p, st);
+    case 3: return launch_sweep_cfg<2, 4, 4, 4, 8, 2, 2>(p, st);
+    case 4: return launch_sweep_cfg<1, 2, 4, 4, 4, 1, 1>(p, st);
+    default: return launch_sweep_cfg<1, 2, 4, 4, 4, 2, 1>(p, st);
   }
 }
 

@@ -262,6 +262,9 @@ int mebptt_profile_collect(mebptt_profile* out) {
     } else if (s.cls == MEBPTT_K_CHAIN) {
       out->chain_steps += s.launches;
       out->chain_ms += ms;
+    } else if (s.cls == MEBPTT_K_SWEEP) {
+      out->sweep_steps += s.launches;
+      out->sweep_ms += ms;
     } else {
       out->forward_run_launches += s.launches;
       out->forward_run_ms += ms;
@@ -640,6 +643,46 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   int pend_step = 0;
   int chain_order_dev = -1;   // device whose chain-ordering event this run waits for and records
 
+  // The time-batched weight gradient and dx of a chunk whose first step has just been back-propagated.
+  auto complete_chunk = [&](int chunk) -> int {
+    const int buf = chunk & 1;
+    const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
+    const size_t x_off = (size_t)chunk * CH * d.B * d.I;
+    if (side) {
+      HIP_TRY(hipEventRecord(side->full[buf], st));
+      HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
+    }
+    HIP_TRY(tm(MEBPTT_K_WGRAD, st2, [&] {
+      hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
+      if (e != hipSuccess) return e;
+      return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1,
+                          reinterpret_cast<float*>(ws + w.dWacc), st2);
+    }));
+    if (dx)
+      HIP_TRY(tm(MEBPTT_K_DGRAD, st2, [&] {
+        return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
+      }));
+    if (side) {
+      HIP_TRY(hipEventRecord(side->done[buf], st2));
+      pending[buf] = true;
+    }
+    first_chunk = false;
+    return MEBPTT_OK;
+  };
+  // Before the first write into a chunk's buffers: their previous user (the GEMMs of the chunk
+  // two before) must be done.
+  auto begin_chunk = [&](int chunk) -> int {
+    if (chunk != cur_chunk) {
+      const int buf = chunk & 1;
+      if (pending[buf]) {
+        HIP_TRY(hipStreamWaitEvent(st, side->done[buf], 0));
+        pending[buf] = false;
+      }
+      cur_chunk = chunk;
+    }
+    return MEBPTT_OK;
+  };
+
   // Launches the held-back backward step, alone or fused with one forward operation, then the
   // time-batched work of its chunk if the step completed one.
   auto flush_backward = [&](const float* x_s, const float* f_src, float* f_dst, float* f_gates) -> int {
@@ -654,30 +697,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     ++bwd;
     have_pending = false;
     const int s = pend_step;
-    const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
-    if (slot == 0) {   // the chunk is complete: time-batched weight gradient and dx
-      const int nslots = (t - chunk * CH) < CH ? (t - chunk * CH) : CH;
-      const size_t x_off = (size_t)chunk * CH * d.B * d.I;
-      if (side) {
-        HIP_TRY(hipEventRecord(side->full[buf], st));
-        HIP_TRY(hipStreamWaitEvent(st2, side->full[buf], 0));
-      }
-      HIP_TRY(tm(MEBPTT_K_WGRAD, st2, [&] {
-        hipError_t e = launch_transpose_x(d, x + x_off, nslots, ws + w.aT[buf], st2);
-        if (e != hipSuccess) return e;
-        return launch_wgrad(d, ws + w.dGT[buf], ws + w.aT[buf], nslots, first_chunk ? 0 : 1,
-                            reinterpret_cast<float*>(ws + w.dWacc), st2);
-      }));
-      if (dx)
-        HIP_TRY(tm(MEBPTT_K_DGRAD, st2, [&] {
-          return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
-        }));
-      if (side) {
-        HIP_TRY(hipEventRecord(side->done[buf], st2));
-        pending[buf] = true;
-      }
-      first_chunk = false;
-    }
+    if ((s - 1) % CH == 0) return complete_chunk((s - 1) / CH);   // the chunk is complete
     return MEBPTT_OK;
   };
 
@@ -700,8 +720,99 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   std::vector<FStep> fsteps;
   const std::vector<mebptt_op>& ops = plan->ops;
 
+  // Before the first launch of this run that wants the whole chip: wait for the last run that had
+  // such launches (on whatever stream), unless this stream is being captured.
+  auto order_resident_launches = [&]() -> int {
+    if (chain_used) return MEBPTT_OK;
+    chain_used = true;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(st, &cap));
+    chain_order_dev = (cap == hipStreamCaptureStatusNone && dev >= 0 && dev < MAX_DEVICES) ? dev : -1;
+    if (chain_order_dev >= 0 && g_chain_recorded[chain_order_dev])
+      HIP_TRY(hipStreamWaitEvent(st, g_chain_done[chain_order_dev], 0));
+    return MEBPTT_OK;
+  };
+  // "forward operation of step s keeping its internal state in the working core, then the backward
+  // operation of step s" -- the pair every step of a sub-sequence that fits into memory ends in.
+  const bool sweep_ok = mode != RUN_STATIC && g_chain_enabled && can_run_sweep(d);
+  auto pair_at = [&](size_t i) {
+    if (i + 1 >= ops.size()) return false;
+    const mebptt_op &f = ops[i], &b = ops[i + 1];
+    return f.op == MEBPTT_OP_FWD_RUN && f.count == 1 && f.keep && f.dst == MEBPTT_LOC_CORE && b.op == MEBPTT_OP_BWD &&
+           b.dst == MEBPTT_LOC_CORE && b.src == f.src && b.step == f.step;
+  };
+
   for (size_t oi = 0; oi < ops.size();) {
     const mebptt_op& op = ops[oi];
+    if (sweep_ok && pair_at(oi)) {
+      // a run of such pairs for steps going down inside one chunk goes out as one sweep launch
+      const int s_hi = op.step, chunk = (s_hi - 1) / CH;
+      int n = 0;
+      const float* srcs[64];
+      while (n < sweep_max_steps() && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - n &&
+             (s_hi - n - 1) / CH == chunk) {
+        srcs[n] = loc(ops[oi + 2 * (size_t)n].src);
+        ++n;
+      }
+      if (n >= 2) {
+        if (have_pending) {
+          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+          if (rc) return rc;
+        }
+        rc = begin_chunk(chunk);
+        if (rc) return rc;
+        rc = order_resident_launches();
+        if (rc) return rc;
+        for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
+        const int buf = chunk & 1;
+        SweepArgs a{};
+        a.Wp = Wp;
+        a.WTh = WTh;
+        a.bp = bp;
+        a.x = x;
+        a.dy = desc->loss == 0 ? dy : nullptr;
+        a.dy_first = desc->dy_first_step;
+        a.dy_is_h = desc->loss == 1;
+        a.dc = dc;
+        a.y_out = y_out;
+        a.dG_next = (s_hi == t) ? nullptr : ws + w.dG[(s_hi / CH) & 1] + (size_t)(s_hi % CH) * dG_step;
+        a.dG_chunk = ws + w.dG[buf];
+        a.dGT = ws + w.dGT[buf];
+        a.aT = ws + w.aT[buf];
+        a.sync = reinterpret_cast<unsigned*>(ws + w.sync);
+        a.base = chain_base;
+        a.launch = chain_launches;
+        a.s_hi = s_hi;
+        a.count = n;
+        a.src = srcs;
+        const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+        Sample smp{MEBPTT_K_SWEEP, nullptr, nullptr, n};
+        if (bracket) {
+          smp.start = g_prof.get();
+          smp.stop = g_prof.get();
+          if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+          HIP_TRY(hipEventRecord(smp.start, st));
+        }
+        HIP_TRY(launch_sweep(d, a, st));
+        if (bracket) {
+          HIP_TRY(hipEventRecord(smp.stop, st));
+          g_prof.runs.push_back(smp);
+        }
+        if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_SWEEP];
+        chain_base += forward_chain_arrivals(n);
+        ++chain_launches;
+        fwd += n;
+        bwd += n;
+        if ((s_hi - n) % CH == 0) {   // the launch reached the first step of the chunk
+          rc = complete_chunk(chunk);
+          if (rc) return rc;
+        }
+        oi += 2 * (size_t)n;
+        continue;
+      }
+    }
     if (op.op == MEBPTT_OP_FWD_RUN) {
       size_t oe = oi + 1;
       if (chain_ok)
@@ -743,16 +854,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         }
       }
       if (chain_ok && total - fi >= (size_t)CHAIN_MIN_STEPS) {
-        if (!chain_used) {
-          chain_used = true;
-          int dev = 0;
-          HIP_TRY(hipGetDevice(&dev));
-          hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-          HIP_TRY(hipStreamIsCapturing(st, &cap));
-          chain_order_dev = (cap == hipStreamCaptureStatusNone && dev >= 0 && dev < MAX_DEVICES) ? dev : -1;
-          if (chain_order_dev >= 0 && g_chain_recorded[chain_order_dev])
-            HIP_TRY(hipStreamWaitEvent(st, g_chain_done[chain_order_dev], 0));
-        }
+        rc = order_resident_launches();
+        if (rc) return rc;
         const int max_steps = forward_chain_max_steps();
         ChainStep cs[64];
         while (fi < total) {
@@ -817,13 +920,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       }
       const int s = op.step;
       const int chunk = (s - 1) / CH, slot = (s - 1) % CH, buf = chunk & 1;
-      if (chunk != cur_chunk) {   // first write into this chunk buffer: its previous user must be done
-        if (pending[buf]) {
-          HIP_TRY(hipStreamWaitEvent(st, side->done[buf], 0));
-          pending[buf] = false;
-        }
-        cur_chunk = chunk;
-      }
+      rc = begin_chunk(chunk);
+      if (rc) return rc;
       touch(op.dst, 3);
       touch(op.src, 1);
       pend = BackwardArgs{};

@@ -1,5 +1,6 @@
-"""GPU tests of the forward-chain launches (a chain of forward operations in one launch, gate
-weights resident on the chip, the batch split over the XCDs): against the float64 oracle, bit for
+"""GPU tests of the forward-chain and sweep launches (a chain of forward operations, or a run of
+forward+backward pairs, in one launch, weights resident on the chip, the batch split over the
+XCDs): against the float64 oracle, bit for
 bit against the launch-per-step path on the same inputs, for every strategy and many budgets, on
 every shape class the kernel is instantiated for, with ragged batches, and from two host threads
 at once."""
@@ -79,9 +80,13 @@ def test_chain_launch_count_and_status():
     mb.mebptt_profile_enable(0)
     assert mb.mebptt_run_status(s.desc, s.workspace) == 0
     assert out.stats.forward_ops == 2 * w.t - 1
-    assert prof.chain_steps >= w.t - 2                     # the initial sweep went out as chains
+    assert prof.chain_steps >= w.t - 2                     # the initial forward pass went out as chains
     assert prof.launches[mb.K_CHAIN] <= (w.t + 47) // 48 + 1
-    assert prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps == out.stats.forward_ops
+    assert prof.sweep_steps >= w.t - 40                    # and the way back as sweep launches, one per chunk of steps
+    assert prof.launches[mb.K_SWEEP] <= (w.t + 31) // 32 + 1
+    assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.sweep_steps
+            == out.stats.forward_ops)
+    assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == w.t
 
 
 def test_chains_from_two_host_threads():
