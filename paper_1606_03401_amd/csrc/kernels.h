@@ -140,8 +140,11 @@ struct SweepArgs {
   unsigned base, launch;
   int s_hi, count;
   const float* const* src;
+  const float* const* state;   // NULL, or per step the unit where an earlier launch stored the internal state:
+                               // then no forward operation is run (can_run_backward_sweep() shapes)
 };
 bool can_run_sweep(const Dims& d);
+bool can_run_backward_sweep(const Dims& d);
 int sweep_max_steps();
 hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st);
 

@@ -389,6 +389,26 @@ __device__ inline RawAct<VEC> load_raw(const float* __restrict__ row, int k, int
   return r;
 }
 
+// As load_raw for rows whose length is a multiple of VEC (k is one too): a fragment lies wholly
+// inside the row or wholly outside, so one address clamp and one select replace the branches.
+// (Branches that load into the same registers make the compiler wait for every outstanding memory
+// operation between them.)
+template <int VEC>
+__device__ inline RawAct<VEC> load_raw_whole(const float* __restrict__ row, int k, int limit) {
+  RawAct<VEC> r;
+  const bool inside = k < limit;
+  const float* src = row + (inside ? k : 0);
+#pragma unroll
+  for (int e = 0; e < VEC; e += 4) {
+    const float4 q = *reinterpret_cast<const float4*>(src + e);
+    r.v[e] = inside ? q.x : 0.0f;
+    r.v[e + 1] = inside ? q.y : 0.0f;
+    r.v[e + 2] = inside ? q.z : 0.0f;
+    r.v[e + 3] = inside ? q.w : 0.0f;
+  }
+  return r;
+}
+
 // One workgroup of 64*KS threads = BT batch tiles (16 sequences each) x NG unit groups (4 hidden
 // units = 16 gate rows each).  Its KS waves split the K axis; every wave covers all NG x BT output
 // tiles (each weight fragment is reused for BT batch tiles, each activation fragment for NG unit
@@ -988,6 +1008,19 @@ __device__ inline unsigned xcc_id() {
   return v & 0xf;
 }
 
+// One operand fragment (16 bytes per lane) fetched with agent scope: the load skips this compute
+// unit's vector cache and is served by the XCD's L2, where the other compute units of the XCD have
+// just written it.  A buffer load with the scope bit, not an atomic load: the compiler may keep as
+// many of them in flight as it has registers for (atomic loads it issues two at a time).
+// `base` is wave-uniform; byte_off < 2^31.
+__device__ inline bf16x8 load_frag_l2(const void* base, unsigned byte_off) {
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+  union { u32x4 u; bf16x8 f; } cv;
+  cv.u = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, 16 /* sc1: agent scope */);
+  return cv.f;
+}
+
 template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
 __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
   using T = __bf16;
@@ -1068,20 +1101,6 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
     }
   }
   const bool x_vec = (p.I & 3) == 0;
-#ifdef MEBPTT_CHAIN_TIMELINE
-  long long tl_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  long long tl_prev = wall_clock64();
-#define TL_MARK(i)                                   \
-  do {                                               \
-    if (threadIdx.x == 0 && j > 0) {                 \
-      const long long now_ = wall_clock64();         \
-      tl_sum[i] += now_ - tl_prev;                   \
-      tl_prev = now_;                                \
-    }                                                \
-  } while (0)
-#else
-#define TL_MARK(i)
-#endif
 
   // Raw x values of this wave's x macro steps for the step about to run (NSXW = how many of the
   // wave's first steps can fall into the x segment at all: KX / 32 / KS rounded up).
@@ -1103,9 +1122,6 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
   fetch_x(0);
 
   for (int j = 0; j < p.count; ++j) {
-#ifdef MEBPTT_CHAIN_TIMELINE
-    if (threadIdx.x == 0) tl_prev = wall_clock64();
-#endif
     // x fragments: the raw fp32 values were requested a step ahead (see below) and are converted
     // now; they do not depend on the other workgroups
     typename M::Frag bf[NSW][NBT];
@@ -1115,7 +1131,6 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
 #pragma unroll
         for (int bt = 0; bt < NBT; ++bt) bf[i][bt] = M::from_f32(xraw[i][bt].v);
       }
-    TL_MARK(0);   // x fragments fetched and converted
     if (j > 0) {
       // all 32 workgroups of this XCD have published h of the previous step?
       if (threadIdx.x == 0) {
@@ -1138,11 +1153,9 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         }
         s_go = ok;
       }
-      TL_MARK(1);   // wait for the other workgroups
       __syncthreads();
       if (!s_go) return;
     }
-    TL_MARK(2);
     // h fragments: the stored input state for the first step, then the exchange ring
     {
       const T* hsrc = (j == 0) ? reinterpret_cast<const T*>(p.src)
@@ -1153,21 +1166,16 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         if (s >= nsx) {
 #pragma unroll
           for (int bt = 0; bt < NBT; ++bt) {
-            const T* fp = hsrc + (((size_t)min(ct0 + bt, nbt_all - 1) * nsh + (s - nsx)) * 64 + lane) * VEC;
-            if (j == 0) {
-              bf[i][bt] = M::load(fp);
-            } else {
-              // agent-scope loads: they skip this compute unit's vector cache and are served by the XCD's L2
-              union { unsigned long long q[2]; typename M::Frag f; } cv;
-              const unsigned long long* qp = reinterpret_cast<const unsigned long long*>(fp);
-              cv.q[0] = __hip_atomic_load(qp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              cv.q[1] = __hip_atomic_load(qp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              bf[i][bt] = cv.f;
-            }
+            const size_t fo = (((size_t)min(ct0 + bt, nbt_all - 1) * nsh + (s - nsx)) * 64 + lane) * VEC;
+            if (j == 0)
+              bf[i][bt] = M::load(hsrc + fo);
+            else
+              bf[i][bt] = load_frag_l2(hsrc, (unsigned)(fo * sizeof(T)));
           }
         }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // every fetch is issued before the first MFMA
     f32x4 acc[NRT][NBT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
@@ -1190,9 +1198,7 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
       for (int bt = 0; bt < NBT; ++bt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[((wave * NT + rt * NBT + bt) * 4 + r) * 64 + lane] = acc[rt][bt][r];
-    TL_MARK(3);   // h fetched, GEMM slice done, partial sums in LDS
     __syncthreads();
-    TL_MARK(4);
     const ResStep dst = p.step[j];
     T* ring_out = reinterpret_cast<T*>(p.ring) + (size_t)(j % RES_RING) * hhalf;
     const bool publish = j + 1 < p.count;
@@ -1228,23 +1234,12 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         dst.gates[p.unit + plane + e] = gate[3];
       }
     }
-    TL_MARK(5);   // pointwise step, stores issued
     if (publish) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's slice of h has reached the L2
-      TL_MARK(6);
       __syncthreads();
       if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      TL_MARK(7);
     }
   }
-#ifdef MEBPTT_CHAIN_TIMELINE
-  if (threadIdx.x == 0 && p.count > 4) {   // ticks of the 100 MHz clock per phase, summed over the launch's steps
-    unsigned long long* outp = reinterpret_cast<unsigned long long*>(p.sync + 1088) + (size_t)(g * RES_MEMBERS + rank) * 9;
-    for (int i = 0; i < 8; ++i) outp[i] += (unsigned long long)tl_sum[i];
-    outp[8] += (unsigned long long)(p.count - 1);
-  }
-#endif
-#undef TL_MARK
 }
 
 // Shape classes with an instantiation: {NRT = H/128, NSW = macro steps per wave, NSL, KS, NBT}.
@@ -1284,11 +1279,7 @@ static int resident_config(const Dims& d) {
 bool can_run_forward_chain(const Dims& d) { return resident_config(d) >= 0; }
 int forward_chain_max_steps() { return RES_MAX_STEPS; }
 size_t forward_chain_ring_bytes(const Dims& d) { return (size_t)RES_RING * d.BP * d.KH * sizeof(__bf16); }
-#ifdef MEBPTT_CHAIN_TIMELINE
-size_t forward_chain_sync_bytes() { return (1088 + 2 * 9 * RES_WGS) * sizeof(unsigned); }
-#else
 size_t forward_chain_sync_bytes() { return (1024 + 64) * sizeof(unsigned); }
-#endif
 size_t forward_chain_status_offset() { return 1024 * sizeof(unsigned); }
 unsigned forward_chain_arrivals(int steps) { return steps > 1 ? (unsigned)(steps - 1) * RES_MEMBERS : 0u; }
 
@@ -1377,13 +1368,16 @@ struct SweepParams {
   int B, I, H, KX, KH, BP, nb, G4, NX, KC, CH;
   size_t unit;
   const float* src[SWEEP_MAX_STEPS];   // src[j]: unit holding the state before step s_hi - j
+  const float* state[SWEEP_MAX_STEPS]; // FWD = false: unit holding the stored internal state of step s_hi - j
 };
 
-template <int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+// FWD = false: the internal states are not recomputed but read from where an earlier launch
+// stored them (internal-state slots): a run of backward operations only, W_hh^T alone resident.
+template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
 __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
   using T = __bf16;
   using M = Mma<T>;
-  constexpr int VEC = 8, KSTEP = 32, FRAG = 64 * VEC;
+  constexpr int VEC = 8, KSTEP = 32;
   constexpr int FT = 8 / KSF;                       // groups of waves that split the forward row tiles
   constexpr int NRTW = (NRT + FT - 1) / FT;         // forward row tiles per wave
   constexpr int UW = NRT * 4;                       // hidden units per workgroup
@@ -1425,14 +1419,16 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
   const int nt0 = (rank * UW) / 16;                 // first 16-unit tile of the dh GEMM
 
   // resident weights: forward rows of this workgroup's units, and the rows of W_hh^T for the same units
-  typename M::Frag wf[NRTW][NSWF], wb[NTB][NSWB];
+  typename M::Frag wf[FWD ? NRTW : 1][FWD ? NSWF : 1], wb[NTB][NSWB];
+  if (FWD) {
 #pragma unroll
-  for (int i = 0; i < NRTW; ++i) {
-    const int rt = min(fg * NRTW + i, NRT - 1);
+    for (int i = 0; i < NRTW; ++i) {
+      const int rt = min(fg * NRTW + i, NRT - 1);
 #pragma unroll
-    for (int k = 0; k < NSWF; ++k)
-      wf[i][k] = M::load(reinterpret_cast<const T*>(p.Wp) +
-                         (((size_t)(rank * NRT + rt) * nstepsF + fk + KSF * k) * 64 + lane) * VEC);
+      for (int k = 0; k < NSWF; ++k)
+        wf[FWD ? i : 0][FWD ? k : 0] = M::load(reinterpret_cast<const T*>(p.Wp) +
+                                               (((size_t)(rank * NRT + rt) * nstepsF + fk + KSF * k) * 64 + lane) * VEC);
+    }
   }
 #pragma unroll
   for (int tb = 0; tb < NTB; ++tb)
@@ -1467,13 +1463,36 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
       dc_run[q] = p.dc[(size_t)b * p.H + u];
     }
   }
-  const bool x_vec = (p.I & 3) == 0;
-
   // operands of a forward operation, requested a step ahead: raw x values, h fragments, c_{s-1}, h_{s-1}
-  RawAct<VEC> xraw[NSXW][NBT];
-  typename M::Frag hfr[NSWF][NBT];
+  RawAct<VEC> xraw[FWD ? NSXW : 1][NBT];
+  typename M::Frag hfr[FWD ? NSWF : 1][NBT];
   float pf_cprev[IPT], pf_hprev[IPT];
+  float pf_gate[FWD ? 1 : IPT][4], pf_c[FWD ? 1 : IPT], pf_h[FWD ? 1 : IPT];   // FWD = false: the stored state, a step ahead
+  const bool want_h = p.dy_is_h || p.y_out != nullptr;
   auto fetch_fwd = [&](int j) {
+    if (!FWD) {
+      const float* stp = p.state[j];
+      const float* src = p.src[j];
+#pragma unroll
+      for (int q = 0; q < IPT; ++q) {
+        pf_cprev[q] = pf_hprev[q] = 0.0f;
+        pf_c[FWD ? 0 : q] = pf_h[FWD ? 0 : q] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pf_gate[FWD ? 0 : q][r] = 0.0f;
+        if (mine[q]) {
+          const size_t e = (size_t)ib[q] * p.H + iu[q];
+          pf_gate[FWD ? 0 : q][0] = stp[p.unit + e];
+          pf_gate[FWD ? 0 : q][1] = stp[p.unit + plane + e];
+          pf_gate[FWD ? 0 : q][2] = stp[2 * p.unit + e];
+          pf_gate[FWD ? 0 : q][3] = stp[2 * p.unit + plane + e];
+          pf_c[FWD ? 0 : q] = stp[hhalf + e];
+          if (want_h) pf_h[FWD ? 0 : q] = HPlane<T>::load(stp, ib[q], iu[q], nsh, p.H, hhalf);
+          pf_cprev[q] = src[hhalf + e];
+          pf_hprev[q] = (float)HPlane<T>::as_operand(src, ib[q], iu[q], nsh, p.H, hhalf);
+        }
+      }
+      return;
+    }
     const int s = p.s_hi - j;
     const float* x_s = p.x + (size_t)(s - 1) * p.B * p.I;
     const float* src = p.src[j];
@@ -1484,10 +1503,10 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
       for (int bt = 0; bt < NBT; ++bt) {
         const int tile = min(ct0 + bt, nbt_all - 1);
         if (ms < nsx) {
-          if (k < NSXW) xraw[k < NSXW ? k : 0][bt] = load_raw<VEC>(x_s + (size_t)min(tile * 16 + lrow, p.B - 1) * p.I,
-                                                                   ms * KSTEP + VEC * lq, p.I, x_vec);
+          if (k < NSXW) xraw[(FWD && k < NSXW) ? k : 0][bt] = load_raw_whole<VEC>(x_s + (size_t)min(tile * 16 + lrow, p.B - 1) * p.I,
+                                                                                  ms * KSTEP + VEC * lq, p.I);
         } else {
-          hfr[k][bt] = M::load(reinterpret_cast<const T*>(src) + (((size_t)tile * nsh + (ms - nsx)) * 64 + lane) * VEC);
+          hfr[FWD ? k : 0][bt] = M::load(reinterpret_cast<const T*>(src) + (((size_t)tile * nsh + (ms - nsx)) * 64 + lane) * VEC);
         }
       }
     }
@@ -1500,33 +1519,56 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
       }
     }
   };
-  // forward operation of step s_hi - j from the fetched operands; leaves the internal state in st_*
-  auto forward = [&](int j) {
-    f32x4 acc[NRTW][NBT];
+  // The forward operation of step s_hi - j comes in two parts, so that the memory operations
+  // between them overlap with neither's waits.  (Loads and stores share one in-order counter: once
+  // both kinds are in flight, a wait for any load is a wait for everything, store acknowledgements
+  // included.)  Part one runs right after an arrival, when nothing is outstanding: the GEMM slice
+  // from the fetched operands, then the request for the operands of the step after.  Part two, after
+  // the stores that only later launches read have been issued, reduces the slices and applies the
+  // gate functions; it leaves the internal state in st_*.
+  auto forward_gemm = [&](int j) {
 #pragma unroll
-    for (int i = 0; i < NRTW; ++i)
+    for (int q = 0; q < IPT; ++q) {
+      st_cprev[q] = pf_cprev[q];
+      st_hprev[q] = pf_hprev[q];
+      if (!FWD) {   // nothing to compute: the fetched state becomes the current one
 #pragma unroll
-      for (int bt = 0; bt < NBT; ++bt) acc[i][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < NSWF; ++k) {
-      const int ms = fk + KSF * k;
-#pragma unroll
-      for (int bt = 0; bt < NBT; ++bt) {
-        const typename M::Frag bfr = (k < NSXW && ms < nsx) ? M::from_f32(xraw[k < NSXW ? k : 0][bt].v) : hfr[k][bt];
-#pragma unroll
-        for (int i = 0; i < NRTW; ++i) acc[i][bt] = M::mma(wf[i][k], bfr, acc[i][bt]);
+        for (int r = 0; r < 4; ++r) st_gate[q][r] = pf_gate[FWD ? 0 : q][r];
+        st_c[q] = pf_c[FWD ? 0 : q];
+        st_h[q] = pf_h[FWD ? 0 : q];
       }
     }
+    if (FWD) {
+      f32x4 acc[NRTW][NBT];
 #pragma unroll
-    for (int i = 0; i < NRTW; ++i) {
-      const int rt = fg * NRTW + i;
-      if (rt < NRT) {
+      for (int i = 0; i < NRTW; ++i)
 #pragma unroll
-        for (int bt = 0; bt < NBT; ++bt)
+        for (int bt = 0; bt < NBT; ++bt) acc[i][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int r = 0; r < 4; ++r) redF[((fk * NTF + rt * NBT + bt) * 4 + r) * 64 + lane] = acc[i][bt][r];
+      for (int k = 0; k < NSWF; ++k) {
+        const int ms = fk + KSF * k;
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt) {
+          const typename M::Frag bfr = (k < NSXW && ms < nsx) ? M::from_f32(xraw[(FWD && k < NSXW) ? k : 0][bt].v) : hfr[FWD ? k : 0][bt];
+#pragma unroll
+          for (int i = 0; i < NRTW; ++i) acc[i][bt] = M::mma(wf[FWD ? i : 0][FWD ? k : 0], bfr, acc[i][bt]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NRTW; ++i) {
+        const int rt = fg * NRTW + i;
+        if (rt < NRT) {
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) redF[((fk * NTF + rt * NBT + bt) * 4 + r) * 64 + lane] = acc[i][bt][r];
+        }
       }
     }
+    if (j + 1 < p.count) fetch_fwd(j + 1);
+  };
+  auto forward_point = [&]() {
+    if (!FWD) return;
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < IPT; ++q) {
@@ -1536,16 +1578,14 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) G[r] += redF[w * NTF * 4 * 64 + icellF[q] + r * 64];
       float second;
-      st_h[q] = cell_forward<0>(G, bias[q], pf_cprev[q], second, st_gate[q]);
+      st_h[q] = cell_forward<0>(G, bias[q], st_cprev[q], second, st_gate[q]);
       st_c[q] = second;
-      st_cprev[q] = pf_cprev[q];
-      st_hprev[q] = pf_hprev[q];
     }
   };
 
   fetch_fwd(0);
-  forward(0);
-  if (p.count > 1) fetch_fwd(1);
+  forward_gemm(0);   // also requests the operands of the step after
+  forward_point();
 
   for (int j = 0; j < p.count; ++j) {
     const int s = p.s_hi - j;                       // the step back-propagated now
@@ -1584,25 +1624,30 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
         for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
           for (int bt = 0; bt < NBT; ++bt) acc[tb][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        typename M::Frag gfr[NSWB][NBT];
+        // The dG fragments come in rounds of GK macro steps: all fetches of a round go out before its
+        // first MFMA (left to itself the scheduler pairs each fetch with the MFMA that needs it, one
+        // L2 round trip after the other).  Two batch tiles beside resident forward weights leave
+        // registers for half the fragments at a time only.
+        constexpr int GK = (FWD && NBT > 1) ? NSWB / 2 : NSWB;
 #pragma unroll
-        for (int k = 0; k < NSWB; ++k)
+        for (int k0 = 0; k0 < NSWB; k0 += GK) {
+          typename M::Frag gfr[GK][NBT];
 #pragma unroll
-          for (int bt = 0; bt < NBT; ++bt) {
-            const T* fp = dG_next + (((size_t)min(ct0 + bt, nbt_all - 1) * nstepsB + wave + KSB * k) * 64 + lane) * VEC;
-            // agent-scope loads: served by the XCD's L2, never by this compute unit's vector cache
-            union { unsigned long long q[2]; typename M::Frag f; } cv;
-            const unsigned long long* qp = reinterpret_cast<const unsigned long long*>(fp);
-            cv.q[0] = __hip_atomic_load(qp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            cv.q[1] = __hip_atomic_load(qp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            gfr[k][bt] = cv.f;
-          }
+          for (int k = 0; k < GK; ++k)
 #pragma unroll
-        for (int k = 0; k < NSWB; ++k)
+            for (int bt = 0; bt < NBT; ++bt) {
+              const size_t fo = (((size_t)min(ct0 + bt, nbt_all - 1) * nstepsB + wave + KSB * (k0 + k)) * 64 + lane) * VEC;
+              gfr[k][bt] = load_frag_l2(dG_next, (unsigned)(fo * sizeof(T)));
+            }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int tb = 0; tb < NTB; ++tb)
+          for (int k = 0; k < GK; ++k)
 #pragma unroll
-            for (int bt = 0; bt < NBT; ++bt) acc[tb][bt] = M::mma(wb[tb][k], gfr[k][bt], acc[tb][bt]);
+            for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+              for (int bt = 0; bt < NBT; ++bt) acc[tb][bt] = M::mma(wb[tb][k0 + k], gfr[k][bt], acc[tb][bt]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
@@ -1616,6 +1661,8 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
     const bool publish = j + 1 < p.count;
     T* dG_cur = reinterpret_cast<T*>(p.dG_chunk) + (size_t)slot * dG_step;
     const int ncs = p.KC / KSTEP, col0 = slot * p.B;
+    T gq[IPT][4];
+    float keep_h[IPT], keep_hprev[IPT];
 #pragma unroll
     for (int q = 0; q < IPT; ++q) {
       if (!mine[q]) continue;
@@ -1630,36 +1677,40 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
       else if (p.dy != nullptr && s >= p.dy_first)
         dyv = p.dy[(size_t)(s - p.dy_first) * plane + e];
       dh += dyv;
-      if (p.y_out) p.y_out[(size_t)(s - 1) * plane + e] = st_h[q];
       float dG[4], dc_out;
       lstm_backward_point(dh, dc_run[q], st_gate[q][0], st_gate[q][1], st_gate[q][2], st_gate[q][3], st_c[q], st_cprev[q],
                           dG, dc_out);
       dc_run[q] = dc_out;
-      const T q0 = (T)dG[0], q1 = (T)dG[1], q2 = (T)dG[2], q3 = (T)dG[3];
       // the four gates of a unit are consecutive in dG: one 8-byte store (what other compute units
       // fetch next must not be written in pieces smaller than a dword)
       union { T t[4]; unsigned long long v; } pk;
-      pk.t[0] = q0;
-      pk.t[1] = q1;
-      pk.t[2] = q2;
-      pk.t[3] = q3;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pk.t[r] = gq[q][r] = (T)dG[r];
       *reinterpret_cast<unsigned long long*>(dG_cur + ft_offset<T>(b, 4 * n, nstepsB)) = pk.v;
-      const int col = col0 + b;
-      T* dGT = reinterpret_cast<T*>(p.dGT);
-      dGT[ft_offset<T>(4 * n + 0, col, ncs)] = q0;
-      dGT[ft_offset<T>(4 * n + 1, col, ncs)] = q1;
-      dGT[ft_offset<T>(4 * n + 2, col, ncs)] = q2;
-      dGT[ft_offset<T>(4 * n + 3, col, ncs)] = q3;
-      reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)st_hprev[q];
+      keep_h[q] = st_h[q];
+      keep_hprev[q] = st_hprev[q];
     }
     if (publish) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's columns of dG have reached the L2
       __syncthreads();
       if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      // the forward operation of the next lower step runs while the other workgroups arrive
-      forward(j + 1);
-      if (j + 2 < p.count) fetch_fwd(j + 2);
+      forward_gemm(j + 1);
     }
+    // What only later launches read -- the transposed copies for the weight gradient, the output --
+    // is stored after the arrival: nobody in this launch waits for it.
+#pragma unroll
+    for (int q = 0; q < IPT; ++q) {
+      if (!mine[q]) continue;
+      const int b = ib[q], n = iu[q];
+      const int col = col0 + b;
+      T* dGT = reinterpret_cast<T*>(p.dGT);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) dGT[ft_offset<T>(4 * n + r, col, ncs)] = gq[q][r];
+      reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)keep_hprev[q];
+      if (p.y_out) p.y_out[(size_t)(s - 1) * plane + (size_t)b * p.H + n] = keep_h[q];
+    }
+    // the pointwise part of the next lower step's forward operation runs while the others arrive
+    if (publish) forward_point();
   }
 #pragma unroll
   for (int q = 0; q < IPT; ++q)
@@ -1673,10 +1724,12 @@ static const SweepConfig SWEEP_CONFIGS[] = {
     {4, 5, 4, 8, 8, 1, 1}, {4, 5, 4, 8, 8, 2, 1},   // H = 512, I <= 128
     {2, 4, 4, 4, 8, 1, 2}, {2, 4, 4, 4, 8, 2, 2},   // H = 256, 128 < I <= 256
     {1, 2, 4, 4, 4, 1, 1}, {1, 2, 4, 4, 4, 2, 1},   // H = 128, I <= 128
+    {8, 5, 8, 16, 8, 1, 1},                         // H = 1024, I <= 256: backward operations only (W_hh^T fits, both do not)
 };
+constexpr int SWEEP_BACKWARD_ONLY_FROM = 6;   // configurations from this index on have no forward part
 
 static int sweep_config(const Dims& d) {
-  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;
+  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H || d.I % 8 != 0) return -1;
   const int nstepsF = d.KP / 32, nstepsB = d.G4 / 32;
   const FwdConfig fc = forward_config<__bf16>(d);
   const int ksf = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;
@@ -1699,21 +1752,25 @@ static int sweep_config(const Dims& d) {
   return -1;
 }
 
-bool can_run_sweep(const Dims& d) { return sweep_config(d) >= 0; }
+bool can_run_sweep(const Dims& d) {
+  const int c = sweep_config(d);
+  return c >= 0 && c < SWEEP_BACKWARD_ONLY_FROM;
+}
+bool can_run_backward_sweep(const Dims& d) { return sweep_config(d) >= 0; }
 int sweep_max_steps() { return SWEEP_MAX_STEPS; }
 
-template <int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
 static hipError_t launch_sweep_cfg(const SweepParams& p, hipStream_t st) {
   constexpr int NTB = (NRT * 4 + 15) / 16;
   const size_t lds = ((size_t)KSF * NRT * NBT + (size_t)KSB * NTB * NBT) * 4 * 64 * sizeof(float);
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_kernel<NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  sweep_kernel<NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW><<<dim3(RES_WGS), dim3(512), lds, st>>>(p);
+  sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW><<<dim3(RES_WGS), dim3(512), lds, st>>>(p);
   return hipGetLastError();
 }
 
@@ -1752,14 +1809,29 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   p.KC = d.KC;
   p.CH = d.CH;
   p.unit = d.unit;
-  for (int j = 0; j < a.count; ++j) p.src[j] = a.src[j];
+  for (int j = 0; j < a.count; ++j) {
+    p.src[j] = a.src[j];
+    p.state[j] = a.state ? a.state[j] : nullptr;
+  }
+  if (a.state) {   // backward operations through stored internal states
+    switch (cfg) {
+      case 0: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 1, 1>(p, st);
+      case 1: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 2, 1>(p, st);
+      case 2: return launch_sweep_cfg<false, 2, 4, 4, 4, 8, 1, 2>(p, st);
+      case 3: return launch_sweep_cfg<false, 2, 4, 4, 4, 8, 2, 2>(p, st);
+      case 4: return launch_sweep_cfg<false, 1, 2, 4, 4, 4, 1, 1>(p, st);
+      case 5: return launch_sweep_cfg<false, 1, 2, 4, 4, 4, 2, 1>(p, st);
+      default: return launch_sweep_cfg<false, 8, 5, 8, 16, 8, 1, 1>(p, st);
+    }
+  }
   switch (cfg) {
-    case 0: return launch_sweep_cfg<4, 5, 4, 8, 8, 1, 1>(p, st);
-    case 1: return launch_sweep_cfg<4, 5, 4, 8, 8, 2, 1>(p, st);
-    case 2: return launch_sweep_cfg<2, 4, 4, 4, 8, 1, 2>(p, st);
-    case 3: return launch_sweep_cfg<2, 4, 4, 4, 8, 2, 2>(p, st);
-    case 4: return launch_sweep_cfg<1, 2, 4, 4, 4, 1, 1>(p, st);
-    default: return launch_sweep_cfg<1, 2, 4, 4, 4, 2, 1>(p, st);
+    case 0: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 1, 1>(p, st);
+    case 1: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 2, 1>(p, st);
+    case 2: return launch_sweep_cfg<true, 2, 4, 4, 4, 8, 1, 2>(p, st);
+    case 3: return launch_sweep_cfg<true, 2, 4, 4, 4, 8, 2, 2>(p, st);
+    case 4: return launch_sweep_cfg<true, 1, 2, 4, 4, 4, 1, 1>(p, st);
+    case 5: return launch_sweep_cfg<true, 1, 2, 4, 4, 4, 2, 1>(p, st);
+    default: return hipErrorInvalidValue;
   }
 }
 

@@ -371,12 +371,6 @@ int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_
   return MEBPTT_OK;
 }
 
-#ifdef MEBPTT_CHAIN_TIMELINE
-size_t mebptt_debug_sync_offset(const mebptt_lstm_desc* desc) {
-  return layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).sync;
-}
-#endif
-
 int mebptt_forward_chain_enable(int32_t on) {
   std::lock_guard<std::mutex> lock(g_run_mutex);
   g_chain_enabled = on != 0;
@@ -744,8 +738,87 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
            b.dst == MEBPTT_LOC_CORE && b.src == f.src && b.step == f.step;
   };
 
+  // Backward operations through internal states that earlier launches stored in slots (internal-state
+  // pushes; store-everything BPTT): consecutive ones go out as backward-only sweep launches.
+  const bool bsweep_ok = mode != RUN_STATIC && g_chain_enabled && can_run_backward_sweep(d);
+  auto stored_bwd_at = [&](size_t i) { return i < ops.size() && ops[i].op == MEBPTT_OP_BWD && ops[i].dst >= 0; };
+  // One sweep launch for steps s_hi, s_hi - 1, ... (n of them, one chunk); states == nullptr: with forward operations.
+  auto issue_sweep = [&](int s_hi, int n, const float* const* srcs, const float* const* states) -> int {
+    const int chunk = (s_hi - 1) / CH, buf = chunk & 1;
+    if (have_pending) {
+      rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+      if (rc) return rc;
+    }
+    rc = begin_chunk(chunk);
+    if (rc) return rc;
+    rc = order_resident_launches();
+    if (rc) return rc;
+    SweepArgs a{};
+    a.Wp = Wp;
+    a.WTh = WTh;
+    a.bp = bp;
+    a.x = x;
+    a.dy = desc->loss == 0 ? dy : nullptr;
+    a.dy_first = desc->dy_first_step;
+    a.dy_is_h = desc->loss == 1;
+    a.dc = dc;
+    a.y_out = y_out;
+    a.dG_next = (s_hi == t) ? nullptr : ws + w.dG[(s_hi / CH) & 1] + (size_t)(s_hi % CH) * dG_step;
+    a.dG_chunk = ws + w.dG[buf];
+    a.dGT = ws + w.dGT[buf];
+    a.aT = ws + w.aT[buf];
+    a.sync = reinterpret_cast<unsigned*>(ws + w.sync);
+    a.base = chain_base;
+    a.launch = chain_launches;
+    a.s_hi = s_hi;
+    a.count = n;
+    a.src = srcs;
+    a.state = states;
+    const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+    Sample smp{MEBPTT_K_SWEEP, nullptr, nullptr, n};
+    if (bracket) {
+      smp.start = g_prof.get();
+      smp.stop = g_prof.get();
+      if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+      HIP_TRY(hipEventRecord(smp.start, st));
+    }
+    HIP_TRY(launch_sweep(d, a, st));
+    if (bracket) {
+      HIP_TRY(hipEventRecord(smp.stop, st));
+      g_prof.runs.push_back(smp);
+    }
+    if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_SWEEP];
+    chain_base += forward_chain_arrivals(n);
+    ++chain_launches;
+    bwd += n;
+    if (!states) fwd += n;
+    if ((s_hi - n) % CH == 0) return complete_chunk(chunk);   // the launch reached the first step of the chunk
+    return MEBPTT_OK;
+  };
+
   for (size_t oi = 0; oi < ops.size();) {
     const mebptt_op& op = ops[oi];
+    if (bsweep_ok && stored_bwd_at(oi) && stored_bwd_at(oi + 1)) {
+      const int s_hi = op.step, chunk = (s_hi - 1) / CH;
+      int n = 0;
+      const float *srcs[64], *states[64];
+      while (n < sweep_max_steps() && stored_bwd_at(oi + (size_t)n) && ops[oi + (size_t)n].step == s_hi - n &&
+             (s_hi - n - 1) / CH == chunk) {
+        srcs[n] = loc(ops[oi + (size_t)n].src);
+        states[n] = loc(ops[oi + (size_t)n].dst);
+        ++n;
+      }
+      if (n >= 2) {
+        for (int j = 0; j < n; ++j) {
+          touch(ops[oi + (size_t)j].dst, 3);
+          touch(ops[oi + (size_t)j].src, 1);
+        }
+        rc = issue_sweep(s_hi, n, srcs, states);
+        if (rc) return rc;
+        oi += (size_t)n;
+        continue;
+      }
+    }
     if (sweep_ok && pair_at(oi)) {
       // a run of such pairs for steps going down inside one chunk goes out as one sweep launch
       const int s_hi = op.step, chunk = (s_hi - 1) / CH;
@@ -757,58 +830,9 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         ++n;
       }
       if (n >= 2) {
-        if (have_pending) {
-          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
-          if (rc) return rc;
-        }
-        rc = begin_chunk(chunk);
-        if (rc) return rc;
-        rc = order_resident_launches();
-        if (rc) return rc;
         for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
-        const int buf = chunk & 1;
-        SweepArgs a{};
-        a.Wp = Wp;
-        a.WTh = WTh;
-        a.bp = bp;
-        a.x = x;
-        a.dy = desc->loss == 0 ? dy : nullptr;
-        a.dy_first = desc->dy_first_step;
-        a.dy_is_h = desc->loss == 1;
-        a.dc = dc;
-        a.y_out = y_out;
-        a.dG_next = (s_hi == t) ? nullptr : ws + w.dG[(s_hi / CH) & 1] + (size_t)(s_hi % CH) * dG_step;
-        a.dG_chunk = ws + w.dG[buf];
-        a.dGT = ws + w.dGT[buf];
-        a.aT = ws + w.aT[buf];
-        a.sync = reinterpret_cast<unsigned*>(ws + w.sync);
-        a.base = chain_base;
-        a.launch = chain_launches;
-        a.s_hi = s_hi;
-        a.count = n;
-        a.src = srcs;
-        const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
-        Sample smp{MEBPTT_K_SWEEP, nullptr, nullptr, n};
-        if (bracket) {
-          smp.start = g_prof.get();
-          smp.stop = g_prof.get();
-          if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
-          HIP_TRY(hipEventRecord(smp.start, st));
-        }
-        HIP_TRY(launch_sweep(d, a, st));
-        if (bracket) {
-          HIP_TRY(hipEventRecord(smp.stop, st));
-          g_prof.runs.push_back(smp);
-        }
-        if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_SWEEP];
-        chain_base += forward_chain_arrivals(n);
-        ++chain_launches;
-        fwd += n;
-        bwd += n;
-        if ((s_hi - n) % CH == 0) {   // the launch reached the first step of the chunk
-          rc = complete_chunk(chunk);
-          if (rc) return rc;
-        }
+        rc = issue_sweep(s_hi, n, srcs, nullptr);
+        if (rc) return rc;
         oi += 2 * (size_t)n;
         continue;
       }

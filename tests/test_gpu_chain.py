@@ -87,6 +87,17 @@ def test_chain_launch_count_and_status():
     assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.sweep_steps
             == out.stats.forward_ops)
     assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == w.t
+    # store-everything BPTT (an internal-state slot per step): the forward pass as chains, the backward pass
+    # through the stored states as backward-only sweep launches
+    s2 = Session(w, inp, kind=wl.KIND_ISM, m=w.t)
+    mb.mebptt_profile_enable(1)
+    out2 = s2.run_and_fetch()
+    prof2 = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    assert out2.stats.forward_ops == w.t and prof2.chain_steps >= w.t - 2
+    assert prof2.sweep_steps >= w.t - 40 and prof2.launches[mb.K_BACKWARD] + prof2.sweep_steps == w.t
+    for f in FIELDS:
+        assert np.array_equal(getattr(out2, f), getattr(out, f)), f
 
 
 def test_chains_from_two_host_threads():
