@@ -273,6 +273,12 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
             ch["us_per_forward_op"] = prof.chain_ms / prof.chain_steps * 1e3
             log(f"[bench]   forward chain: {ch['steps_per_step']:.0f} forward ops/step in {ch['launches_per_step']:.0f} launches, "
                 f"{ch['us_per_forward_op']:.2f} us per forward op")
+        if prof.sweep_steps:
+            sw = classes["sweep"]
+            sw["steps_per_step"] = prof.sweep_steps / prof_steps
+            sw["us_per_step"] = prof.sweep_ms / prof.sweep_steps * 1e3
+            log(f"[bench]   sweep: {sw['steps_per_step']:.0f} backward steps/step in {sw['launches_per_step']:.0f} launches, "
+                f"{sw['us_per_step']:.2f} us per step")
         # The dominant kernel = the class with the largest share of the step; its roofline block.
         share = {}
         for name in ("forward", "backward", "backward+forward"):
@@ -281,12 +287,23 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
                 share[name] = c["net_us"] * c["launches_per_step"]
         if prof.chain_steps:
             share["forward chain"] = prof.chain_ms / prof_steps * 1e3
+        if prof.sweep_steps:
+            share["sweep"] = prof.sweep_ms / prof_steps * 1e3
         out["time_share_us"] = share
         if share:
             dom = max(share, key=share.get)
             kernel = {"forward": "forward_kernel", "backward": "backward_kernel", "backward+forward": "pair_kernel",
-                      "forward chain": "forward_chain_kernel"}[dom]
-            if dom == "forward chain":
+                      "forward chain": "forward_chain_kernel", "sweep": "sweep_kernel"}[dom]
+            if dom == "sweep":
+                # both weight operands stay on the chip; a step carries the dh GEMM and, where the
+                # internal state is recomputed (hidden-state slots), the forward GEMM as well
+                us = classes[dom]["us_per_step"]
+                fl = F_dh + (F_fwd if sess.kind == wl.KIND_HSM else 0.0)
+                tf = fl / (us * 1e-6) / 1e12
+                out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
+                                   "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
+                                   "flops_per_launch": fl, "note": "per backward step inside a sweep launch"}
+            elif dom == "forward chain":
                 # weights stay on the chip: what bounds a step is the matrix pipe and the exchange of h,
                 # so the launch is placed on the MFMA roof
                 us = classes[dom]["us_per_forward_op"]
@@ -350,6 +367,42 @@ def fig2b_rows(steps, warmup, lengths=(100, 400, 1000)):
     return rows
 
 
+def floors(args) -> int:
+    """The fixed costs the per-step times sit on, each measured alone on an otherwise idle device:
+    a dependent empty launch, one synchronisation of a resident launch's workgroups (device-wide,
+    per XCD, per XCD with the operand exchange), and the two time-batched GEMMs of one chunk for
+    every named configuration."""
+    import torch
+    from paper_1606_03401_amd import binding as mb
+    from paper_1606_03401_amd import workloads as wl
+    out = {"experiment": "floors", "null_launch_us": mb.mebptt_null_launch_us(4000), "sync": [], "gemms_alone": []}
+    log(f"[floors] dependent empty launch: {out['null_launch_us']:.2f} us")
+    names = ("all 256 workgroups, one device-wide counter", "32 workgroups per XCD, per-XCD counter",
+             "per-XCD counter + 16 KiB exchange through the L2")
+    for v, name in enumerate(names):
+        mb.mebptt_measure_sync(v, 200)   # warm-up
+        us, status = mb.mebptt_measure_sync(v, 3000)
+        out["sync"].append({"variant": v, "what": name, "us_per_sync": us, "status": status})
+        log(f"[floors] sync variant {v} ({name}): {us:.2f} us, status {status}")
+    for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+        w = wl.CONFIGS[name]
+        desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype, w.loss, w.dy_first_step)
+        ws = torch.zeros(mb.mebptt_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+        wu, du = mb.mebptt_measure_gemms(desc, ws, 30)
+        ch = mb.mebptt_chunk_steps(desc)
+        fw, fd = ch * forward_flops(w), ch * 2.0 * gate_blocks(w) * w.B * w.H * w.I
+        peak = MFMA_PEAK_TFLOPS[w.gemm_dtype]
+        row = {"name": name, "chunk_steps": ch, "wgrad_us": wu, "wgrad_tflops": fw / wu / 1e6, "wgrad_frac_mfma_peak": fw / wu / 1e6 / peak,
+               "dgrad_us": du, "dgrad_tflops": fd / du / 1e6, "dgrad_frac_mfma_peak": fd / du / 1e6 / peak}
+        out["gemms_alone"].append(row)
+        log(f"[floors] {name}: chunk of {ch} steps: dW GEMM {wu:.1f} us = {row['wgrad_tflops']:.0f} TFLOP/s "
+            f"({100 * row['wgrad_frac_mfma_peak']:.1f}% of MFMA peak); dx GEMM {du:.1f} us = {row['dgrad_tflops']:.0f} TFLOP/s "
+            f"({100 * row['dgrad_frac_mfma_peak']:.1f}%)")
+        del ws
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -364,6 +417,8 @@ def main() -> int:
                     help="only the shape of the paper's timing experiment: LSTM 256->256, batch 64, us per time step "
                          "vs sequence length at budgets of 10/50/100/500/1000 hidden states")
     ap.add_argument("--cell", choices=("lstm", "gru"), default="lstm", help="RNN core run on the workload's shape")
+    ap.add_argument("--floors", action="store_true",
+                    help="only the fixed costs: empty launch, workgroup synchronisation variants, the chunk GEMMs alone")
     ap.add_argument("--chen", action="store_true",
                     help="Chen et al.'s sqrt(t) / recursive strategies as policies through the same executor, beside "
                          "BPTT-MSM at the same memory, and the paper's numerical comparison (table on stderr)")
@@ -383,6 +438,8 @@ def main() -> int:
         print(json.dumps({"experiment": "fig2b", "rows": fig2b_rows(args.steps, args.warmup, (100, 200, 400, 600, 800, 1000))}),
               flush=True)
         return 0
+    if args.floors:
+        return floors(args)
     if args.chen:
         return chen_comparison(args)
     w = wl.CONFIGS[args.workload]

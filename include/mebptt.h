@@ -435,6 +435,19 @@ int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us);
  * Synchronises the stream.  Errors: EINVAL, EWORKSPACE, EHIP. */
 int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
                          void* stream, double* wgrad_us, double* dgrad_us);
+/* Time steps per chunk of the time-batched GEMMs for this shape (the K extent of the dW GEMM is
+ * this many times B), or a negative error code. */
+int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc);
+
+/* What one synchronisation of the 256 workgroups of a resident launch costs, alone: `iters`
+ * synchronisations inside one kernel on `stream`, microseconds per synchronisation (host memory).
+ * variant 0: all workgroups meet at one device-wide counter; 1: the 32 workgroups of each XCD meet
+ * at their XCD's counter (what forward chains and sweeps do per time step); 2: as 1, plus an
+ * exchange of 512 bytes per workgroup that the 32 of the XCD then read through the L2, every word
+ * checked.  *status (host memory): 0 ok, 1 a bounded wait gave up, 2 the workgroups were not placed
+ * 32 per XCD, 3 a word read back differed.  Allocates and frees its own small device buffers;
+ * synchronises the stream.  Errors: EINVAL, EHIP. */
+int mebptt_measure_sync(int32_t variant, int32_t iters, void* stream, double* us_per_sync, int32_t* status);
 
 const char* mebptt_last_error(void);
 /* Library version string, e.g. "mebptt 0.1 (gfx950)". */

@@ -131,6 +131,8 @@ SIGNATURES = {
     "mebptt_forward_chain_enable": (C.c_int, [C.c_int32]),
     "mebptt_shutdown": (C.c_int, []),
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
+    "mebptt_measure_sync": (C.c_int, [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
+    "mebptt_chunk_steps": (C.c_int32, [_DESC]),
     "mebptt_measure_gemms": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
     "mebptt_profile_collect": (C.c_int, [C.POINTER(mebptt_profile)]),
@@ -417,6 +419,13 @@ def mebptt_null_launch_us(launches: int = 2000, stream: Optional[int] = None) ->
     return out.value
 
 
+def mebptt_measure_sync(variant: int, iters: int = 3000, stream: Optional[int] = None):
+    """(microseconds per synchronisation, status) of the stand-alone synchronisation kernel."""
+    out, status = C.c_double(0.0), C.c_int32(0)
+    _check(lib().mebptt_measure_sync(variant, iters, _stream(stream), C.byref(out), C.byref(status)))
+    return out.value, status.value
+
+
 def make_chain_desc(widths, B: int, unit_bytes: int) -> mebptt_chain_desc:
     """Descriptor of a chain of dense tanh layers; keeps the widths array alive on the object."""
     arr = (C.c_int32 * len(widths))(*[int(v) for v in widths])
@@ -448,6 +457,13 @@ def mebptt_chain_run(desc: mebptt_chain_desc, plan: ChainPlan, W, b, x0, dy, poo
                                 arr(db), _ptr(dx0), _ptr(y_out), C.byref(stats), _stream(stream))
     _check(rc)
     return stats
+
+
+def mebptt_chunk_steps(desc: mebptt_lstm_desc) -> int:
+    n = lib().mebptt_chunk_steps(C.byref(desc))
+    if n < 0:
+        _check(n)
+    return n
 
 
 def mebptt_measure_gemms(desc: mebptt_lstm_desc, workspace, reps: int = 20, stream: Optional[int] = None):

@@ -13,7 +13,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmebptt.so")
-SOURCES = ["planner.cpp", "chain_planner.cpp", "kernels.hip", "run.hip", "chain_run.hip"]
+SOURCES = ["planner.cpp", "chain_planner.cpp", "kernels.hip", "run.hip", "chain_run.hip", "measure_sync.hip"]
 
 
 def hipcc() -> str:

@@ -1032,7 +1032,9 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
   float* red = reinterpret_cast<float*>(smem);                               // [KS][NT][4][64]
   T* wl = reinterpret_cast<T*>(smem + (size_t)KS * NT * 4 * 64 * sizeof(float));   // [KS][NRT][NSL] fragments
   __shared__ int s_go, s_g, s_rank;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the wave index as a scalar: conditions on it become scalar branches (an MFMA under a lane mask
+  // that is empty would still execute)
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
   if (threadIdx.x == 0) {
     const unsigned xcc = xcc_id();
@@ -1131,6 +1133,27 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
 #pragma unroll
         for (int bt = 0; bt < NBT; ++bt) bf[i][bt] = M::from_f32(xraw[i][bt].v);
       }
+    f32x4 acc[NRT][NBT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto weight = [&](int rt, int i) -> typename M::Frag {
+      return (i < NSR) ? wr[rt][i < NSR ? i : 0]
+                       : M::load(&wl[((size_t)(wave * NRT + rt) * NSL + (i - NSR)) * FRAG + lane * VEC]);
+    };
+    // the x part of the sum needs nothing from the other workgroups (a wave's x macro steps precede
+    // its h macro steps, so the order of the additions is that of forward_body)
+#pragma unroll
+    for (int i = 0; i < NSXW; ++i)
+      if (wave + KS * i < nsx) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          const typename M::Frag a = weight(rt, i);
+#pragma unroll
+          for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = M::mma(a, bf[i][bt], acc[rt][bt]);
+        }
+      }
     if (j > 0) {
       // all 32 workgroups of this XCD have published h of the previous step?
       if (threadIdx.x == 0) {
@@ -1176,20 +1199,15 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
       }
     }
     __builtin_amdgcn_sched_barrier(0);   // every fetch is issued before the first MFMA
-    f32x4 acc[NRT][NBT];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-      for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < NSW; ++i)
+      if (!(i < NSXW && wave + KS * i < nsx)) {
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) {
-        const typename M::Frag a =
-            (i < NSR) ? wr[rt][i < NSR ? i : 0]
-                      : M::load(&wl[((size_t)(wave * NRT + rt) * NSL + (i - NSR)) * FRAG + lane * VEC]);
+        for (int rt = 0; rt < NRT; ++rt) {
+          const typename M::Frag a = weight(rt, i);
 #pragma unroll
-        for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = M::mma(a, bf[i][bt], acc[rt][bt]);
+          for (int bt = 0; bt < NBT; ++bt) acc[rt][bt] = M::mma(a, bf[i][bt], acc[rt][bt]);
+        }
       }
     if (j + 1 < p.count) fetch_x(j + 1);   // in flight while this step finishes and the next wait runs
 #pragma unroll
@@ -1389,7 +1407,9 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
   float* redF = reinterpret_cast<float*>(smem);                       // [KSF][NTF][4][64]
   float* redB = redF + (size_t)KSF * NTF * 4 * 64;                    // [KSB][NTBT][4][64]
   __shared__ int s_go, s_g, s_rank;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the wave index as a scalar: conditions on it become scalar branches (an MFMA under a lane mask
+  // that is empty would still execute)
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
   if (threadIdx.x == 0) {
     const unsigned xcc = xcc_id();

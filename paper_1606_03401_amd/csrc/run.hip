@@ -48,7 +48,7 @@ Workspace layout(const Dims& d) {
   w.state = take(9 * unit);   // T0 | T1 | core A (3 units) | copy of (h0,c0) | core B (3 units)
   w.dWacc = take(wgrad_accumulator_bytes(d));
   w.dc = take((size_t)d.B * d.H * sizeof(float));
-  w.sync = take(forward_chain_sync_bytes());   // counters and status word of the forward-chain launches: cleared with dc
+  w.sync = take(forward_chain_sync_bytes());   // counters and status word of the resident launches: cleared with dc
   for (int i = 0; i < 2; ++i) w.dG[i] = take((size_t)d.CH * d.BP * d.G4 * op);
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
   for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)d.NA * d.KC * op);
@@ -449,6 +449,12 @@ int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us) {
   if (e != hipSuccess) return set_error(MEBPTT_EHIP, "null-launch timing failed: %s", hipGetErrorString(e));
   *out_us = (double)ms * 1e3 / launches;
   return MEBPTT_OK;
+}
+
+int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  return make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell).CH;
 }
 
 int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
