@@ -192,7 +192,7 @@ def memory_report(w, sess):
 
 
 def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile=True, store_all=True,
-            launch_floor_us=None, bracket_us=None):
+            launch_floor_us=None, bracket_us=None, bracket_curve=None):
     """Times one configuration: ms per gradient step (stream launches and HIP-graph replay, the
     faster is reported), per kernel class the event-sampled time per launch and its MFMA fraction,
     the forward kernel's roofline position, the store-everything run for the cost ratio."""
@@ -231,6 +231,19 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
         prof = mb.mebptt_profile_collect()
         mb.mebptt_profile_enable(0)
         overhead_us = max(0.0, (bracket_us or 0.0) - (launch_floor_us or 0.0))
+
+        def net_of(avg):
+            """Event-bracketed time of a single launch -> that launch's own time, through the
+            calibration curve (idle kernels of known length, bracketed and back to back)."""
+            if not bracket_curve:
+                return max(avg - overhead_us, 1e-3)
+            pts = sorted(bracket_curve, key=lambda pb: pb[1])
+            if avg <= pts[0][1]:
+                return max(pts[0][0] - (pts[0][1] - avg), 1e-3)
+            for (p0, b0), (p1, b1) in zip(pts, pts[1:]):
+                if avg <= b1:
+                    return p0 + (p1 - p0) * (avg - b0) / max(b1 - b0, 1e-9)
+            return avg - (pts[-1][1] - pts[-1][0])
         # flops of one launch of each class: forward op 8BH(I+H); backward step (dh GEMM) 8BH^2; the
         # time-batched GEMMs carry t steps over their launches: dW 8BH(I+H), dx 8BHI per step.
         # The sequential GEMMs stream their weights once per launch: B flop per weight byte (bf16
@@ -242,12 +255,16 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
         seq_cap_tf = min(peak_tf, 2.0 * w.B / opb * HBM_PEAK_GBS / 1e3)
         classes = {}
         for k, name in enumerate(mb.K_NAMES):
-            n_s = prof.sampled[k]
+            n_s, n_g = prof.sampled[k], prof.sampled_groups[k]
             lps = prof.launches[k] / prof_steps
             avg_us = prof.sampled_ms[k] / n_s * 1e3 if n_s else None
             classes[name] = {"launches_per_step": lps, "avg_us": avg_us}
             if avg_us is not None and lps > 0:
-                net_us = max(avg_us - overhead_us, 1e-3)
+                # a bracket holds n_s / n_g launches on average: its own time through the calibration
+                # curve, then per launch (for the sequential classes this includes the gap between
+                # dependent launches, as the chain pays it)
+                per_group = n_s / max(n_g, 1)
+                net_us = net_of(avg_us * per_group) / per_group
                 flops = {"forward": F_fwd, "backward": F_dh, "backward+forward": F_dh + F_fwd,
                          "wgrad": w.t * F_fwd / lps, "dgrad": w.t * F_dx / lps,
                          "forward chain": F_fwd * prof.chain_steps / max(prof.launches[k], 1)}.get(name)
@@ -257,7 +274,7 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
                     cap = peak_tf if name in ("wgrad", "dgrad") else seq_cap_tf
                     classes[name].update({"gflop_per_launch": flops / 1e9, "tflops": tf, "frac_mfma_peak": tf / peak_tf,
                                           "attainable_tflops": cap, "frac_of_attainable": tf / cap})
-            log(f"[bench]   {name}: {lps:.0f} launches/step, avg {avg_us if avg_us is None else round(avg_us, 2)} us ({n_s} samples)"
+            log(f"[bench]   {name}: {lps:.0f} launches/step, avg {avg_us if avg_us is None else round(avg_us, 2)} us ({n_s} launches in {n_g} brackets)"
                 + (f", net {classes[name]['net_us']:.2f} us, {classes[name]['tflops']:.0f} TFLOP/s = "
                    f"{100 * classes[name]['frac_mfma_peak']:.1f}% of MFMA peak, {100 * classes[name]['frac_of_attainable']:.0f}% of attainable"
                    if "tflops" in classes[name] else ""))
@@ -465,12 +482,17 @@ def main() -> int:
         b.record()
     torch.cuda.synchronize()
     bracket_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 10]
+    # What a bracket adds depends on how long the kernel inside it runs: idle kernels of known
+    # length, timed back to back and each inside its own bracket, give the curve that turns an
+    # event-sampled single-launch time into the launch's own time.
+    bracket_curve = [mb.mebptt_bracket_overhead_us(L, 200) for L in (0, 2, 4, 8, 16, 32, 64, 128, 256, 512)]
     log(f"[bench] back-to-back empty launches: {launch_floor_us:.2f} us each; event bracket around a minimal launch: "
-        f"{bracket_us:.2f} us -> {max(0.0, bracket_us - launch_floor_us):.2f} us subtracted from single-launch samples")
+        f"{bracket_us:.2f} us; bracket curve (own time -> bracketed): "
+        + ", ".join(f"{a:.1f}->{b:.1f}" for a, b in bracket_curve))
 
     inp = wl.make_inputs(w)
     head = measure(w, inp, steps=args.steps, warmup=args.warmup, graph=not args.no_graph,
-                   launch_floor_us=launch_floor_us, bracket_us=bracket_us)
+                   launch_floor_us=launch_floor_us, bracket_us=bracket_us, bracket_curve=bracket_curve)
     if args.sweep:
         from paper_1606_03401_amd.session import Session
         sa_ms = head["cost_ratio_vs_store_all"]["store_all_ms"]
@@ -528,7 +550,7 @@ def main() -> int:
                 few = 2 if (name == "cfg5" and m < 31) else 3
                 row = measure(wc, inp_c, m=m, steps=few, warmup=1, graph=(name != "cfg4" and not args.no_graph),
                               profile=(m == wc.m), store_all=(i == 0),
-                              launch_floor_us=launch_floor_us, bracket_us=bracket_us)
+                              launch_floor_us=launch_floor_us, bracket_us=bracket_us, bracket_curve=bracket_curve)
                 if i > 0:   # one store-everything run serves the whole sweep
                     sa_ms = configs[-i]["cost_ratio_vs_store_all"]["store_all_ms"]
                     row["cost_ratio_vs_store_all"].update({"store_all_ms": sa_ms,

@@ -401,8 +401,9 @@ enum {
 };
 typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
-  int64_t sampled[MEBPTT_K_CLASSES];  /* launches that were bracketed by an event pair   */
-  double sampled_ms[MEBPTT_K_CLASSES]; /* sum of the bracketed launches' elapsed times    */
+  int64_t sampled[MEBPTT_K_CLASSES];  /* launches inside event brackets (consecutive launches of a
+                                         sequential class share one bracket, up to eight)  */
+  double sampled_ms[MEBPTT_K_CLASSES]; /* sum of the brackets' elapsed times              */
   /* Forward runs of nine or more consecutive operations are also bracketed as a whole (all but
    * their first launch): one event pair around many back-to-back launches, so the cost of the
    * events themselves disappears from the per-launch average. */
@@ -414,6 +415,7 @@ typedef struct {
   /* Likewise the sweep launches: (forward, backward) pairs they carried, and their time. */
   int64_t sweep_steps;
   double sweep_ms;
+  int64_t sampled_groups[MEBPTT_K_CLASSES]; /* event brackets behind `sampled` and `sampled_ms` */
 } mebptt_profile;
 /* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
  * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;
@@ -448,6 +450,13 @@ int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc);
  * 32 per XCD, 3 a word read back differed.  Allocates and frees its own small device buffers;
  * synchronises the stream.  Errors: EINVAL, EHIP. */
 int mebptt_measure_sync(int32_t variant, int32_t iters, void* stream, double* us_per_sync, int32_t* status);
+
+/* What an event pair around a single launch adds to that launch's time, for a kernel lasting about
+ * kernel_us (0..1000): `reps` (1..2000) launches of a kernel that idles that long, back to back
+ * inside one event pair -> *per_launch_us; the same launches each inside its own event pair ->
+ * *bracketed_us (mean).  Event-sampled per-launch times carry the difference.  Host memory outputs;
+ * synchronises the stream.  Errors: EINVAL, EHIP. */
+int mebptt_bracket_overhead_us(double kernel_us, int32_t reps, void* stream, double* per_launch_us, double* bracketed_us);
 
 const char* mebptt_last_error(void);
 /* Library version string, e.g. "mebptt 0.1 (gfx950)". */

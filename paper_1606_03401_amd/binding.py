@@ -81,7 +81,7 @@ class mebptt_profile(C.Structure):
     _fields_ = [("launches", C.c_int64 * K_CLASSES), ("sampled", C.c_int64 * K_CLASSES),
                 ("sampled_ms", C.c_double * K_CLASSES), ("forward_run_launches", C.c_int64),
                 ("forward_run_ms", C.c_double), ("chain_steps", C.c_int64), ("chain_ms", C.c_double),
-                ("sweep_steps", C.c_int64), ("sweep_ms", C.c_double)]
+                ("sweep_steps", C.c_int64), ("sweep_ms", C.c_double), ("sampled_groups", C.c_int64 * K_CLASSES)]
 
 
 # name -> (restype, argtypes): every symbol the header declares
@@ -133,6 +133,7 @@ SIGNATURES = {
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_measure_sync": (C.c_int, [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "mebptt_chunk_steps": (C.c_int32, [_DESC]),
+    "mebptt_bracket_overhead_us": (C.c_int, [C.c_double, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_measure_gemms": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
     "mebptt_profile_collect": (C.c_int, [C.POINTER(mebptt_profile)]),
@@ -424,6 +425,13 @@ def mebptt_measure_sync(variant: int, iters: int = 3000, stream: Optional[int] =
     out, status = C.c_double(0.0), C.c_int32(0)
     _check(lib().mebptt_measure_sync(variant, iters, _stream(stream), C.byref(out), C.byref(status)))
     return out.value, status.value
+
+
+def mebptt_bracket_overhead_us(kernel_us: float, reps: int = 200, stream: Optional[int] = None):
+    """(time per launch back to back, mean time of the same launch inside its own event pair), in us."""
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().mebptt_bracket_overhead_us(float(kernel_us), reps, _stream(stream), C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def make_chain_desc(widths, B: int, unit_bytes: int) -> mebptt_chain_desc:

@@ -126,6 +126,13 @@ __global__ __launch_bounds__(256) void sync_kernel(SyncParams p) {
   if (bad) atomicAdd(p.flag + 1, bad);
 }
 
+// A kernel of 256 workgroups that does nothing for `ticks` ticks of the 100 MHz wall clock.
+__global__ __launch_bounds__(256) void wait_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < ticks) {
+  }
+}
+
 struct Buffers {
   unsigned* base = nullptr;
   ~Buffers() {
@@ -173,5 +180,51 @@ extern "C" int mebptt_measure_sync(int32_t variant, int32_t iters, void* stream,
   if (e != hipSuccess) return MEBPTT_EHIP;
   *us_per_sync = (double)ms * 1e3 / iters;
   *status = flags[2] ? 2 : flags[0] ? 1 : flags[1] ? 3 : 0;   // 2 placement, 1 a wait gave up, 3 wrong words read
+  return MEBPTT_OK;
+}
+
+// What a pair of events around a single launch adds to the launch's own time, for a kernel that
+// lasts about `kernel_us`: `reps` such launches back to back inside one event pair give the time
+// per launch, the same launches each inside its own event pair give the bracketed time; the
+// difference is what event-sampled per-launch times carry on top (it depends on the kernel's
+// length: part of the event processing hides behind a kernel that runs for a while).
+extern "C" int mebptt_bracket_overhead_us(double kernel_us, int32_t reps, void* stream, double* per_launch_us,
+                                          double* bracketed_us) {
+  if (!(kernel_us >= 0.0) || kernel_us > 1000.0 || reps < 1 || reps > 2000 || !per_launch_us || !bracketed_us) return MEBPTT_EINVAL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const long long ticks = (long long)(kernel_us * 100.0);
+  const int n = reps;
+  hipEvent_t* ev = new hipEvent_t[2 * n + 2]();
+  hipError_t e = hipSuccess;
+  for (int i = 0; i < 2 * n + 2 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+  if (e == hipSuccess) {
+    for (int i = 0; i < 8; ++i) wait_kernel<<<dim3(256), dim3(256), 0, st>>>(ticks);   // warm-up
+    e = hipEventRecord(ev[2 * n], st);
+  }
+  if (e == hipSuccess) {
+    for (int i = 0; i < n; ++i) wait_kernel<<<dim3(256), dim3(256), 0, st>>>(ticks);
+    e = hipEventRecord(ev[2 * n + 1], st);
+  }
+  for (int i = 0; i < n && e == hipSuccess; ++i) {
+    e = hipEventRecord(ev[2 * i], st);
+    wait_kernel<<<dim3(256), dim3(256), 0, st>>>(ticks);
+    if (e == hipSuccess) e = hipEventRecord(ev[2 * i + 1], st);
+  }
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  float ms = 0.0f;
+  double sum = 0.0;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[2 * n], ev[2 * n + 1]);
+  const double plain = (double)ms * 1e3 / n;
+  for (int i = 0; i < n && e == hipSuccess; ++i) {
+    e = hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
+    sum += (double)ms * 1e3;
+  }
+  for (int i = 0; i < 2 * n + 2; ++i)
+    if (ev[i]) (void)hipEventDestroy(ev[i]);
+  delete[] ev;
+  if (e != hipSuccess) return MEBPTT_EHIP;
+  *per_launch_us = plain;
+  *bracketed_us = sum / n;
   return MEBPTT_OK;
 }

@@ -84,6 +84,14 @@ struct Sample {
 struct Profiler {
   int every_n = 0;
   bool in_run = false;   // inside a bracketed forward run: no per-launch brackets
+  // A bracket that is still open: launches of one class on one stream share an event pair, up to
+  // group_size(cls) of them, so that what the events themselves cost is spread over the group.
+  struct Open {
+    int cls = -1;
+    hipStream_t st = nullptr;
+    hipEvent_t start = nullptr;
+    int64_t n = 0;
+  } open;
   int64_t launches[MEBPTT_K_CLASSES] = {};
   std::vector<Sample> pending;
   std::vector<Sample> runs;   // whole forward runs, one event pair around many launches
@@ -101,21 +109,57 @@ struct Profiler {
 };
 Profiler g_prof;
 
-// Brackets one launch with events when it falls on the sampling grid.
+// Launches of the sequential chain are bracketed in groups of up to eight consecutive launches of
+// one class (an event pair around a single short launch adds microseconds to it); the batched GEMMs
+// and the set-up kernels, which are long and not consecutive, one by one.
+inline int group_size(int cls) {
+  return (cls == MEBPTT_K_FORWARD || cls == MEBPTT_K_BACKWARD || cls == MEBPTT_K_PAIR) ? 8 : 1;
+}
+
+// Ends the open bracket, if any: its stop event goes onto its stream now.  Called before anything
+// that is not a launch of the open class is put on that stream.
+hipError_t close_group() {
+  Profiler& p = g_prof;
+  if (p.open.cls < 0) return hipSuccess;
+  Sample s{p.open.cls, p.open.start, p.get(), p.open.n};
+  p.open.cls = -1;
+  if (!s.stop) {
+    p.pool.push_back(s.start);
+    return hipErrorOutOfMemory;
+  }
+  hipError_t e = hipEventRecord(s.stop, p.open.st);
+  p.pending.push_back(s);
+  return e;
+}
+
+// Brackets a group of launches with events when its first launch falls on the sampling grid.
 template <class F>
 hipError_t timed(int cls, hipStream_t st, F&& launch) {
   Profiler& p = g_prof;
   if (p.every_n <= 0) return launch();
-  const bool sample = (p.launches[cls]++ % p.every_n) == 0 && p.pending.size() < 200000 && !p.in_run;
-  if (!sample) return launch();
-  Sample s{cls, p.get(), p.get(), 1};
-  if (!s.start || !s.stop) return hipErrorOutOfMemory;
-  hipError_t e = hipEventRecord(s.start, st);
+  if (p.open.cls >= 0 && (p.open.cls != cls || p.open.st != st || p.in_run)) {
+    hipError_t e = close_group();
+    if (e != hipSuccess) return e;
+  }
+  const int64_t index = p.launches[cls]++;
+  if (p.open.cls < 0) {
+    const bool sample = (index % p.every_n) == 0 && p.pending.size() < 200000 && !p.in_run;
+    if (!sample) return launch();
+    hipEvent_t start = p.get();
+    if (!start) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(start, st);
+    if (e != hipSuccess) {
+      p.pool.push_back(start);
+      return e;
+    }
+    p.open.cls = cls;
+    p.open.st = st;
+    p.open.start = start;
+    p.open.n = 0;
+  }
+  hipError_t e = launch();
   if (e != hipSuccess) return e;
-  e = launch();
-  if (e != hipSuccess) return e;
-  e = hipEventRecord(s.stop, st);
-  p.pending.push_back(s);
+  if (++p.open.n >= group_size(cls)) e = close_group();
   return e;
 }
 
@@ -248,6 +292,7 @@ int mebptt_profile_collect(mebptt_profile* out) {
   if (!out) return set_error(MEBPTT_EINVAL, "out is NULL");
   std::memset(out, 0, sizeof *out);
   Profiler& p = g_prof;
+  if (close_group() != hipSuccess) return set_error(MEBPTT_EHIP, "closing an event bracket failed");
   for (int c = 0; c < MEBPTT_K_CLASSES; ++c) {
     out->launches[c] = p.launches[c];
     p.launches[c] = 0;
@@ -280,7 +325,8 @@ int mebptt_profile_collect(mebptt_profile* out) {
     if (e != hipSuccess) {
       rc = set_error(MEBPTT_EHIP, "event timing failed: %s", hipGetErrorString(e));
     } else {
-      out->sampled[s.cls] += 1;
+      out->sampled[s.cls] += s.launches;
+      out->sampled_groups[s.cls] += 1;
       out->sampled_ms[s.cls] += ms;
     }
     p.pool.push_back(s.start);
@@ -599,6 +645,10 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   };
 
   std::lock_guard<std::mutex> lock(g_run_mutex);   // side stream, events, profiler and static scratch are shared
+  if (g_prof.open.cls >= 0) {   // a run that failed midway left its last bracket open: forget it
+    g_prof.pool.push_back(g_prof.open.start);
+    g_prof.open.cls = -1;
+  }
 
   // Set-up: operand copies of the weights, zeroed staging (the padding must stay zero), start state.
   if (mode != RUN_PREPARED) {
@@ -781,6 +831,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     a.src = srcs;
     a.state = states;
     const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+    if (use_profiler) HIP_TRY(close_group());
     Sample smp{MEBPTT_K_SWEEP, nullptr, nullptr, n};
     if (bracket) {
       smp.start = g_prof.get();
@@ -898,6 +949,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
           const float* x_first = x_of(fsteps[fi].step);
           // Measurement hook: every chain launch is bracketed (they are few), with its step count.
           const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+          if (use_profiler) HIP_TRY(close_group());
           Sample smp{MEBPTT_K_CHAIN, nullptr, nullptr, n};
           if (bracket) {
             smp.start = g_prof.get();
@@ -923,6 +975,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         const bool bracket = use_profiler && g_prof.every_n > 0 && total - fi >= 8 && g_prof.runs.size() < 100000;
         Sample run_sample{MEBPTT_K_FORWARD, nullptr, nullptr, (int64_t)(total - fi)};
         if (bracket) {
+          HIP_TRY(close_group());
           run_sample.start = g_prof.get();
           run_sample.stop = g_prof.get();
           if (!run_sample.start || !run_sample.stop) return set_error(MEBPTT_EHIP, "event creation failed");
@@ -993,6 +1046,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     return launch_wgrad_finish(d, reinterpret_cast<const float*>(ws + w.dWacc), dW_ih, dW_hh, db, st);
   }));
 
+  if (use_profiler) HIP_TRY(close_group());
   if (chain_used && chain_order_dev >= 0) {
     if (!g_chain_done[chain_order_dev])
       HIP_TRY(hipEventCreateWithFlags(&g_chain_done[chain_order_dev], hipEventDisableTiming));
