@@ -1863,21 +1863,24 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
 template <class T, int NT, int RT, int KS, int U>
 __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT, int N, const T* __restrict__ dG,
                                                         int nrow_tiles, int B, int BP, int G4,
-                                                        float* __restrict__ out, int ld_out, int rows_per_xcd) {
+                                                        float* __restrict__ out, int ld_out) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC, NTILE = NT * RT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
-  __shared__ float red[KS * NTILE * 4 * 64];
+  extern __shared__ __attribute__((aligned(16))) unsigned char dgrad_smem[];
+  float* red = reinterpret_cast<float*>(dgrad_smem);   // [KS][NTILE][4][64]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lrow = lane & 15, lq = lane >> 4;
-  // Workgroups are handed to the 8 XCDs round-robin by their linear id.  As launched, an XCD owns
-  // every 8th column group and sees all of dG.  With rows_per_xcd set, the id is re-mapped so
-  // that each XCD works through a contiguous range of (row group, column group) pairs, column
-  // group fastest: the workgroups that share a dG row group then share an L2 and every XCD
-  // fetches only its own eighth of dG -- the better choice when all of WT fits in one L2.
+  // Workgroups are handed to the 8 XCDs round-robin by their linear id.  As launched, an XCD would
+  // own every 8th column group and see all of dG.  The id is re-mapped so that each XCD works
+  // through a contiguous range of (row group, column group) pairs, column group fastest: the
+  // workgroups that share a dG row group then share an L2, every XCD fetches only its own eighth
+  // of dG, and the weight operand streams through each L2 once per round of resident workgroups
+  // (measured: 136 -> 34 MB fetched per chunk on the 256 -> 1024 shape, 569 -> about 200 MB on
+  // 512 -> 2048).
   const int gx = (int)gridDim.x, total = gx * (int)gridDim.y;
   const int id = (int)blockIdx.x + gx * (int)blockIdx.y;
   const int xcd = id & 7;
-  const int work = rows_per_xcd ? xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3) : id;
+  const int work = xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3);
   const int bx = work % gx, by = work / gx;
   const int ncol_tiles = (N + 15) / 16;
   const int nsteps = G4 / KSTEP;
@@ -1936,29 +1939,41 @@ __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT
   }
 }
 
-template <class T>
-static void launch_dgrad_t(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
-                           hipStream_t st) {
-  const int ncol_tiles = round_up(N, 16) / 16, nrow_tiles = nslots * d.BP / 16;
-  const int rows_per_xcd = (size_t)ncol_tiles * 16 * d.G4 * sizeof(T) <= ((size_t)4 << 20);   // WT fits one XCD's L2
-  if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 1) / 2) >= TARGET_WGS) {
-    dim3 grid((ncol_tiles + 1) / 2, (nrow_tiles + 1) / 2);
-    dgrad_kernel<T, 2, 2, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
-                                                            ld_out, rows_per_xcd);
-  } else {
-    dim3 grid(ncol_tiles, nrow_tiles);
-    dgrad_kernel<T, 1, 1, 8, 4><<<grid, dim3(512), 0, st>>>((const T*)WT, N, (const T*)dG, nrow_tiles, d.B, d.BP, d.G4, out,
-                                                            ld_out, rows_per_xcd);
+template <class T, int NT, int RT, int KS, int U>
+static hipError_t launch_dgrad_cfg(dim3 grid, const T* WT, int N, const T* dG, int nrow_tiles, const Dims& d, float* out,
+                                   int ld_out, hipStream_t st) {
+  const size_t lds = (size_t)KS * NT * RT * 4 * 64 * sizeof(float);
+  static bool configured = false;   // per instantiation; needed above 64 KiB only, harmless below
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dgrad_kernel<T, NT, RT, KS, U>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
   }
+  dgrad_kernel<T, NT, RT, KS, U><<<grid, dim3(64 * KS), lds, st>>>(WT, N, dG, nrow_tiles, d.B, d.BP, d.G4, out, ld_out);
+  return hipGetLastError();
+}
+
+template <class T>
+static hipError_t launch_dgrad_t(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
+                                 hipStream_t st) {
+  const int ncol_tiles = round_up(N, 16) / 16, nrow_tiles = nslots * d.BP / 16;
+  // The largest output block per workgroup that still gives every compute unit one: each operand
+  // byte a workgroup fetches is used for 64, 32 or 16 outputs.
+  if (((ncol_tiles + 3) / 4) * ((nrow_tiles + 3) / 4) >= TARGET_WGS)
+    return launch_dgrad_cfg<T, 4, 4, 8, 4>(dim3((ncol_tiles + 3) / 4, (nrow_tiles + 3) / 4), (const T*)WT, N, (const T*)dG,
+                                           nrow_tiles, d, out, ld_out, st);
+  if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 1) / 2) >= TARGET_WGS)
+    return launch_dgrad_cfg<T, 2, 2, 8, 4>(dim3((ncol_tiles + 1) / 2, (nrow_tiles + 1) / 2), (const T*)WT, N, (const T*)dG,
+                                           nrow_tiles, d, out, ld_out, st);
+  return launch_dgrad_cfg<T, 1, 1, 8, 4>(dim3(ncol_tiles, nrow_tiles), (const T*)WT, N, (const T*)dG, nrow_tiles, d, out, ld_out,
+                                         st);
 }
 
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out, int ld_out,
                              hipStream_t st) {
-  if (d.dtype)
-    launch_dgrad_t<__bf16>(d, WT, N, dG, nslots, out, ld_out, st);
-  else
-    launch_dgrad_t<float>(d, WT, N, dG, nslots, out, ld_out, st);
-  return hipGetLastError();
+  return d.dtype ? launch_dgrad_t<__bf16>(d, WT, N, dG, nslots, out, ld_out, st)
+                 : launch_dgrad_t<float>(d, WT, N, dG, nslots, out, ld_out, st);
 }
 
 // ---- time-batched GEMM on 256 x 256 workgroup tiles --------------------------------------------
