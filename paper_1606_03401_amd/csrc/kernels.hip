@@ -1963,6 +1963,9 @@ static hipError_t launch_dgrad_t(const Dims& d, const void* WT, int N, const voi
   if (((ncol_tiles + 3) / 4) * ((nrow_tiles + 3) / 4) >= TARGET_WGS)
     return launch_dgrad_cfg<T, 4, 4, 8, 4>(dim3((ncol_tiles + 3) / 4, (nrow_tiles + 3) / 4), (const T*)WT, N, (const T*)dG,
                                            nrow_tiles, d, out, ld_out, st);
+  if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 3) / 4) >= TARGET_WGS)
+    return launch_dgrad_cfg<T, 2, 4, 8, 4>(dim3((ncol_tiles + 1) / 2, (nrow_tiles + 3) / 4), (const T*)WT, N, (const T*)dG,
+                                           nrow_tiles, d, out, ld_out, st);
   if (((ncol_tiles + 1) / 2) * ((nrow_tiles + 1) / 2) >= TARGET_WGS)
     return launch_dgrad_cfg<T, 2, 2, 8, 4>(dim3((ncol_tiles + 1) / 2, (nrow_tiles + 1) / 2), (const T*)WT, N, (const T*)dG,
                                            nrow_tiles, d, out, ld_out, st);
@@ -2062,24 +2065,25 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
     for (int ks = 0; ks < 2; ++ks) {
       if (r * 2 + ks < p.nk) {   // uniform
         const T* base = &lds[((size_t)stage * 32 + ks * 16) * FRAG + lane * VEC];
-        // A fragments two at a time, the next pair requested before the current pair's eight
-        // MFMAs are issued, so that the LDS latency of a pair hides behind the pair before it
-        typename M::Frag a_cur[2], a_nxt[2];
-        a_cur[0] = M::load(base + (size_t)(wi * TI) * FRAG);
-        a_cur[1] = M::load(base + (size_t)(wi * TI + 1) * FRAG);
+        // The wave's TI fragments of A come from LDS two ahead of the MFMAs that use them: two
+        // reads, then TJ MFMAs and one more read in turn, so an LDS round trip always has eight
+        // MFMAs to hide behind.  (Left to itself the scheduler puts every read right before its
+        // MFMAs and waits for it.)  The group barriers fix that order for the instructions of
+        // this block: 0x100 = LDS read, 0x008 = MFMA.
+        typename M::Frag a[TI];
 #pragma unroll
-        for (int ip = 0; ip < TI / 2; ++ip) {
-          if (ip + 1 < TI / 2) {
-            a_nxt[0] = M::load(base + (size_t)(wi * TI + 2 * ip + 2) * FRAG);
-            a_nxt[1] = M::load(base + (size_t)(wi * TI + 2 * ip + 3) * FRAG);
-          }
+        for (int i = 0; i < TI; ++i) a[i] = M::load(base + (size_t)(wi * TI + i) * FRAG);
 #pragma unroll
-          for (int h = 0; h < 2; ++h)
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
-            for (int j = 0; j < TJ; ++j) acc[2 * ip + h][j] = M::mma(a_cur[h], ringB[set][ks][j], acc[2 * ip + h][j]);
-          a_cur[0] = a_nxt[0];
-          a_cur[1] = a_nxt[1];
+          for (int j = 0; j < TJ; ++j) acc[i][j] = M::mma(a[i], ringB[set][ks][j], acc[i][j]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+        for (int i = 0; i < TI - 2; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, TJ, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * TJ, 0);
       }
     }
   };
@@ -2285,14 +2289,23 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
         fetch(j, ks + PD);             // ring slot j was stashed for step ks; refill it PD steps ahead
         typename M::Frag af[WT], bf[WT];
 #pragma unroll
-        for (int i = 0; i < WT; ++i) {
-          af[i] = M::load(&lds[ks & 1][(wm * WT + i) * FRAG + lane * VEC]);
-          bf[i] = M::load(&lds[ks & 1][(2 * WT + wn * WT + i) * FRAG + lane * VEC]);
-        }
+        for (int i = 0; i < WT; ++i) bf[i] = M::load(&lds[ks & 1][(2 * WT + wn * WT + i) * FRAG + lane * VEC]);
+#pragma unroll
+        for (int i = 0; i < WT; ++i) af[i] = M::load(&lds[ks & 1][(wm * WT + i) * FRAG + lane * VEC]);
 #pragma unroll
         for (int i = 0; i < WT; ++i)
 #pragma unroll
           for (int jj = 0; jj < WT; ++jj) acc[i][jj] = M::mma(af[i], bf[jj], acc[i][jj]);
+        // order of this block's LDS reads (0x100) and MFMAs (0x008): what the first row of MFMAs
+        // needs (af[0] and every bf) plus af[1], then a row of MFMAs and the next af in turn, so
+        // that only the first reads of a macro step are waited for
+        __builtin_amdgcn_sched_group_barrier(0x100, WT + 2, 0);
+#pragma unroll
+        for (int i = 0; i < WT - 2; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, WT, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * WT, 0);
         if (ks + 1 < nk) stash((j + 1) % PD, (ks + 1) & 1);
       }
       __syncthreads();
