@@ -485,7 +485,7 @@ def main() -> int:
     # What a bracket adds depends on how long the kernel inside it runs: idle kernels of known
     # length, timed back to back and each inside its own bracket, give the curve that turns an
     # event-sampled single-launch time into the launch's own time.
-    bracket_curve = [mb.mebptt_bracket_overhead_us(L, 200) for L in (0, 2, 4, 8, 16, 32, 64, 128, 256, 512)]
+    bracket_curve = [mb.mebptt_bracket_overhead_us(L, 100) for L in (0, 2, 4, 8, 16, 32, 64)]
     log(f"[bench] back-to-back empty launches: {launch_floor_us:.2f} us each; event bracket around a minimal launch: "
         f"{bracket_us:.2f} us; bracket curve (own time -> bracketed): "
         + ", ".join(f"{a:.1f}->{b:.1f}" for a, b in bracket_curve))
