@@ -152,3 +152,30 @@ def test_shutdown_and_reuse():
     _same(Session(w, inp).run_and_fetch(), want)
     us = mb.mebptt_null_launch_us(500)
     assert 0.2 < us < 100.0
+
+
+def test_measurement_hooks():
+    """The stand-alone measurements return sane values and leave the device usable: every
+    synchronisation variant completes with status 0 (32 workgroups per XCD, no wait gave up, every
+    exchanged word read back right), the per-XCD meeting is cheaper than the device-wide one, an
+    event pair costs something but not much, and the chunk length follows the documented rule."""
+    from paper_1606_03401_amd.session import Session
+    us = []
+    for variant in (0, 1, 2):
+        t, status = mb.mebptt_measure_sync(variant, 500)
+        assert status == 0, (variant, status)
+        assert 0.05 < t < 100.0, (variant, t)
+        us.append(t)
+    assert us[1] < us[0]
+    with pytest.raises(mb.MebpttError):
+        mb.mebptt_measure_sync(3, 10)
+    plain, bracketed = mb.mebptt_bracket_overhead_us(8.0, 50)
+    assert 8.0 <= plain < 40.0 and plain < bracketed < plain + 40.0
+    for name, ch in (("cfg2", 32), ("cfg3", 32), ("cfg5", 64), ("cfg1", 64)):
+        w = wl.CONFIGS[name]
+        desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype, w.loss, w.dy_first_step)
+        assert mb.mebptt_chunk_steps(desc) == ch
+    w = wl.CONFIGS["cfg1"]
+    inp = wl.make_inputs(w)
+    a = Session(w, inp).run_and_fetch()
+    _same(Session(w, inp).run_and_fetch(), a)
