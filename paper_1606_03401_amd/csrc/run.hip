@@ -182,6 +182,22 @@ std::mutex g_run_mutex;
 // would each hold a part of the chip and wait for the rest.  The last run that used them records
 // this event when its work is enqueued and the next such run makes its stream wait for it.
 bool g_chain_enabled = true;
+
+// The resident launches (forward chains, sweeps) are laid out for a device of 8 XCDs with 32 compute
+// units each; on anything else (a partitioned device, masked compute units) they would only raise
+// their status word, so there the launch-per-step path is used from the start.  Cached per device;
+// called with g_run_mutex held.
+int g_device_cus[16] = {};   // 0: not asked yet
+bool device_fits_resident_launches() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return false;
+  if (g_device_cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = -1;
+    g_device_cus[dev] = n > 0 ? n : -1;
+  }
+  return g_device_cus[dev] == 256;
+}
 hipEvent_t g_chain_done[MAX_DEVICES] = {};
 bool g_chain_recorded[MAX_DEVICES] = {};
 
@@ -756,7 +772,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // chain goes out as forward-chain launches of up to forward_chain_max_steps() steps instead of
   // one launch per step.  Not in the no-allocation path, which owns no event to keep two such runs
   // from overlapping on the device.
-  const bool chain_ok = mode != RUN_STATIC && g_chain_enabled && can_run_forward_chain(d);
+  const bool resident_ok = mode != RUN_STATIC && g_chain_enabled && device_fits_resident_launches();
+  const bool chain_ok = resident_ok && can_run_forward_chain(d);
   constexpr int CHAIN_MIN_STEPS = 3;
   unsigned chain_base = 0;        // arrivals left in the group counters by this run's earlier chain launches
   unsigned chain_launches = 0;    // chain launches of this run so far
@@ -786,7 +803,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   };
   // "forward operation of step s keeping its internal state in the working core, then the backward
   // operation of step s" -- the pair every step of a sub-sequence that fits into memory ends in.
-  const bool sweep_ok = mode != RUN_STATIC && g_chain_enabled && can_run_sweep(d);
+  const bool sweep_ok = resident_ok && can_run_sweep(d);
   auto pair_at = [&](size_t i) {
     if (i + 1 >= ops.size()) return false;
     const mebptt_op &f = ops[i], &b = ops[i + 1];
@@ -796,7 +813,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
 
   // Backward operations through internal states that earlier launches stored in slots (internal-state
   // pushes; store-everything BPTT): consecutive ones go out as backward-only sweep launches.
-  const bool bsweep_ok = mode != RUN_STATIC && g_chain_enabled && can_run_backward_sweep(d);
+  const bool bsweep_ok = resident_ok && can_run_backward_sweep(d);
   auto stored_bwd_at = [&](size_t i) { return i < ops.size() && ops[i].op == MEBPTT_OP_BWD && ops[i].dst >= 0; };
   // One sweep launch for steps s_hi, s_hi - 1, ... (n of them, one chunk); states == nullptr: with forward operations.
   auto issue_sweep = [&](int s_hi, int n, const float* const* srcs, const float* const* states) -> int {
