@@ -548,7 +548,7 @@ def main() -> int:
             budgets = wl.CFG5_BUDGET_SWEEP if name == "cfg5" else (wc.m,)
             for i, m in enumerate(budgets):
                 few = 2 if (name == "cfg5" and m < 31) else 3
-                row = measure(wc, inp_c, m=m, steps=few, warmup=1, graph=(name != "cfg4" and not args.no_graph),
+                row = measure(wc, inp_c, m=m, steps=few, warmup=1, graph=not args.no_graph,
                               profile=(m == wc.m), store_all=(i == 0),
                               launch_floor_us=launch_floor_us, bracket_us=bracket_us, bracket_curve=bracket_curve)
                 if i > 0:   # one store-everything run serves the whole sweep
