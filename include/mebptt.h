@@ -362,6 +362,13 @@ int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_
  * one with masked compute units the launch-per-step path runs regardless of this switch.
  * Process-wide; not to be toggled while a run is enqueued. */
 int mebptt_forward_chain_enable(int32_t on);
+/* The bound every wait inside a forward-chain or sweep launch runs under, in ticks of the device's
+ * 100 MHz wall clock (default 50 000 000 = 0.5 s; a negative value restores the default).  With 0
+ * every wait that does not find its data at once gives up: each workgroup leaves through the
+ * ordinary exit, the run completes with invalid results and mebptt_run_status reports 1 -- the path
+ * a real time-out takes, made reachable for tests.  Process-wide; applies to launches enqueued
+ * after the call. */
+int mebptt_resident_wait_limit(int64_t ticks);
 
 /* Releases what the library created on every device: the side streams and their events, the
  * events of the measurement hooks, the record of prepared workspaces.  Waits for the side

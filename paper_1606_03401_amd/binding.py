@@ -129,6 +129,7 @@ SIGNATURES = {
     "mebptt_static_workspace_bytes": (C.c_size_t, []),
     "mebptt_run_status": (C.c_int, [_DESC, _P, C.c_size_t, _P, C.POINTER(C.c_int32)]),
     "mebptt_forward_chain_enable": (C.c_int, [C.c_int32]),
+    "mebptt_resident_wait_limit": (C.c_int, [C.c_int64]),
     "mebptt_shutdown": (C.c_int, []),
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_measure_sync": (C.c_int, [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
@@ -408,6 +409,10 @@ def mebptt_run_status(desc: mebptt_lstm_desc, workspace, stream: Optional[int] =
 
 def mebptt_forward_chain_enable(on: bool) -> None:
     _check(lib().mebptt_forward_chain_enable(1 if on else 0))
+
+
+def mebptt_resident_wait_limit(ticks: int) -> None:
+    _check(lib().mebptt_resident_wait_limit(int(ticks)))
 
 
 def mebptt_shutdown() -> None:

@@ -106,6 +106,9 @@ struct ChainStep {
   float* out;
   float* gates;
 };
+// Bound of every wait inside a resident launch, in ticks of the 100 MHz wall clock (negative: the
+// default of 0.5 s).  0 makes every wait give up at once.
+void set_resident_wait_ticks(long long ticks);
 bool can_run_forward_chain(const Dims& d);
 int forward_chain_max_steps();
 size_t forward_chain_ring_bytes(const Dims& d);

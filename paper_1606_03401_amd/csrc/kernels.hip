@@ -982,6 +982,11 @@ constexpr int RES_MAX_STEPS = 48;   // steps of one launch: their destinations t
 constexpr int RES_RING = 4;         // h slices in flight (two would do: a step ahead at most)
 constexpr int RES_WGS = 256, RES_GROUPS = 8, RES_MEMBERS = RES_WGS / RES_GROUPS;
 constexpr long long RES_WAIT_TICKS = 50000000;   // 0.5 s of the 100 MHz wall clock
+// The bound every wait of a resident launch runs under, in ticks of that clock.  A host-side
+// setting (resident_wait_ticks) so that a test can make the waits give up at once -- every
+// workgroup then leaves through the same path as after a real time-out -- without anything hanging.
+static long long g_wait_ticks = RES_WAIT_TICKS;
+void set_resident_wait_ticks(long long ticks) { g_wait_ticks = ticks < 0 ? RES_WAIT_TICKS : ticks; }
 
 struct ResStep {
   float* out;     // unit that receives (h, c) of this step, or NULL
@@ -996,6 +1001,7 @@ struct ResParams {
   unsigned* sync;      // words: arrival counter of XCD g at [g*64], rank counter at [512 + g*64], status at [1024]
   unsigned base;       // value of every arrival counter when the launch starts
   unsigned launch;     // chain launches of this run before this one (every rank counter stands at 32 * launch)
+  long long wait_ticks;   // bound of every wait, in ticks of the 100 MHz wall clock
   int count;
   int B, I, H, KX, KH, BP, nb;
   size_t unit;         // floats per unit
@@ -1163,10 +1169,10 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         // agent-scope loads see the counter in the L2 (32 pollers do not queue behind each other as
         // read-modify-writes would: 1.95 -> 1.59 us per exchange round in isolation)
         while ((int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-          if ((++polls & 15) == 0) {
+          if (p.wait_ticks == 0 || (++polls & 15) == 0) {   // a bound of 0: one look only
             const long long now = wall_clock64();
             if (t0 == 0) t0 = now;
-            if (now - t0 > RES_WAIT_TICKS ||
+            if (now - t0 >= p.wait_ticks ||
                 __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
               __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               ok = 0;
@@ -1329,6 +1335,7 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
   p.sync = sync;
   p.base = base;
   p.launch = launch;
+  p.wait_ticks = g_wait_ticks;
   p.count = count;
   p.B = d.B;
   p.I = d.I;
@@ -1382,6 +1389,7 @@ struct SweepParams {
   void* aT;
   unsigned* sync;
   unsigned base, launch;
+  long long wait_ticks;  // bound of every wait, in ticks of the 100 MHz wall clock
   int s_hi, count;       // steps s_hi, s_hi - 1, ..., s_hi - count + 1 (all in one chunk)
   int B, I, H, KX, KH, BP, nb, G4, NX, KC, CH;
   size_t unit;
@@ -1620,10 +1628,10 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
         int ok = 1, polls = 0;
         long long t0 = 0;
         while ((int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-          if ((++polls & 15) == 0) {
+          if (p.wait_ticks == 0 || (++polls & 15) == 0) {   // a bound of 0: one look only
             const long long now = wall_clock64();
             if (t0 == 0) t0 = now;
-            if (now - t0 > RES_WAIT_TICKS ||
+            if (now - t0 >= p.wait_ticks ||
                 __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
               __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               ok = 0;
@@ -1814,6 +1822,7 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   p.aT = a.aT;
   p.sync = a.sync;
   p.base = a.base;
+  p.wait_ticks = g_wait_ticks;
   p.launch = a.launch;
   p.s_hi = a.s_hi;
   p.count = a.count;

@@ -433,6 +433,12 @@ int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_
   return MEBPTT_OK;
 }
 
+int mebptt_resident_wait_limit(int64_t ticks) {
+  std::lock_guard<std::mutex> lock(g_run_mutex);
+  set_resident_wait_ticks((long long)ticks);
+  return MEBPTT_OK;
+}
+
 int mebptt_forward_chain_enable(int32_t on) {
   std::lock_guard<std::mutex> lock(g_run_mutex);
   g_chain_enabled = on != 0;

@@ -137,3 +137,24 @@ def test_chains_from_two_host_threads():
         assert len(results[k]) == 5
         for got in results[k]:
             _same(got, want[k])
+
+
+def test_bounded_waits_give_up_and_report():
+    """With the wait bound set to zero from the host, a workgroup that does not find the others'
+    data at its first look gives up: every kernel still runs to its end, the run returns, the status
+    word says a wait gave up and the session refuses the results.  With the default bound restored
+    the same session computes the right gradients again."""
+    from paper_1606_03401_amd.session import Session
+    w = wl.Workload("give-up", B=64, I=128, H=128, t=60, kind=wl.KIND_HSM, m=60, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, seed=77)
+    inp = wl.make_inputs(w)
+    s = Session(w, inp)
+    good = s.run_and_fetch()
+    mb.mebptt_resident_wait_limit(0)
+    try:
+        with pytest.raises(RuntimeError):
+            s.run_and_fetch()
+        assert mb.mebptt_run_status(s.desc, s.workspace) == 1
+    finally:
+        mb.mebptt_resident_wait_limit(-1)
+    _same(s.run_and_fetch(), good, "after restoring the bound")
