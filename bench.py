@@ -405,11 +405,14 @@ def floors(args) -> int:
         w = wl.CONFIGS[name]
         desc = mb.make_desc(w.B, w.I, w.H, w.t, w.gemm_dtype, w.loss, w.dy_first_step)
         ws = torch.zeros(mb.mebptt_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+        su, sb = mb.mebptt_measure_forward_stream(desc, ws, 50)
+        log(f"[floors] {name}: a kernel that only reads what a forward launch reads: {su:.2f} us per launch for {sb / 1e6:.0f} MB "
+            f"through the L2s = {sb / su / 1e6:.1f} TB/s to the compute units (weights {forward_bytes(w) / 1e6:.1f} MB algorithmic)")
         wu, du = mb.mebptt_measure_gemms(desc, ws, 30)
         ch = mb.mebptt_chunk_steps(desc)
         fw, fd = ch * forward_flops(w), ch * 2.0 * gate_blocks(w) * w.B * w.H * w.I
         peak = MFMA_PEAK_TFLOPS[w.gemm_dtype]
-        row = {"name": name, "chunk_steps": ch, "wgrad_us": wu, "wgrad_tflops": fw / wu / 1e6, "wgrad_frac_mfma_peak": fw / wu / 1e6 / peak,
+        row = {"name": name, "forward_stream_us": su, "forward_stream_bytes": sb, "chunk_steps": ch, "wgrad_us": wu, "wgrad_tflops": fw / wu / 1e6, "wgrad_frac_mfma_peak": fw / wu / 1e6 / peak,
                "dgrad_us": du, "dgrad_tflops": fd / du / 1e6, "dgrad_frac_mfma_peak": fd / du / 1e6 / peak}
         out["gemms_alone"].append(row)
         log(f"[floors] {name}: chunk of {ch} steps: dW GEMM {wu:.1f} us = {row['wgrad_tflops']:.0f} TFLOP/s "

@@ -446,6 +446,14 @@ int mebptt_null_launch_us(int32_t launches, void* stream, double* out_us);
  * Synchronises the stream.  Errors: EINVAL, EWORKSPACE, EHIP. */
 int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
                          void* stream, double* wgrad_us, double* dgrad_us);
+/* What the memory system needs to deliver one forward launch's bytes: a kernel with the grid of the
+ * forward launch of this shape whose workgroups only read the operand panels their forward
+ * counterparts read (the weight panel from the workspace's operand copy, an activation panel of the
+ * same size from its state area), launched `reps` times back to back on `stream`: microseconds per
+ * launch and the bytes all workgroups read per launch (host memory).  Contents are not looked at.
+ * Synchronises the stream.  Errors: EINVAL, EWORKSPACE, EHIP. */
+int mebptt_measure_forward_stream(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
+                                  void* stream, double* us_per_launch, double* delivered_bytes);
 /* Time steps per chunk of the time-batched GEMMs for this shape (the K extent of the dW GEMM is
  * this many times B), or a negative error code. */
 int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc);

@@ -134,6 +134,7 @@ SIGNATURES = {
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_measure_sync": (C.c_int, [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "mebptt_chunk_steps": (C.c_int32, [_DESC]),
+    "mebptt_measure_forward_stream": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_bracket_overhead_us": (C.c_int, [C.c_double, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_measure_gemms": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_profile_enable": (C.c_int, [C.c_int32]),
@@ -470,6 +471,14 @@ def mebptt_chain_run(desc: mebptt_chain_desc, plan: ChainPlan, W, b, x0, dy, poo
                                 arr(db), _ptr(dx0), _ptr(y_out), C.byref(stats), _stream(stream))
     _check(rc)
     return stats
+
+
+def mebptt_measure_forward_stream(desc: mebptt_lstm_desc, workspace, reps: int = 50, stream: Optional[int] = None):
+    """(us per launch, bytes read per launch) of the kernel that only streams a forward launch's operand panels."""
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().mebptt_measure_forward_stream(C.byref(desc), _ptr(workspace), _nbytes(workspace), reps, _stream(stream),
+                                               C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def mebptt_chunk_steps(desc: mebptt_lstm_desc) -> int:

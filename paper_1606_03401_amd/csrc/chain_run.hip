@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void chain_gemm_kernel(const float* __restrict
                                                          const float* __restrict__ Bm, long sbk, long sbj,
                                                          float* __restrict__ C, long ldc, int M, int N, int K,
                                                          const float* __restrict__ bias, int epilogue) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: conditions on it are scalar branches (an MFMA under an empty lane mask would still execute)
   const int i0 = (blockIdx.y * 2 + (wave >> 1)) * 16, j0 = (blockIdx.x * 2 + (wave & 1)) * 16;
   if (i0 >= M || j0 >= N) return;   // whole wave
   const int li = lane & 15, lk = lane >> 4;

@@ -82,6 +82,12 @@ struct BackwardArgs {
 // LSTM backward producing dG_s and dc_{s-1}.
 hipError_t launch_backward(const Dims& d, const BackwardArgs& a, hipStream_t st);
 
+// Measurement: a kernel with the grid of the forward launch of this shape whose workgroups only
+// read the operand panels their forward counterparts read (weights from Wp, activations from
+// `act`, act_bytes of readable memory); *delivered_bytes = what all workgroups read together.
+hipError_t launch_forward_stream(const Dims& d, const void* Wp, const void* act, size_t act_bytes, float* sink,
+                                 size_t* delivered_bytes, hipStream_t st);
+
 // True when the shape runs the large-K kernel configurations, for which a backward step and an
 // independent forward step can share one launch.
 bool can_fuse_pair(const Dims& d);

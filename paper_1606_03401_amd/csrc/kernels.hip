@@ -15,6 +15,8 @@
 // pointwise forward fused).  In the backward step the four rows are four consecutive hidden
 // units of dh, and loss-gradient injection and the pointwise backward again run on the GEMM
 // result (the dh = dG W_hh product of step s+1 fused with the pointwise backward of step s).
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace mebptt {
@@ -420,7 +422,10 @@ template <class T, int NG, int BT, int KS, int U, int CELL>
 __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* red) {
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // wave_index note: the wave index is read into a scalar register.  Conditions on it then compile
+  // to scalar branches; as a vector value they become lane masks, and an MFMA under a lane mask that
+  // is empty still executes (short masked blocks get no branch around them).
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
   const int group0 = bx * NG;
@@ -484,36 +489,94 @@ __device__ inline void forward_body(const FwdParams& p, int bx, int by, float* r
     }
   }
 
-  for (int s0 = wave; s0 < nsteps; s0 += KS * U) {
-    RawAct<VEC> rb[U][BT];          // fp32 activations still to be converted (x; h in the plain layout)
-    typename M::Frag hb[U][BT];     // ready-made h fragments (split layout)
-    typename M::Frag af[U][NG];
+  // This wave's macro steps wave, wave + KS, ... in rising order: first those of the x segment
+  // (and, in the plain layout, all of them), U at a time: all loads, then all MFMAs.  When every
+  // row length is a multiple of the fragment width the loads are the branch-free ones (a loader
+  // with branches makes the compiler wait for all outstanding loads between fragments); the
+  // choice is made once, outside the loop.
+  const int n_batch = HP_::SPLIT ? nsx : nsteps;   // macro steps handled by the batched loop
+  auto batched = [&](auto whole_tag) {
+    constexpr bool WHOLE = decltype(whole_tag)::value;
+    for (int s0 = wave; s0 < n_batch; s0 += KS * U) {
+      RawAct<VEC> rb[U][BT];          // fp32 activations still to be converted (x; h in the plain layout)
+      typename M::Frag af[U][NG];
 #pragma unroll
-    for (int uu = 0; uu < U; ++uu) {
-      const int s = min(s0 + uu * KS, nsteps - 1);   // clamped: the surplus fragment is discarded
-      const int k = s * KSTEP + VEC * lq;
-#pragma unroll
-      for (int t = 0; t < BT; ++t) {
-        if (s < nsx)
-          rb[uu][t] = load_raw<VEC>(xrow[t], k, p.I, x_vec);
-        else if (HP_::SPLIT)
-          hb[uu][t] = M::load(hfrag[t] + (size_t)(s - nsx) * 64 * VEC);
-        else
-          rb[uu][t] = load_raw<VEC>(hrow[t], k - p.KX, p.H, h_vec);
-      }
-#pragma unroll
-      for (int g = 0; g < NG; ++g) af[uu][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
-    }
-#pragma unroll
-    for (int uu = 0; uu < U; ++uu) {
-      const int s = s0 + uu * KS;
-      if (s < nsteps) {
+      for (int uu = 0; uu < U; ++uu) {
+        const int s = min(s0 + uu * KS, n_batch - 1);   // clamped: the surplus fragment is discarded
+        const int k = s * KSTEP + VEC * lq;
 #pragma unroll
         for (int t = 0; t < BT; ++t) {
-          typename M::Frag bf = (HP_::SPLIT && s >= nsx) ? hb[uu][t] : M::from_f32(rb[uu][t].v);
-#pragma unroll
-          for (int g = 0; g < NG; ++g) acc[g][t] = M::mma(af[uu][g], bf, acc[g][t]);
+          if (WHOLE)
+            rb[uu][t] = s < nsx ? load_raw_whole<VEC>(xrow[t], k, p.I) : load_raw_whole<VEC>(hrow[t], k - p.KX, p.H);
+          else if (s < nsx)
+            rb[uu][t] = load_raw<VEC>(xrow[t], k, p.I, x_vec);
+          else
+            rb[uu][t] = load_raw<VEC>(hrow[t], k - p.KX, p.H, h_vec);
         }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) af[uu][g] = M::load(wbase[g] + (size_t)s * 64 * VEC);
+      }
+#pragma unroll
+      for (int uu = 0; uu < U; ++uu) {
+        const int s = s0 + uu * KS;
+        if (s < n_batch) {
+#pragma unroll
+          for (int t = 0; t < BT; ++t) {
+            typename M::Frag bf = M::from_f32(rb[uu][t].v);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g][t] = M::mma(af[uu][g], bf, acc[g][t]);
+          }
+        }
+      }
+    }
+  };
+  if (p.I % VEC == 0 && (HP_::SPLIT || p.H % VEC == 0))
+    batched(std::true_type{});
+  else
+    batched(std::false_type{});
+  if (HP_::SPLIT) {
+    // The h segment (ready-made fragments: every load is 16 bytes per lane, no branches) runs
+    // through a ring of U register slots: a slot is refilled with the step U ahead as soon as its
+    // MFMAs are issued, so U steps' loads stay in flight while the matrix pipe works, instead of
+    // the pipe idling through every batch of loads.  The main loop has no conditions (the compiler
+    // can then wait for exactly the loads a step needs); the last steps are peeled.
+    const int sh0 = wave >= nsx ? wave : wave + KS * ((nsx - wave + KS - 1) / KS);   // this wave's first h step
+    typename M::Frag af[U][NG], hb[U][BT];
+    auto load_slot = [&](int u, int step) {
+      const int sc = min(step, nsteps - 1);   // clamped: a surplus fragment is discarded
+#pragma unroll
+      for (int t = 0; t < BT; ++t) hb[u][t] = M::load(hfrag[t] + (size_t)(sc - nsx) * 64 * VEC);
+#pragma unroll
+      for (int g = 0; g < NG; ++g) af[u][g] = M::load(wbase[g] + (size_t)sc * 64 * VEC);
+    };
+    auto mma_slot = [&](int u) {
+#pragma unroll
+      for (int t = 0; t < BT; ++t)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g][t] = M::mma(af[u][g], hb[u][t], acc[g][t]);
+    };
+    if (sh0 < nsteps) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) load_slot(u, sh0 + u * KS);
+      int s = sh0;
+      for (; s + KS * (2 * U - 1) < nsteps; s += KS * U) {   // every refill target is a real step
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          mma_slot(u);
+          load_slot(u, s + (u + U) * KS);
+        }
+      }
+      // what the slots hold now, then at most U - 1 further steps, fetched as a batch
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (s + u * KS < nsteps) mma_slot(u);
+      s += KS * U;
+      if (s < nsteps) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) load_slot(u, s + u * KS);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (s + u * KS < nsteps) mma_slot(u);
       }
     }
   }
@@ -591,7 +654,7 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
   using M = Mma<T>;
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC;
   constexpr int NTILE = NT * BT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   if (wave >= KS) return;   // surplus waves of a wider (fused) workgroup leave before any barrier
   const int lrow = lane & 15, lq = lane >> 4;
   const int ntiles_n = p.HP / 16, ntiles_b = p.BP / 16;
@@ -859,6 +922,66 @@ hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const 
                           float* dst_unit, float* gates_units, hipStream_t st) {
   FwdParams p = make_fwd_params(d, Wp, bp, x_s, src_unit, dst_unit, gates_units);
   return d.dtype ? launch_forward_t<__bf16>(d, p, st) : launch_forward_t<float>(d, p, st);
+}
+
+// ---- measurement: the bytes of a forward launch, streamed -----------------------------------
+// The grid and block of the forward launch of this shape; every workgroup reads the weight panel
+// (its gate rows x K, GEMM operand type) and the activation panel (its sequences x K: x in fp32, h
+// in the operand type) its forward counterpart reads, from the same weight array, with the same
+// 16-byte-per-lane loads, eight in flight per wave -- and does nothing else.  What this takes is
+// what the memory system needs to deliver the launch's bytes to the compute units.
+__global__ __launch_bounds__(512) void stream_panels_kernel(const uint4* __restrict__ w, size_t w_panel, const uint4* __restrict__ a,
+                                                            size_t a_panel, float* __restrict__ sink) {
+  constexpr int U = 8;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+  float acc = 0.0f;
+  for (int part = 0; part < 2; ++part) {
+    const uint4* base = part ? a + (size_t)blockIdx.y * a_panel : w + (size_t)blockIdx.x * w_panel;
+    const size_t nblk = (part ? a_panel : w_panel) / 64;   // blocks of 64 x 16 bytes
+    for (size_t b0 = wave; b0 < nblk; b0 += (size_t)nwaves * U) {
+      uint4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        size_t b = b0 + (size_t)u * nwaves;
+        if (b >= nblk) b = nblk - 1;
+        v[u] = base[b * 64 + lane];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc += __uint_as_float(v[u].x ^ v[u].y ^ v[u].z ^ v[u].w);
+    }
+  }
+  if (acc == 12345.678f) sink[0] = acc;   // keeps the loads alive; never true in practice
+}
+
+template <class T>
+static void forward_launch_shape(const Dims& d, int& ng, int& bt, int& ks) {
+  switch (forward_config<T>(d)) {
+    case FWD_TINY: ng = 1, bt = 1, ks = 4; break;
+    case FWD_SMALLK: ng = 4, bt = 1, ks = 4; break;
+    case FWD_82: ng = 8, bt = 2, ks = 8; break;
+    case FWD_42: ng = 4, bt = 2, ks = 8; break;
+    default: ng = PAIR_NG, bt = 1, ks = PAIR_FKS; break;
+  }
+}
+
+hipError_t launch_forward_stream(const Dims& d, const void* Wp, const void* act, size_t act_bytes, float* sink,
+                                 size_t* delivered_bytes, hipStream_t st) {
+  int ng, bt, ks;
+  if (d.dtype)
+    forward_launch_shape<__bf16>(d, ng, bt, ks);
+  else
+    forward_launch_shape<float>(d, ng, bt, ks);
+  const size_t op = d.op_bytes();
+  const dim3 grid((d.HP / 4 + ng - 1) / ng, (d.BP / 16 + bt - 1) / bt);
+  // 16-byte vectors per panel, rounded down to whole 1 KiB blocks
+  const size_t w_panel = (size_t)ng * 16 * d.KP * op / 1024 * 64;
+  const size_t a_panel = ((size_t)bt * 16 * ((size_t)d.KX * 4 + (size_t)d.KH * op)) / 1024 * 64;
+  if (w_panel == 0 || a_panel == 0 || a_panel * 16 * grid.y > act_bytes) return hipErrorInvalidValue;
+  if ((size_t)grid.x * w_panel * 16 > (size_t)d.G4 * d.KP * op) return hipErrorInvalidValue;
+  if (delivered_bytes) *delivered_bytes = (size_t)grid.x * grid.y * (w_panel + a_panel) * 16;
+  stream_panels_kernel<<<grid, dim3(64 * ks), 0, st>>>(reinterpret_cast<const uint4*>(Wp), w_panel,
+                                                      reinterpret_cast<const uint4*>(act), a_panel, sink);
+  return hipGetLastError();
 }
 
 template <class T, int NT, int BT, int KS, int U>
@@ -1877,7 +2000,7 @@ __global__ __launch_bounds__(64 * KS) void dgrad_kernel(const T* __restrict__ WT
   constexpr int VEC = M::VEC, KSTEP = 4 * VEC, NTILE = NT * RT, NPIECE = NTILE * 4, PPW = (NPIECE + KS - 1) / KS;
   extern __shared__ __attribute__((aligned(16))) unsigned char dgrad_smem[];
   float* red = reinterpret_cast<float*>(dgrad_smem);   // [KS][NTILE][4][64]
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   const int lrow = lane & 15, lq = lane >> 4;
   // Workgroups are handed to the 8 XCDs round-robin by their linear id.  As launched, an XCD would
   // own every 8th column group and see all of dG.  The id is re-mapped so that each XCD works
@@ -2020,7 +2143,7 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
   typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   T* lds = reinterpret_cast<T*>(smem);    // [stage 2][macro step 2][16 tiles of A][FRAG]
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   const int wi = wave & 1, wj = wave >> 1;
   const int total = p.gx * p.gy, id = (int)blockIdx.x;
   const int xcd = id & 7;
@@ -2245,7 +2368,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
   constexpr int FRAG = 64 * VEC;                  // elements of one fragment block (1 KiB)
   typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
   __shared__ __attribute__((aligned(16))) T lds[2][4 * WT * FRAG];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   const int wm = wave & 1, wn = wave >> 1;
   const int MT = G4 / 16, NT = NTOT / 16;
   const int mt_wg = blockIdx.x * 2 * WT, nt_wg = blockIdx.y * 2 * WT;

@@ -564,6 +564,41 @@ int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t w
   return MEBPTT_OK;
 }
 
+int mebptt_measure_forward_stream(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
+                                  void* stream, double* us_per_launch, double* delivered_bytes) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (reps < 1 || reps > 10000 || !us_per_launch || !delivered_bytes)
+    return set_error(MEBPTT_EINVAL, "reps must be in [1, 10000] and the outputs non-NULL");
+  if (!workspace) return set_error(MEBPTT_EWORKSPACE, "workspace is NULL");
+  const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell);
+  const Workspace w = layout(d);
+  if (workspace_bytes < w.total)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  if (misaligned(workspace, ALIGN)) return set_error(MEBPTT_EWORKSPACE, "workspace must be 256-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  std::lock_guard<std::mutex> lock(g_run_mutex);
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  for (hipEvent_t& e : ev) HIP_TRY(hipEventCreate(&e));
+  size_t delivered = 0;
+  hipError_t e = hipSuccess;
+  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {   // first pass warms up
+    e = hipEventRecord(ev[0], st);
+    for (int i = 0; i < reps && e == hipSuccess; ++i)
+      e = launch_forward_stream(d, ws + w.Wp, ws + w.state, w.dWacc - w.state, reinterpret_cast<float*>(ws + w.dc), &delivered, st);
+    if (e == hipSuccess) e = hipEventRecord(ev[1], st);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
+  }
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+  for (hipEvent_t& x : ev) (void)hipEventDestroy(x);
+  if (e != hipSuccess) return set_error(MEBPTT_EHIP, "streaming measurement failed: %s", hipGetErrorString(e));
+  *us_per_launch = (double)ms * 1e3 / reps;
+  *delivered_bytes = (double)delivered;
+  return MEBPTT_OK;
+}
+
 size_t mebptt_static_workspace_bytes(void) { return MEBPTT_STATIC_WORKSPACE_BYTES; }
 
 int mebptt_run_static(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, const float* W_ih, const float* W_hh,
