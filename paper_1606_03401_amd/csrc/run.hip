@@ -815,7 +815,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // from overlapping on the device.
   const bool resident_ok = mode != RUN_STATIC && g_chain_enabled && device_fits_resident_launches();
   const bool chain_ok = resident_ok && can_run_forward_chain(d);
-  constexpr int CHAIN_MIN_STEPS = 3;
+  constexpr int CHAIN_MIN_STEPS = 2;     // two steps in one launch already beat two launches (measured on the paper's 256-wide model)
   unsigned chain_base = 0;        // arrivals left in the group counters by this run's earlier chain launches
   unsigned chain_launches = 0;    // chain launches of this run so far
   bool chain_used = false;
