@@ -296,6 +296,12 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
             sw["us_per_step"] = prof.sweep_ms / prof.sweep_steps * 1e3
             log(f"[bench]   sweep: {sw['steps_per_step']:.0f} backward steps/step in {sw['launches_per_step']:.0f} launches, "
                 f"{sw['us_per_step']:.2f} us per step")
+        if prof.batch_steps:
+            fb = classes["forward batch"]
+            fb["steps_per_step"] = prof.batch_steps / prof_steps
+            fb["us_per_forward_op"] = prof.batch_ms / prof.batch_steps * 1e3
+            log(f"[bench]   forward batch: {fb['steps_per_step']:.0f} independent forward ops/step in {fb['launches_per_step']:.0f} launches, "
+                f"{fb['us_per_forward_op']:.2f} us per forward op")
         # The dominant kernel = the class with the largest share of the step; its roofline block.
         share = {}
         for name in ("forward", "backward", "backward+forward"):
@@ -306,16 +312,19 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
             share["forward chain"] = prof.chain_ms / prof_steps * 1e3
         if prof.sweep_steps:
             share["sweep"] = prof.sweep_ms / prof_steps * 1e3
+        if prof.batch_steps:
+            share["forward batch"] = prof.batch_ms / prof_steps * 1e3
         out["time_share_us"] = share
         if share:
             dom = max(share, key=share.get)
             kernel = {"forward": "forward_kernel", "backward": "backward_kernel", "backward+forward": "pair_kernel",
-                      "forward chain": "forward_chain_kernel", "sweep": "sweep_kernel"}[dom]
+                      "forward chain": "forward_chain_kernel", "sweep": "sweep_kernel",
+                      "forward batch": "forward_batch_kernel"}[dom]
             if dom == "sweep":
-                # both weight operands stay on the chip; a step carries the dh GEMM and, where the
-                # internal state is recomputed (hidden-state slots), the forward GEMM as well
+                # the weight operands stay on the chip; a step carries the dh GEMM and, in the launches
+                # that recompute the internal state themselves, the forward GEMM as well
                 us = classes[dom]["us_per_step"]
-                fl = F_dh + (F_fwd if sess.kind == wl.KIND_HSM else 0.0)
+                fl = F_dh + F_fwd * prof.sweep_forward_steps / prof.sweep_steps
                 tf = fl / (us * 1e-6) / 1e12
                 out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
                                    "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
@@ -328,6 +337,13 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
                 out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
                                    "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
                                    "flops_per_launch": forward_flops(w), "note": "per forward operation inside a chain launch"}
+            elif dom == "forward batch":
+                # independent forward operations: a dense contraction over all their sequences at once
+                us = classes[dom]["us_per_forward_op"]
+                tf = forward_flops(w) / (us * 1e-6) / 1e12
+                out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
+                                   "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
+                                   "flops_per_launch": forward_flops(w), "note": "per forward operation inside a batch launch"}
             else:
                 us = classes[dom]["net_us"]
                 nbytes = {"forward": forward_bytes(w), "backward": backward_bytes(w),

@@ -406,7 +406,8 @@ enum {
   MEBPTT_K_PAIR = 5,     /* one launch carrying a backward step and an independent forward op */
   MEBPTT_K_CHAIN = 6,    /* one launch carrying a chain of forward operations, weights resident  */
   MEBPTT_K_SWEEP = 7,    /* one launch carrying a run of (forward, backward) pairs, weights resident */
-  MEBPTT_K_CLASSES = 8
+  MEBPTT_K_FWD_BATCH = 8, /* one launch carrying forward operations that do not depend on each other */
+  MEBPTT_K_CLASSES = 9
 };
 typedef struct {
   int64_t launches[MEBPTT_K_CLASSES]; /* launches of the class in the profiled runs      */
@@ -425,6 +426,11 @@ typedef struct {
   int64_t sweep_steps;
   double sweep_ms;
   int64_t sampled_groups[MEBPTT_K_CLASSES]; /* event brackets behind `sampled` and `sampled_ms` */
+  /* Forward operations carried by sweep launches (the others run on internal states stored before). */
+  int64_t sweep_forward_steps;
+  /* The launches of independent forward operations are all bracketed: operations carried, time. */
+  int64_t batch_steps;
+  double batch_ms;
 } mebptt_profile;
 /* every_n > 0: from now on mebptt_run (on this thread's process-wide state) brackets every
  * every_n-th launch of each class with a pair of HIP events recorded on the run's stream;

@@ -73,15 +73,17 @@ class mebptt_stats(C.Structure):
                 ("reserved", C.c_int32), ("peak_slot_bytes", C.c_size_t)]
 
 
-K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_PAIR, K_CHAIN, K_SWEEP, K_CLASSES = 0, 1, 2, 3, 4, 5, 6, 7, 8
-K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward", "forward chain", "sweep")
+K_FORWARD, K_BACKWARD, K_WGRAD, K_DGRAD, K_SETUP, K_PAIR, K_CHAIN, K_SWEEP, K_FWD_BATCH, K_CLASSES = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+K_NAMES = ("forward", "backward", "wgrad", "dgrad", "setup", "backward+forward", "forward chain", "sweep",
+           "forward batch")
 
 
 class mebptt_profile(C.Structure):
     _fields_ = [("launches", C.c_int64 * K_CLASSES), ("sampled", C.c_int64 * K_CLASSES),
                 ("sampled_ms", C.c_double * K_CLASSES), ("forward_run_launches", C.c_int64),
                 ("forward_run_ms", C.c_double), ("chain_steps", C.c_int64), ("chain_ms", C.c_double),
-                ("sweep_steps", C.c_int64), ("sweep_ms", C.c_double), ("sampled_groups", C.c_int64 * K_CLASSES)]
+                ("sweep_steps", C.c_int64), ("sweep_ms", C.c_double), ("sampled_groups", C.c_int64 * K_CLASSES),
+                ("sweep_forward_steps", C.c_int64), ("batch_steps", C.c_int64), ("batch_ms", C.c_double)]
 
 
 # name -> (restype, argtypes): every symbol the header declares

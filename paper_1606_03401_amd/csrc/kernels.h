@@ -64,6 +64,14 @@ hipError_t launch_init_state(const Dims& d, const float* h0, const float* c0, fl
 hipError_t launch_forward(const Dims& d, const void* Wp, const float* bp, const float* x_s, const float* src_unit,
                           float* dst_unit, float* gates_units, hipStream_t st);
 
+// n independent forward operations in one launch (n <= forward_batch_max_steps()): operation j reads
+// x[j] and the hidden-state unit src[j] and writes the state and the gates to the three units at
+// dst[j].  Same bits as launch_forward.  bf16 LSTM only (can_run_forward_batch).
+int forward_batch_max_steps();
+bool can_run_forward_batch(const Dims& d);
+hipError_t launch_forward_batch(const Dims& d, const void* Wp, const float* bp, int n, const float* const* x,
+                                const float* const* src, float* const* dst, hipStream_t st);
+
 struct BackwardArgs {
   const void* WTh;
   const void* dG_next;    // dG rows of step s+1 (BP rows of the chunk buffer), or NULL for s = t

@@ -28,8 +28,20 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Workspace {
-  size_t Wp, bp, WTh, WTx, state, dWacc, dc, sync, dG[2], dGT[2], aT[2], ring, total;
+  size_t Wp, bp, WTh, WTx, state, dWacc, dc, sync, dG[2], dGT[2], aT[2], ring, stage, total;
+  size_t total_no_stage;   // what a run that issues no batched recomputation needs (the no-allocation path)
+  int stage_steps;         // internal states the stage holds
 };
+
+// Internal states the recomputation stage holds: as many steps as a sweep launch carries, within
+// 48 MiB; none where no backward-only sweep launch could consume them.
+constexpr size_t STAGE_MAX_BYTES = (size_t)48 << 20;
+int recompute_stage_steps(const Dims& d) {
+  if (!can_run_forward_batch(d) || !can_run_backward_sweep(d)) return 0;
+  const size_t state_bytes = 3 * d.unit * sizeof(float);
+  const int n = (int)std::min<size_t>(STAGE_MAX_BYTES / state_bytes, (size_t)std::min(sweep_max_steps(), forward_batch_max_steps()));
+  return n >= 4 ? n : 0;
+}
 
 Workspace layout(const Dims& d) {
   Workspace w{};
@@ -53,6 +65,9 @@ Workspace layout(const Dims& d) {
   for (int i = 0; i < 2; ++i) w.dGT[i] = take((size_t)d.G4 * d.KC * op);
   for (int i = 0; i < 2; ++i) w.aT[i] = take((size_t)d.NA * d.KC * op);
   w.ring = take(can_run_forward_chain(d) ? forward_chain_ring_bytes(d) : 0);
+  w.total_no_stage = off;
+  w.stage_steps = recompute_stage_steps(d);
+  w.stage = take((size_t)w.stage_steps * 3 * unit);   // last: nothing ever clears it
   w.total = off;
   return w;
 }
@@ -93,6 +108,7 @@ struct Profiler {
     int64_t n = 0;
   } open;
   int64_t launches[MEBPTT_K_CLASSES] = {};
+  int64_t sweep_forward_steps = 0;   // forward operations carried by sweep launches
   std::vector<Sample> pending;
   std::vector<Sample> runs;   // whole forward runs, one event pair around many launches
   std::vector<hipEvent_t> pool;
@@ -313,6 +329,8 @@ int mebptt_profile_collect(mebptt_profile* out) {
     out->launches[c] = p.launches[c];
     p.launches[c] = 0;
   }
+  out->sweep_forward_steps = p.sweep_forward_steps;
+  p.sweep_forward_steps = 0;
   int rc = MEBPTT_OK;
   for (Sample& s : p.runs) {
     float ms = 0.0f;
@@ -326,6 +344,9 @@ int mebptt_profile_collect(mebptt_profile* out) {
     } else if (s.cls == MEBPTT_K_SWEEP) {
       out->sweep_steps += s.launches;
       out->sweep_ms += ms;
+    } else if (s.cls == MEBPTT_K_FWD_BATCH) {
+      out->batch_steps += s.launches;
+      out->batch_ms += ms;
     } else {
       out->forward_run_launches += s.launches;
       out->forward_run_ms += ms;
@@ -402,7 +423,7 @@ int mebptt_prepare(const mebptt_lstm_desc* desc, const float* W_ih, const float*
   HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] {
     return launch_prep_weights(d, W_ih, W_hh, b, ws + w.Wp, reinterpret_cast<float*>(ws + w.bp), ws + w.WTh, ws + w.WTx, st);
   }));
-  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
+  HIP_TRY(timed(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total_no_stage - w.dc, st); }));
   remember_prepared(workspace, d);
   return MEBPTT_OK;
 }
@@ -607,7 +628,7 @@ int mebptt_run_static(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan, c
                       float* y_out, mebptt_stats* stats, void* stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
-  const size_t need = layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).total;
+  const size_t need = layout(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell)).total_no_stage;
   if (need > MEBPTT_STATIC_WORKSPACE_BYTES)
     return set_error(MEBPTT_EWORKSPACE, "this shape needs %zu bytes of workspace; the static scratch holds %zu", need,
                      (size_t)MEBPTT_STATIC_WORKSPACE_BYTES);
@@ -640,8 +661,9 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
                      mebptt_slot_pool_bytes(desc, plan));
   const Dims d = make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell);
   const Workspace w = layout(d);
-  if (workspace_bytes < w.total)
-    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  const size_t ws_need = mode == RUN_STATIC ? w.total_no_stage : w.total;   // the no-allocation path never uses the stage
+  if (workspace_bytes < ws_need)
+    return set_error(MEBPTT_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws_need);
   if (misaligned(slots, ALIGN) || misaligned(workspace, ALIGN))
     return set_error(MEBPTT_EWORKSPACE, "slots and workspace must be 256-byte aligned");
   const void* f32ptrs[] = {W_ih, W_hh, b, x, dy, h0, c0, dW_ih, dW_hh, db, dh0, dc0, dx, y_out};
@@ -710,7 +732,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // Set-up: operand copies of the weights, zeroed staging (the padding must stay zero), start state.
   if (mode != RUN_PREPARED) {
     HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_prep_weights(d, W_ih, W_hh, b, Wp, bp, WTh, WTx, st); }));
-    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total - w.dc, st); }));
+    HIP_TRY(tm(MEBPTT_K_SETUP, st, [&] { return launch_fill_zero(ws + w.dc, w.total_no_stage - w.dc, st); }));
   } else {
     // The staging keeps what the previous run left.  Only the running gradient plane must start
     // at zero, and -- when the last chunk in time is short and its K is padded -- the operand
@@ -852,6 +874,12 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
            b.dst == MEBPTT_LOC_CORE && b.src == f.src && b.step == f.step;
   };
 
+  // Where backward-only sweep launches exist but sweep launches with forward operations do not (the
+  // weights of both directions do not fit on the chip together), runs of such pairs are recomputed
+  // as a batch: see the main loop.
+  constexpr bool BATCH_OVER_SWEEP = false;   // shapes that have both: the sweep launch with forward operations
+  const bool batch_ok = resident_ok && can_run_backward_sweep(d) && w.stage_steps >= 2 &&
+                        (BATCH_OVER_SWEEP || !can_run_sweep(d));
   // Backward operations through internal states that earlier launches stored in slots (internal-state
   // pushes; store-everything BPTT): consecutive ones go out as backward-only sweep launches.
   const bool bsweep_ok = resident_ok && can_run_backward_sweep(d);
@@ -902,7 +930,10 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       HIP_TRY(hipEventRecord(smp.stop, st));
       g_prof.runs.push_back(smp);
     }
-    if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_SWEEP];
+    if (use_profiler && g_prof.every_n > 0) {
+      ++g_prof.launches[MEBPTT_K_SWEEP];
+      if (!states) g_prof.sweep_forward_steps += n;
+    }
     chain_base += forward_chain_arrivals(n);
     ++chain_launches;
     bwd += n;
@@ -931,6 +962,51 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         rc = issue_sweep(s_hi, n, srcs, states);
         if (rc) return rc;
         oi += (size_t)n;
+        continue;
+      }
+    }
+    if (batch_ok && pair_at(oi)) {
+      // A run of such pairs for steps going down inside one chunk, every step's input state in a
+      // slot: the forward operations do not depend on each other and go out as one launch that
+      // leaves the internal states in the stage; one backward-only sweep launch then consumes them.
+      const int s_hi = op.step, chunk = (s_hi - 1) / CH;
+      const int n_max = std::min(sweep_max_steps(), w.stage_steps);
+      int n = 0;
+      const float *srcs[64], *xs[64], *states[64];
+      float* dsts[64];
+      while (n < n_max && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - n &&
+             ops[oi + 2 * (size_t)n].src >= 0 && (s_hi - n - 1) / CH == chunk) {
+        srcs[n] = loc(ops[oi + 2 * (size_t)n].src);
+        xs[n] = x + (size_t)(s_hi - n - 1) * d.B * d.I;
+        dsts[n] = reinterpret_cast<float*>(ws + w.stage) + (size_t)n * 3 * unit;
+        states[n] = dsts[n];
+        ++n;
+      }
+      if (n >= 2) {
+        if (have_pending) {
+          rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
+          if (rc) return rc;
+        }
+        for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
+        const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+        if (use_profiler) HIP_TRY(close_group());
+        Sample smp{MEBPTT_K_FWD_BATCH, nullptr, nullptr, n};
+        if (bracket) {
+          smp.start = g_prof.get();
+          smp.stop = g_prof.get();
+          if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+          HIP_TRY(hipEventRecord(smp.start, st));
+        }
+        HIP_TRY(launch_forward_batch(d, Wp, bp, n, xs, srcs, dsts, st));
+        if (bracket) {
+          HIP_TRY(hipEventRecord(smp.stop, st));
+          g_prof.runs.push_back(smp);
+        }
+        if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_FWD_BATCH];
+        fwd += n;
+        rc = issue_sweep(s_hi, n, srcs, states);
+        if (rc) return rc;
+        oi += 2 * (size_t)n;
         continue;
       }
     }

@@ -36,7 +36,7 @@ def test_size_queries():
     p = mb.mebptt_plan(1000, 100, mb.ISM)
     assert mb.mebptt_slot_pool_bytes(d, p) == 100 * 4 * unit
     ws = mb.mebptt_workspace_bytes(d)
-    assert 0 < ws < 128 << 20
+    assert 0 < ws < 192 << 20          # operand copies, chunk buffers of the batched GEMMs, recomputation stage (<= 48 MiB)
     # independent of t
     assert mb.mebptt_workspace_bytes(mb.make_desc(64, 256, 1024, 7, 1, 0, 1)) == ws
     assert mb.mebptt_units_for_bytes(d, mb.MSM, 4_000_000_000) == 4_000_000_000 // unit

@@ -84,8 +84,9 @@ def test_chain_launch_count_and_status():
     assert prof.launches[mb.K_CHAIN] <= (w.t + 47) // 48 + 1
     assert prof.sweep_steps >= w.t - 40                    # and the way back as sweep launches, one per chunk of steps
     assert prof.launches[mb.K_SWEEP] <= (w.t + 31) // 32 + 1
-    assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.sweep_steps
-            == out.stats.forward_ops)
+    assert prof.sweep_forward_steps == prof.sweep_steps    # these sweep launches recompute the internal states themselves
+    assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.sweep_forward_steps
+            + prof.batch_steps == out.stats.forward_ops)
     assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == w.t
     # store-everything BPTT (an internal-state slot per step): the forward pass as chains, the backward pass
     # through the stored states as backward-only sweep launches
@@ -94,10 +95,46 @@ def test_chain_launch_count_and_status():
     out2 = s2.run_and_fetch()
     prof2 = mb.mebptt_profile_collect()
     mb.mebptt_profile_enable(0)
-    assert out2.stats.forward_ops == w.t and prof2.chain_steps >= w.t - 2
+    assert out2.stats.forward_ops == w.t and prof2.chain_steps >= w.t - 2 and prof2.sweep_forward_steps == 0
     assert prof2.sweep_steps >= w.t - 40 and prof2.launches[mb.K_BACKWARD] + prof2.sweep_steps == w.t
     for f in FIELDS:
         assert np.array_equal(getattr(out2, f), getattr(out, f)), f
+
+
+@pytest.mark.parametrize("B,I,H,t", [(64, 256, 1024, 70), (64, 120, 1024, 45), (128, 64, 1024, 40), (16, 30, 1024, 37)])
+def test_batched_recomputation(B, I, H, t):
+    """H = 1024: the weights of both directions do not fit on the chip together, so the way back
+    through a stretch of stored hidden states is one launch of independent forward operations (the
+    internal states of up to a chunk of steps, into the stage) followed by one backward-only sweep
+    launch.  The launches really are those, every forward operation is accounted for, and the
+    gradients are the per-step path's bit for bit and the oracle's within tolerance."""
+    from paper_1606_03401_amd.session import Session
+    from test_gpu_parity import TOL, check_against_oracle
+    w = wl.Workload("batch", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=t, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, dy_first_step=3, seed=400 + B)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    ref = ob.lstm_bptt(inp.W_ih, inp.W_hh, inp.b, inp.x, inp.h0, inp.c0, inp.dy, w.dy_first_step)
+    base = _run(w, inp, wl.KIND_HSM, t, chain=False)
+    for kind, m in ((wl.KIND_HSM, t), (wl.KIND_HSM, 9), (wl.KIND_HSM, 4), (wl.KIND_MSM, 30), (wl.KIND_ISM, t)):
+        s = Session(w, inp, kind=kind, m=m)
+        mb.mebptt_profile_enable(1)
+        out = s.run_and_fetch()
+        prof = mb.mebptt_profile_collect()
+        mb.mebptt_profile_enable(0)
+        assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+        _same(out, base, ("batched recomputation", kind, m))
+        assert prof.sweep_forward_steps == 0 and prof.sweep_steps > 0
+        assert prof.launches[mb.K_FWD_BATCH] <= prof.launches[mb.K_SWEEP]
+        assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.batch_steps
+                == out.stats.forward_ops)
+        assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == t
+        if kind == wl.KIND_HSM:
+            assert prof.batch_steps == prof.sweep_steps
+        if kind == wl.KIND_HSM and m == t:
+            assert prof.batch_steps >= t - 8     # all but single steps left over at chunk boundaries
+        if kind == wl.KIND_ISM:
+            assert prof.batch_steps == 0         # the internal states were stored on the way forward
+    check_against_oracle(w, inp, base, ref, TOL[w.gemm_dtype], label=f"batched recomputation {B}x{I}x{H}: ")
 
 
 def test_chains_from_two_host_threads():
