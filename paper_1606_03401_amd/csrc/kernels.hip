@@ -2191,6 +2191,13 @@ struct TgemmParams {
   int gx, gy;         // workgroup grid: i-blocks, j-blocks
   float* acc;         // tile-ordered accumulator
   int accumulate;     // 0: overwrite it, 1: add to it
+  // The first `full` workgroups (a multiple of the compute units) take one output block each over
+  // the whole of K; the blocks left over, too few for a round of their own, are shared out `split`
+  // ways along K so that the last round is short instead of mostly empty: part 0 adds into the
+  // block's place in `acc`, part q > 0 into `extra` block (q - 1) * (gx * gy - full) + (block - full).
+  // Which part sums what is fixed by the shape, so results do not depend on scheduling.
+  int full, split;
+  float* extra;
 };
 
 template <class T>
@@ -2204,11 +2211,25 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
   T* lds = reinterpret_cast<T*>(smem);    // [stage 2][macro step 2][16 tiles of A][FRAG]
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;   // scalar: see wave_index note
   const int wi = wave & 1, wj = wave >> 1;
-  const int total = p.gx * p.gy, id = (int)blockIdx.x;
-  const int xcd = id & 7;
-  const int work = xcd * (total >> 3) + min(xcd, total & 7) + (id >> 3);
+  const int id = (int)blockIdx.x;
+  int work, part = 0, nparts = 1;
+  if (id < p.full) {
+    const int xcd = id & 7;
+    work = xcd * (p.full >> 3) + min(xcd, p.full & 7) + (id >> 3);
+  } else {
+    work = p.full + (id - p.full) / p.split;
+    part = (id - p.full) % p.split;
+    nparts = p.split;
+  }
   const int bx = work / p.gy, by = work % p.gy;
-  const int nrounds = (p.nk + 1) >> 1;
+  // this workgroup's share of K: rounds [r0, r1) of two macro steps each
+  const int rounds_all = (p.nk + 1) >> 1;
+  const int r0 = part * rounds_all / nparts, r1 = (part + 1) * rounds_all / nparts;
+  const int nk = min(p.nk, 2 * r1) - 2 * r0;   // macro steps of the share (may be 0)
+  const int nrounds = (nk + 1) >> 1;
+  // a wave whose 128 x 64 outputs all lie outside the matrix (the last block of a ragged edge) only
+  // helps to stage A
+  const bool active = bx * WGT + wi * TI < p.mt_total && by * WGT + wj * TJ < p.nt_total;
   // A (the i operand, shared by the four waves of a row) goes L2 -> registers -> LDS: this wave
   // copies fragments f = wave*4 .. +4 of every round, f = ks * 16 + tile.  B (the j operand,
   // shared by two waves only) is fetched by each wave straight into its MFMA registers: LDS
@@ -2219,23 +2240,26 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
   for (int q = 0; q < 4; ++q) {
     const int f = wave * 4 + q, ks = f >> 4, tile = f & 15;
     ks_of[q] = ks;
-    srcA[q] = reinterpret_cast<const T*>(p.A) + ((size_t)min(bx * WGT + tile, p.mt_total - 1) * p.a_steps * 64 + lane) * VEC;
+    srcA[q] = reinterpret_cast<const T*>(p.A) + ((size_t)min(bx * WGT + tile, p.mt_total - 1) * p.a_steps * 64 + lane) * VEC +
+              (size_t)2 * r0 * FRAG;
   }
   const T* srcB[TJ];
 #pragma unroll
   for (int j = 0; j < TJ; ++j)
-    srcB[j] = reinterpret_cast<const T*>(p.B) + ((size_t)min(by * WGT + wj * TJ + j, p.nt_total - 1) * p.b_steps * 64 + lane) * VEC;
+    srcB[j] = reinterpret_cast<const T*>(p.B) + ((size_t)min(by * WGT + wj * TJ + j, p.nt_total - 1) * p.b_steps * 64 + lane) * VEC +
+              (size_t)2 * r0 * FRAG;
   u32x4 ringA[2][4];
   typename M::Frag ringB[2][2][TJ];   // [set][macro step of the round][tile]
   auto fetch = [&](int set, int round) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int s = min(round * 2 + ks_of[q], p.nk - 1);   // a macro step past the end is fetched (clamped) and never used
+      const int s = min(round * 2 + ks_of[q], nk - 1);   // a macro step past the end is fetched (clamped) and never used
       ringA[set][q] = *reinterpret_cast<const u32x4*>(srcA[q] + (size_t)s * FRAG);
     }
+    if (!active) return;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const int s = min(round * 2 + ks, p.nk - 1);
+      const int s = min(round * 2 + ks, nk - 1);
 #pragma unroll
       for (int j = 0; j < TJ; ++j) ringB[set][ks][j] = M::load(srcB[j] + (size_t)s * FRAG);
     }
@@ -2252,9 +2276,10 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
     for (int j = 0; j < TJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   auto compute = [&](int r, int stage, int set) {
+    if (!active) return;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      if (r * 2 + ks < p.nk) {   // uniform
+      if (r * 2 + ks < nk) {   // uniform
         const T* base = &lds[((size_t)stage * 32 + ks * 16) * FRAG + lane * VEC];
         // The wave's TI fragments of A come from LDS two ahead of the MFMAs that use them: two
         // reads, then TJ MFMAs and one more read in turn, so an LDS round trip always has eight
@@ -2303,7 +2328,9 @@ __global__ __launch_bounds__(512) void tgemm_kernel(TgemmParams p) {
   // Running sum in a tile-ordered accumulator: a wave's 32 tiles are one contiguous run and a
   // lane's four rows one float4, so the read-modify-write of every chunk is fully coalesced;
   // wgrad_finish_kernel converts it to the caller's row-major dW once at the end of the run.
-  float4* accp = reinterpret_cast<float4*>(p.acc) + (((size_t)(bx * p.gy + by) * 8 + wave) * (TI * TJ)) * 64 + lane;
+  if (!active) return;   // nobody reads blocks outside the matrix
+  const size_t block = part == 0 ? (size_t)work : (size_t)(part - 1) * (p.gx * p.gy - p.full) + (work - p.full);
+  float4* accp = reinterpret_cast<float4*>(part == 0 ? p.acc : p.extra) + ((block * 8 + wave) * (TI * TJ)) * 64 + lane;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {   // two batches of 16 tiles: the old values pass through few registers
     float4 old[TI * TJ / 2];
@@ -2338,8 +2365,18 @@ static hipError_t launch_tgemm(const TgemmParams& p, hipStream_t st) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  tgemm_kernel<T><<<dim3(p.gx * p.gy), dim3(512), TGEMM_LDS_BYTES, st>>>(p);
+  tgemm_kernel<T><<<dim3(p.full + (p.gx * p.gy - p.full) * p.split), dim3(512), TGEMM_LDS_BYTES, st>>>(p);
   return hipGetLastError();
+}
+
+// How the 256 x 256 output blocks are dealt out: whole rounds of one block per compute unit over all
+// of K, and the blocks left over split along K as many ways as fit one more round (at most four).
+constexpr int TGEMM_ROUND = 256;
+static void tgemm_shares(int blocks, int& full, int& split) {
+  full = blocks / TGEMM_ROUND * TGEMM_ROUND;
+  const int rest = blocks - full;
+  split = rest == 0 ? 1 : std::max(1, std::min(4, TGEMM_ROUND / rest));
+  if (split == 1) full = blocks;
 }
 
 // The weight gradient runs on the 256 x 256 tiles when the operands are bf16 and dW has enough tiles.
@@ -2533,7 +2570,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T* __restrict__ dGT, c
 // between the input and the recurrent side for the GRU (packed_gate_x / packed_gate_h).
 __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int grid_y, int nsplit, size_t split_stride,
                                     int NX, int HP, int I, int H, int cell, float* __restrict__ dW_ih,
-                                    float* __restrict__ dW_hh, float* __restrict__ db) {
+                                    float* __restrict__ dW_hh, float* __restrict__ db, int blocks) {
   const int ngates = cell ? 3 : 4;
   const size_t nih = (size_t)ngates * H * I, nhh = (size_t)ngates * H * H, nb = (size_t)(cell ? 6 : 4) * H;
   const size_t total = nih + nhh + nb;
@@ -2570,7 +2607,15 @@ __global__ void wgrad_finish_kernel(const float* __restrict__ dWacc, int WT, int
     if (WT == 0) {   // tgemm_kernel's blocks: 2 x 4 waves of 8 x 4 tiles per 256 x 256 workgroup
       const int wgx = mt >> 4, wi = (mt & 15) >> 3, ti = mt & 7;
       const int wgy = nt >> 4, wj = (nt & 15) >> 2, tj = nt & 3;
-      off = ((((size_t)(wgx * grid_y + wgy) * 8 + (wi + 2 * wj)) * 32 + (ti * 4 + tj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+      const size_t inner = (((size_t)(wi + 2 * wj) * 32 + (ti * 4 + tj)) * 64 + (lq * 16 + lrow)) * 4 + r;
+      const int block = wgx * grid_y + wgy, first_shared = (int)split_stride;
+      constexpr size_t BLOCK = 256 * 256;
+      float v = dWacc[(size_t)block * BLOCK + inner];
+      if (block >= first_shared)   // a block whose K was shared out: the other parts' sums, fixed order
+        for (int sp = 1; sp < nsplit; ++sp)
+          v += dWacc[((size_t)blocks + (size_t)(sp - 1) * (blocks - first_shared) + (block - first_shared)) * BLOCK + inner];
+      *dst = v;
+      continue;
     } else {
       const int wgx = mt / (2 * WT), wm = (mt % (2 * WT)) / WT, i = mt % WT;
       const int wgy = nt / (2 * WT), wn = (nt % (2 * WT)) / WT, jj = nt % WT;
@@ -2605,7 +2650,9 @@ static size_t wgrad_partial_floats(const Dims& d) {   // one partial accumulator
 size_t wgrad_accumulator_bytes(const Dims& d) {
   if (wgrad_uses_big_tiles(d)) {   // one padded 256 x 256 block per workgroup
     const size_t gx = (d.G4 / 16 + 15) / 16, gy = (d.NA / 16 + 15) / 16;
-    return gx * gy * 256 * 256 * sizeof(float);
+    int full, split;
+    tgemm_shares((int)(gx * gy), full, split);
+    return (gx * gy + (gx * gy - full) * (split - 1)) * 256 * 256 * sizeof(float);
   }
   return wgrad_partial_floats(d) * wgrad_splits(d) * sizeof(float);
 }
@@ -2637,6 +2684,8 @@ hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslo
     p.gy = (p.nt_total + 15) / 16;
     p.acc = dWacc;
     p.accumulate = accumulate;
+    tgemm_shares(p.gx * p.gy, p.full, p.split);
+    p.extra = dWacc + (size_t)p.gx * p.gy * 256 * 256;
     return launch_tgemm<__bf16>(p, st);
   }
   if (d.dtype)
@@ -2649,14 +2698,18 @@ hipError_t launch_wgrad(const Dims& d, const void* dGT, const void* aT, int nslo
 hipError_t launch_wgrad_finish(const Dims& d, const float* dWacc, float* dW_ih, float* dW_hh, float* db,
                                hipStream_t st) {
   if (wgrad_uses_big_tiles(d)) {
-    wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, 0, (d.NA / 16 + 15) / 16, 1, 0, d.NX, d.HP, d.I, d.H, d.cell,
-                                                          dW_ih, dW_hh, db);
+    const int gx = (d.G4 / 16 + 15) / 16, gy = (d.NA / 16 + 15) / 16;
+    int full, split;
+    tgemm_shares(gx * gy, full, split);
+    // nsplit and split_stride: here the shares of the left-over blocks and the first of those blocks
+    wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, 0, gy, split, (size_t)full, d.NX, d.HP, d.I, d.H, d.cell,
+                                                          dW_ih, dW_hh, db, gx * gy);
     return hipGetLastError();
   }
   const int WT = wgrad_wave_tile(d);
   const int grid_y = (d.NA / 16 + 2 * WT - 1) / (2 * WT);
   wgrad_finish_kernel<<<dim3(2048), dim3(256), 0, st>>>(dWacc, WT, grid_y, wgrad_splits(d), wgrad_partial_floats(d), d.NX, d.HP,
-                                                        d.I, d.H, d.cell, dW_ih, dW_hh, db);
+                                                        d.I, d.H, d.cell, dW_ih, dW_hh, db, 0);
   return hipGetLastError();
 }
 
