@@ -334,8 +334,11 @@ def measure(w, inp, *, kind=None, m=None, steps=3, warmup=1, graph=True, profile
                 # so the launch is placed on the MFMA roof
                 us = classes[dom]["us_per_forward_op"]
                 tf = forward_flops(w) / (us * 1e-6) / 1e12
+                per_launch = pmc_traffic(w.name, kernel)   # HBM bytes of a whole chain launch (counter summary)
+                ops_per_launch = prof.chain_steps / max(prof.launches[mb.K_CHAIN], 1)
                 out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": tf, "peak": peak_tf, "unit": "TFLOP/s",
-                                   "frac": tf / peak_tf, "traffic": None, "avg_launch_us": us,
+                                   "frac": tf / peak_tf, "traffic": per_launch / ops_per_launch if per_launch else None,
+                                   "traffic_per_chain_launch": per_launch, "avg_launch_us": us,
                                    "flops_per_launch": forward_flops(w), "note": "per forward operation inside a chain launch"}
             elif dom == "forward batch":
                 # independent forward operations: a dense contraction over all their sequences at once
