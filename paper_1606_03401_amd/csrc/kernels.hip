@@ -1457,14 +1457,12 @@ static const ResConfig RES_CONFIGS[] = {
     {1, 2, 0, 4, 1, 1}, {1, 2, 0, 4, 2, 1},   // H = 128, I <= 128
 };
 
-// Index into RES_CONFIGS for this shape, or -1 when the chain kernel does not apply.
-static int resident_config(const Dims& d) {
-  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H) return -1;
-  const int nsteps = d.KP / 32;
-  const FwdConfig fc = forward_config<__bf16>(d);
-  const int ks = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;   // the K split of the per-step kernels
-  if (nsteps % ks != 0) return -1;
-  const int nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+// The batch is dealt to the XCDs in groups of nb consecutive sequences.  An even share,
+// nb = ceil(B / 8), keeps every XCD busy but may make a group straddle more 16-sequence MFMA tiles
+// than a kernel is instantiated for; the share rounded up to whole tiles never straddles (some XCDs
+// then get no sequences and only keep the meeting going).  group_tiles: batch tiles the widest group
+// touches; the configuration look-ups try the even share first.
+static int group_tiles(const Dims& d, int nb) {
   int nbt = 1;
   for (int g = 0; g < RES_GROUPS; ++g) {
     const int lo = g * nb, hi = (lo + nb < d.B ? lo + nb : d.B);
@@ -1472,10 +1470,30 @@ static int resident_config(const Dims& d) {
     const int span = (hi - 1) / 16 - lo / 16 + 1;
     nbt = span > nbt ? span : nbt;
   }
-  for (size_t i = 0; i < sizeof RES_CONFIGS / sizeof RES_CONFIGS[0]; ++i) {
-    const ResConfig& c = RES_CONFIGS[i];
-    if (c.nrt == d.H / 128 && c.ks == ks && c.nsw == nsteps / ks && c.nbt == nbt && c.nsxw == (d.KX / 32 + ks - 1) / ks)
-      return (int)i;
+  return nbt;
+}
+static int group_share(const Dims& d, int candidate) {
+  const int even = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  return candidate == 0 ? even : round_up(even, 16);
+}
+
+// Index into RES_CONFIGS for this shape, or -1 when the chain kernel does not apply; *nb_out = the
+// sequences per XCD to launch it with.
+static int resident_config(const Dims& d, int* nb_out = nullptr) {
+  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H) return -1;
+  const int nsteps = d.KP / 32;
+  const FwdConfig fc = forward_config<__bf16>(d);
+  const int ks = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;   // the K split of the per-step kernels
+  if (nsteps % ks != 0) return -1;
+  for (int cand = 0; cand < 2; ++cand) {
+    const int nb = group_share(d, cand), nbt = group_tiles(d, nb);
+    for (size_t i = 0; i < sizeof RES_CONFIGS / sizeof RES_CONFIGS[0]; ++i) {
+      const ResConfig& c = RES_CONFIGS[i];
+      if (c.nrt == d.H / 128 && c.ks == ks && c.nsw == nsteps / ks && c.nbt == nbt && c.nsxw == (d.KX / 32 + ks - 1) / ks) {
+        if (nb_out) *nb_out = nb;
+        return (int)i;
+      }
+    }
   }
   return -1;
 }
@@ -1504,7 +1522,8 @@ static hipError_t launch_chain_cfg(const ResParams& p, hipStream_t st) {
 hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, const float* x_first, const float* src_unit,
                                 const ChainStep* steps, int count, void* ring, unsigned* sync, unsigned base,
                                 unsigned launch, hipStream_t st) {
-  const int cfg = resident_config(d);
+  int nb = 0;
+  const int cfg = resident_config(d, &nb);
   if (cfg < 0 || count < 1 || count > RES_MAX_STEPS) return hipErrorInvalidValue;
   ResParams p{};
   p.Wp = Wp;
@@ -1523,7 +1542,7 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
   p.KX = d.KX;
   p.KH = d.KH;
   p.BP = d.BP;
-  p.nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  p.nb = nb;
   p.unit = d.unit;
   for (int j = 0; j < count; ++j) p.step[j] = ResStep{steps[j].out, steps[j].gates};
   switch (cfg) {
@@ -1936,28 +1955,26 @@ static const SweepConfig SWEEP_CONFIGS[] = {
 };
 constexpr int SWEEP_BACKWARD_ONLY_FROM = 6;   // configurations from this index on have no forward part
 
-static int sweep_config(const Dims& d) {
+static int sweep_config(const Dims& d, int* nb_out = nullptr) {
   if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;
   const int nstepsF = d.KP / 32, nstepsB = d.G4 / 32;
   const FwdConfig fc = forward_config<__bf16>(d);
   const int ksf = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;
   const int ksb = backward_config<__bf16>(d) == BWD_SMALLK ? 4 : 8;
   if (nstepsB % ksb != 0) return -1;
-  const int nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
-  int nbt = 1;
-  for (int g = 0; g < RES_GROUPS; ++g) {
-    const int lo = g * nb, hi = (lo + nb < d.B ? lo + nb : d.B);
-    if (lo >= d.B) break;
-    const int span = (hi - 1) / 16 - lo / 16 + 1;
-    nbt = span > nbt ? span : nbt;
-  }
-  for (size_t i = 0; i < sizeof SWEEP_CONFIGS / sizeof SWEEP_CONFIGS[0]; ++i) {
-    const SweepConfig& c = SWEEP_CONFIGS[i];
-    if (c.nrt != d.H / 128 || c.ksb != ksb || c.nswb != nstepsB / ksb || c.nbt != nbt) continue;
-    // the forward part fixes the width of x as well; a backward-only launch never reads x
-    if ((int)i >= SWEEP_BACKWARD_ONLY_FROM ||
-        (d.I % 8 == 0 && nstepsF % ksf == 0 && c.ksf == ksf && c.nswf == nstepsF / ksf && c.nsxw == (d.KX / 32 + ksf - 1) / ksf))
-      return (int)i;
+  for (int cand = 0; cand < 2; ++cand) {
+    const int nb = group_share(d, cand), nbt = group_tiles(d, nb);
+    for (size_t i = 0; i < sizeof SWEEP_CONFIGS / sizeof SWEEP_CONFIGS[0]; ++i) {
+      const SweepConfig& c = SWEEP_CONFIGS[i];
+      if (c.nrt != d.H / 128 || c.ksb != ksb || c.nswb != nstepsB / ksb || c.nbt != nbt) continue;
+      // the forward part fixes the width of x as well; a backward-only launch never reads x
+      if ((int)i >= SWEEP_BACKWARD_ONLY_FROM ||
+          (d.I % 8 == 0 && nstepsF % ksf == 0 && c.ksf == ksf && c.nswf == nstepsF / ksf &&
+           c.nsxw == (d.KX / 32 + ksf - 1) / ksf)) {
+        if (nb_out) *nb_out = nb;
+        return (int)i;
+      }
+    }
   }
   return -1;
 }
@@ -1985,7 +2002,8 @@ static hipError_t launch_sweep_cfg(const SweepParams& p, hipStream_t st) {
 }
 
 hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
-  const int cfg = sweep_config(d);
+  int nb = 0;
+  const int cfg = sweep_config(d, &nb);
   if (cfg < 0 || a.count < 1 || a.count > SWEEP_MAX_STEPS) return hipErrorInvalidValue;
   if ((a.s_hi - 1) / d.CH != (a.s_hi - a.count) / d.CH) return hipErrorInvalidValue;   // one chunk per launch
   SweepParams p{};
@@ -2014,7 +2032,7 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   p.KX = d.KX;
   p.KH = d.KH;
   p.BP = d.BP;
-  p.nb = (d.B + RES_GROUPS - 1) / RES_GROUPS;
+  p.nb = nb;
   p.G4 = d.G4;
   p.NX = d.NX;
   p.KC = d.KC;

@@ -101,7 +101,7 @@ def test_chain_launch_count_and_status():
         assert np.array_equal(getattr(out2, f), getattr(out, f)), f
 
 
-@pytest.mark.parametrize("B,I,H,t", [(64, 256, 1024, 70), (64, 120, 1024, 45), (128, 64, 1024, 40), (16, 30, 1024, 37)])
+@pytest.mark.parametrize("B,I,H,t", [(64, 256, 1024, 70), (64, 120, 1024, 45), (128, 64, 1024, 40), (16, 30, 1024, 37), (100, 120, 1024, 45)])
 def test_batched_recomputation(B, I, H, t):
     """H = 1024: the weights of both directions do not fit on the chip together, so the way back
     through a stretch of stored hidden states is one launch of independent forward operations (the
