@@ -752,10 +752,14 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   }));
   if (plan->kind != MEBPTT_ISM) touch(0, 1);
 
-  // The time-batched GEMMs go to the side stream, or -- in the no-allocation path, which creates
-  // no stream and no event -- stay on the caller's stream in the same order.
+  // The time-batched GEMMs go to the side stream where the sequential work runs as resident
+  // launches (they then fill the gaps those launches leave: measured 1 % faster on H = 1024).
+  // Beside launch-per-step kernels, which fill the device on their own, the two only get in each
+  // other's way (H = 2048: 2.8 % slower, H = 4096: 1.4 %), so there -- and in the no-allocation
+  // path, which creates no stream and no event -- they stay on the caller's stream in the same order.
+  const bool resident_ok = mode != RUN_STATIC && g_chain_enabled && device_fits_resident_launches();
   SideStream* side = nullptr;
-  if (mode != RUN_STATIC) HIP_TRY(get_side_stream(&side));
+  if (resident_ok && (can_run_forward_chain(d) || can_run_backward_sweep(d))) HIP_TRY(get_side_stream(&side));
   hipStream_t st2 = side ? side->stream : st;
   bool pending[2] = {false, false};   // side-stream work on chunk buffer i not yet joined
   int cur_chunk = -1;
@@ -835,7 +839,6 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // chain goes out as forward-chain launches of up to forward_chain_max_steps() steps instead of
   // one launch per step.  Not in the no-allocation path, which owns no event to keep two such runs
   // from overlapping on the device.
-  const bool resident_ok = mode != RUN_STATIC && g_chain_enabled && device_fits_resident_launches();
   const bool chain_ok = resident_ok && can_run_forward_chain(d);
   constexpr int CHAIN_MIN_STEPS = 2;     // two steps in one launch already beat two launches (measured on the paper's 256-wide model)
   unsigned chain_base = 0;        // arrivals left in the group counters by this run's earlier chain launches
