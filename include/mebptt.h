@@ -270,8 +270,11 @@ size_t mebptt_slot_pool_bytes(const mebptt_lstm_desc* desc, const mebptt_plan_t*
  * RNN core available for intermediate calculations, able to store a single internal state":
  * that is the working core and the two transient hidden states here.  The rest is what this
  * implementation adds around it: operand copies of the weights in the GEMM type, the running
- * gradients, a dW accumulator, and staging of dG / [x; h] for the steps of two chunks of the
- * time-batched weight-gradient GEMM.  Independent of t and of the budget. */
+ * gradients, a dW accumulator, staging of dG / [x; h] for the steps of two chunks of the
+ * time-batched weight-gradient GEMM and, on shapes where the way back through a stretch of stored
+ * hidden states recomputes the stretch's internal states in one launch (bf16 LSTM, H = 1024), a
+ * stage for those internal states (at most 32 of them and at most 48 MiB).  Independent of t and
+ * of the budget. */
 size_t mebptt_workspace_bytes(const mebptt_lstm_desc* desc);
 /* Largest budget, in the given kind's unit, whose slot pool fits in budget_bytes (0 if none). */
 int32_t mebptt_units_for_bytes(const mebptt_lstm_desc* desc, int32_t kind, size_t budget_bytes);
@@ -381,7 +384,8 @@ int mebptt_shutdown(void);
  * MEBPTT_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the process ends.
  * The call creates no stream and no event and allocates nothing: every kernel, including the
  * time-batched GEMMs, is enqueued on `stream` in schedule order; the measurement hooks are
- * ignored.  Results are bit-identical to mebptt_run's.  Shapes whose mebptt_workspace_bytes()
+ * ignored.  Results are bit-identical to mebptt_run's.  Shapes whose workspace (as
+ * mebptt_workspace_bytes() counts it, less the recomputation stage, which this path never uses)
  * exceeds the array are refused with EWORKSPACE before anything is enqueued.  All calls on one
  * GPU share the array, which keeps the previous call's contents (the call clears what must start
  * at zero): calls whose device work overlaps on one GPU race -- keep them on one stream or
@@ -405,7 +409,8 @@ enum {
   MEBPTT_K_SETUP = 4,    /* operand copies of the weights, zero fills, start-state copy       */
   MEBPTT_K_PAIR = 5,     /* one launch carrying a backward step and an independent forward op */
   MEBPTT_K_CHAIN = 6,    /* one launch carrying a chain of forward operations, weights resident  */
-  MEBPTT_K_SWEEP = 7,    /* one launch carrying a run of (forward, backward) pairs, weights resident */
+  MEBPTT_K_SWEEP = 7,    /* one launch carrying a run of backward steps (with or without the forward
+                            operations that recompute their internal states), weights resident */
   MEBPTT_K_FWD_BATCH = 8, /* one launch carrying forward operations that do not depend on each other */
   MEBPTT_K_CLASSES = 9
 };
@@ -422,7 +427,7 @@ typedef struct {
   /* Forward-chain launches are all bracketed: forward operations they carried, and their time. */
   int64_t chain_steps;
   double chain_ms;
-  /* Likewise the sweep launches: (forward, backward) pairs they carried, and their time. */
+  /* Likewise the sweep launches: backward steps they carried, and their time. */
   int64_t sweep_steps;
   double sweep_ms;
   int64_t sampled_groups[MEBPTT_K_CLASSES]; /* event brackets behind `sampled` and `sampled_ms` */

@@ -34,10 +34,12 @@ struct Workspace {
 };
 
 // Internal states the recomputation stage holds: as many steps as a sweep launch carries, within
-// 48 MiB; none where no backward-only sweep launch could consume them.
+// 48 MiB; none where no backward-only sweep launch could consume them, and none on shapes that have
+// the sweep launch with forward operations, which is the faster way there (H = 512, B = 256: 171 ms
+// against 189 ms per gradient step).
 constexpr size_t STAGE_MAX_BYTES = (size_t)48 << 20;
 int recompute_stage_steps(const Dims& d) {
-  if (!can_run_forward_batch(d) || !can_run_backward_sweep(d)) return 0;
+  if (!can_run_forward_batch(d) || !can_run_backward_sweep(d) || can_run_sweep(d)) return 0;
   const size_t state_bytes = 3 * d.unit * sizeof(float);
   const int n = (int)std::min<size_t>(STAGE_MAX_BYTES / state_bytes, (size_t)std::min(sweep_max_steps(), forward_batch_max_steps()));
   return n >= 4 ? n : 0;
@@ -879,10 +881,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
 
   // Where backward-only sweep launches exist but sweep launches with forward operations do not (the
   // weights of both directions do not fit on the chip together), runs of such pairs are recomputed
-  // as a batch: see the main loop.
-  constexpr bool BATCH_OVER_SWEEP = false;   // shapes that have both: the sweep launch with forward operations
-  const bool batch_ok = resident_ok && can_run_backward_sweep(d) && w.stage_steps >= 2 &&
-                        (BATCH_OVER_SWEEP || !can_run_sweep(d));
+  // as a batch: see the main loop.  (The workspace has a stage exactly on those shapes.)
+  const bool batch_ok = resident_ok && can_run_backward_sweep(d) && w.stage_steps >= 2;
   // Backward operations through internal states that earlier launches stored in slots (internal-state
   // pushes; store-everything BPTT): consecutive ones go out as backward-only sweep launches.
   const bool bsweep_ok = resident_ok && can_run_backward_sweep(d);
