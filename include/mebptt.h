@@ -340,12 +340,16 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
  * single-step pushes of a sub-sequence that fits into memory) are issued as "forward-chain"
  * launches where the shape allows it (bf16 operands, LSTM, H a multiple of 128 and gate weights
  * that fit into the registers and LDS of one XCD's compute units): one launch then carries up to
- * 48 steps, keeps the gate weights on the chip, splits the batch over the 8 XCDs and lets the 32
+ * 192 steps, keeps the gate weights on the chip, splits the batch over the 8 XCDs and lets the 32
  * compute units of an XCD exchange h through their shared L2.  Where the transposed recurrent
  * weights fit as well (H = 128, 256, 512 with I <= H/4 .. H), the runs of "forward operation keeping
  * the internal state, then backward operation" that end every sub-sequence are issued the same way
- * ("sweep" launches, up to 32 pairs, internal states never leaving the registers).  Results are
- * bit-identical to the launch-per-step path.  Such a launch assumes that its 256 workgroups are all resident and dealt
+ * ("sweep" launches, up to 32 pairs, internal states never leaving the registers).  Where only the
+ * transposed recurrent weights fit (H = 1024), the forward operations of such a run -- they do not
+ * depend on each other, every input state being in a slot already -- go out as one "forward-batch"
+ * launch that leaves the internal states in the workspace's stage, followed by one sweep launch of
+ * backward operations on them; backward operations on internal states stored in slots go out as
+ * such sweep launches as well.  Results are bit-identical to the launch-per-step path.  Such a launch assumes that its 256 workgroups are all resident and dealt
  * round-robin to the XCDs; each workgroup checks this, every wait inside is bounded by a wall
  * clock, and a launch that cannot proceed gives up and raises a status word in the workspace
  * instead of hanging.  mebptt_run_status copies that word to *status (host) after waiting for

@@ -1158,7 +1158,7 @@ hipError_t launch_backward_forward_pair(const Dims& d, const BackwardArgs& a, co
 // an assumption that does not hold.
 // Sums are formed exactly as forward_body forms them (KS partial sums over the macro steps
 // w, w+KS, ..., added in the order 0..KS-1), so a step gives the same bits either way.
-constexpr int RES_MAX_STEPS = 48;   // steps of one launch: their destinations travel as kernel arguments
+constexpr int RES_MAX_STEPS = 192;  // steps of one launch: their destinations travel as kernel arguments (3 KiB of the 4 KiB there are)
 constexpr int RES_RING = 4;         // h slices in flight (two would do: a step ahead at most)
 constexpr int RES_WGS = 256, RES_GROUPS = 8, RES_MEMBERS = RES_WGS / RES_GROUPS;
 constexpr long long RES_WAIT_TICKS = 50000000;   // 0.5 s of the 100 MHz wall clock

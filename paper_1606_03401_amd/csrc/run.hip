@@ -1075,7 +1075,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         rc = order_resident_launches();
         if (rc) return rc;
         const int max_steps = forward_chain_max_steps();
-        ChainStep cs[64];
+        ChainStep cs[256];   // >= forward_chain_max_steps()
         while (fi < total) {
           const int n = (int)std::min<size_t>(total - fi, (size_t)max_steps);
           for (int j = 0; j < n; ++j) {
