@@ -195,3 +195,30 @@ def test_bounded_waits_give_up_and_report():
     finally:
         mb.mebptt_resident_wait_limit(-1)
     _same(s.run_and_fetch(), good, "after restoring the bound")
+
+
+@pytest.mark.parametrize("B,I,H,t,m", [(64, 128, 128, 70, 6), (64, 256, 1024, 45, 8)])
+def test_resident_launches_in_a_captured_graph(B, I, H, t, m):
+    """A run whose sequential work goes out as chain, sweep and forward-batch launches, captured into
+    a HIP graph: every replay -- with eager runs, clobbered outputs and synchronisations between
+    them -- reproduces the eager result bit for bit and leaves the status word clear (the arrival
+    counters the captured launches count on are cleared by the run's own first kernel)."""
+    import torch
+    from paper_1606_03401_amd.session import Session
+    w = wl.Workload("graph-resident", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=m, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, seed=610 + H)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    base = _run(w, inp, wl.KIND_HSM, m, chain=False)
+    s = Session(w, inp)
+    eager = s.run_and_fetch()
+    _same(eager, base, "eager")
+    s.capture()
+    for rep in range(4):
+        for tsr in (s.dW_ih, s.dW_hh, s.db, s.dh0, s.dc0, s.dx, s.y):
+            tsr.fill_(float("nan"))
+        torch.cuda.synchronize()
+        s.replay()
+        _same(s.fetch(), eager, ("replay", rep))
+        assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+        if rep % 2 == 0:          # the program's own eager work between replays
+            _same(s.run_and_fetch(), eager, ("eager after replay", rep))
