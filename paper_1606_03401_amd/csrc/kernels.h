@@ -167,6 +167,12 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st);
 
 // out[slot*B + b][n] = sum_k dG[slot*BP + b][k] * WT[n][k] for slot < nslots, b < B, n < N;
 // ld_out = row stride of out.  Used for dx (WT = WTx, N = I) and for dh_0 (WT = WTh, N = H).
+// dx of a chunk of steps: launch_dgrad_gemm(WTx, I, ...) on most shapes; where the output has few
+// 256 x 256 blocks and K = 4H is long, the blocked GEMM with every block's K shared out, its partial
+// blocks in `scratch` (device memory the caller lends until the call's work is done; contents lost).
+bool dx_gemm_uses_blocks(const Dims& d, size_t scratch_bytes);
+hipError_t launch_dx_gemm(const Dims& d, const void* WTx, const void* dG, int nslots, float* dx, void* scratch,
+                          size_t scratch_bytes, hipStream_t st);
 hipError_t launch_dgrad_gemm(const Dims& d, const void* WT, int N, const void* dG, int nslots, float* out,
                              int ld_out, hipStream_t st);
 

@@ -2397,6 +2397,94 @@ static void tgemm_shares(int blocks, int& full, int& split) {
   if (split == 1) full = blocks;
 }
 
+// ---- dx GEMM on the 256 x 256 blocks ---------------------------------------------------------
+// dx[(step, b)][n] = sum_k dG[(step, b)][k] W_ih^T[n][k] over a chunk of steps has few output blocks
+// (cfg3: 2 x 16) and a long K = 4H, so every block's K is shared out over `split` workgroups, each
+// writing its partial block; dx_finish_kernel adds the parts in a fixed order and stores the rows
+// of real sequences.  The partial blocks live in a scratch buffer the caller lends (the chunk's
+// dG^T buffer, which nobody reads between this chunk's dW GEMM and the next chunk that fills it).
+// Used when that gives the chip at least 192 workgroups with at least 16 macro steps each.
+constexpr int DX_MAX_SPLIT = 8;
+struct DxBlocks {
+  int gx, gy, split;   // blocks along n, along the rows of a full chunk, K shares per block (0: not used)
+};
+static DxBlocks dx_blocks(const Dims& d, size_t scratch_bytes) {
+  DxBlocks b{0, 0, 0};
+  if (!d.dtype || d.NX < 256) return b;
+  b.gx = (d.NX / 16 + 15) / 16;
+  b.gy = (d.CH * d.BP / 16 + 15) / 16;
+  const int blocks = b.gx * b.gy, nk = d.G4 / 32;
+  const size_t fit = scratch_bytes / ((size_t)blocks * 256 * 256 * sizeof(float));
+  const int split = (int)std::min<size_t>(std::min(DX_MAX_SPLIT, std::min(TGEMM_ROUND / blocks, nk / 16)), fit);
+  if (split >= 1 && blocks * split >= 192) b.split = split;
+  return b;
+}
+
+// partial[part][block][wave][tile][lane] (tgemm_kernel's accumulator order) -> dx rows.  One thread
+// per float4 of a block: four consecutive n of one (step, b) row.
+__global__ void dx_finish_kernel(const float4* __restrict__ partial, int blocks, int split, int gy, int nrows, int B, int BP,
+                                 int I, float* __restrict__ out, int ld_out) {
+  const size_t total = (size_t)blocks * (256 * 256 / 4), stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+    const int lane = (int)(idx & 63), tile = (int)((idx >> 6) & 31), wave = (int)((idx >> 11) & 7);
+    const int block = (int)(idx >> 14);
+    const int bx = block / gy, by = block % gy;
+    const int wi = wave & 1, wj = wave >> 1, ti = tile >> 2, tj = tile & 3;
+    const int n = ((bx * 16 + wi * 8 + ti) * 16) + 4 * (lane >> 4);
+    const int row = ((by * 16 + wj * 4 + tj) * 16) + (lane & 15);   // padded row: slot * BP + b
+    const int slot = row / BP, b = row % BP;
+    if (row >= nrows || b >= B || n >= I) continue;
+    float4 u[DX_MAX_SPLIT];   // all parts fetched before the first addition: the loads overlap
+#pragma unroll
+    for (int q = 0; q < DX_MAX_SPLIT; ++q)
+      if (q < split) u[q] = partial[(size_t)q * total + idx];
+    float4 v = u[0];
+#pragma unroll
+    for (int q = 1; q < DX_MAX_SPLIT; ++q)   // fixed order
+      if (q < split) {
+        v.x += u[q].x;
+        v.y += u[q].y;
+        v.z += u[q].z;
+        v.w += u[q].w;
+      }
+    float* dst = out + ((size_t)slot * B + b) * ld_out + n;
+    if (n + 3 < I && (ld_out & 3) == 0) {
+      *reinterpret_cast<float4*>(dst) = v;
+    } else {
+      const float e[4] = {v.x, v.y, v.z, v.w};
+      for (int r = 0; r < 4 && n + r < I; ++r) dst[r] = e[r];
+    }
+  }
+}
+
+bool dx_gemm_uses_blocks(const Dims& d, size_t scratch_bytes) { return dx_blocks(d, scratch_bytes).split > 0; }
+
+hipError_t launch_dx_gemm(const Dims& d, const void* WTx, const void* dG, int nslots, float* dx, void* scratch,
+                          size_t scratch_bytes, hipStream_t st) {
+  const DxBlocks b = dx_blocks(d, scratch_bytes);
+  if (b.split == 0) return launch_dgrad_gemm(d, WTx, d.I, dG, nslots, dx, d.I, st);
+  TgemmParams p{};
+  p.A = WTx;
+  p.B = dG;
+  p.mt_total = d.NX / 16;
+  p.nt_total = nslots * d.BP / 16;
+  p.a_steps = p.b_steps = d.G4 / 32;
+  p.nk = d.G4 / 32;
+  p.gx = b.gx;
+  p.gy = (p.nt_total + 15) / 16;   // a short chunk has fewer blocks; the shares stay those of the shape
+  p.acc = reinterpret_cast<float*>(scratch);
+  p.accumulate = 0;
+  p.full = 0;
+  p.split = b.split;
+  p.extra = p.acc + (size_t)p.gx * p.gy * 256 * 256;
+  hipError_t e = launch_tgemm<__bf16>(p, st);
+  if (e != hipSuccess) return e;
+  const int blocks = p.gx * p.gy;
+  dx_finish_kernel<<<dim3(std::min(blocks * 64, 4096)), dim3(256), 0, st>>>(reinterpret_cast<const float4*>(scratch), blocks, b.split,
+                                                                           p.gy, nslots * d.BP, d.B, d.BP, d.I, dx, d.I);
+  return hipGetLastError();
+}
+
 // The weight gradient runs on the 256 x 256 tiles when the operands are bf16 and dW has enough tiles.
 static bool wgrad_uses_big_tiles(const Dims& d) {
   if (!d.dtype) return false;

@@ -573,7 +573,7 @@ int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t w
       e = launch_wgrad(d, ws + w.dGT[0], ws + w.aT[0], d.CH, 1, reinterpret_cast<float*>(ws + w.dWacc), st);
     if (e == hipSuccess) e = hipEventRecord(ev[1], st);
     for (int i = 0; i < reps && e == hipSuccess; ++i)
-      e = launch_dgrad_gemm(d, ws + w.WTx, d.I, ws + w.dG[0], d.CH, dx_scratch, d.I, st);
+      e = launch_dx_gemm(d, ws + w.WTx, ws + w.dG[0], d.CH, dx_scratch, ws + w.dGT[1], w.dGT[1] - w.dGT[0], st);
     if (e == hipSuccess) e = hipEventRecord(ev[2], st);
     if (e == hipSuccess) e = hipEventSynchronize(ev[2]);
   }
@@ -795,7 +795,9 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     }));
     if (dx)
       HIP_TRY(tm(MEBPTT_K_DGRAD, st2, [&] {
-        return launch_dgrad_gemm(d, WTx, d.I, ws + w.dG[buf], nslots, dx + x_off, d.I, st2);
+        // the chunk's dG^T buffer is free from here (its dW GEMM is ahead on the same stream) until the
+        // chunk after next fills it: the dx GEMM may keep partial sums there
+        return launch_dx_gemm(d, WTx, ws + w.dG[buf], nslots, dx + x_off, ws + w.dGT[buf], w.dGT[1] - w.dGT[0], st2);
       }));
     if (side) {
       HIP_TRY(hipEventRecord(side->done[buf], st2));
