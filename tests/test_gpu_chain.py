@@ -197,6 +197,20 @@ def test_bounded_waits_give_up_and_report():
     _same(s.run_and_fetch(), good, "after restoring the bound")
 
 
+def test_batched_recomputation_with_the_loss_on_h():
+    """The same path when the loss is half the sum of the squared outputs (dy_t = h_t): the backward-only
+    sweep launch then takes the injected gradient from the states the forward-batch launch left in the
+    stage."""
+    from test_gpu_parity import TOL, check_against_oracle, oracle_gradients
+    w = wl.Workload("batch-h2", B=64, I=64, H=1024, t=40, kind=wl.KIND_HSM, m=7, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_HALF_SUM_H2, seed=515)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    base = _run(w, inp, wl.KIND_HSM, 7, chain=False)
+    for kind, m in ((wl.KIND_HSM, 7), (wl.KIND_HSM, 40), (wl.KIND_MSM, 25)):
+        _same(_run(w, inp, kind, m, chain=True), base, (kind, m))
+    check_against_oracle(w, inp, base, oracle_gradients(w, inp), TOL[w.gemm_dtype], label="batched recomputation, loss on h: ")
+
+
 @pytest.mark.parametrize("B,I,H,t,m", [(64, 128, 128, 70, 6), (64, 256, 1024, 45, 8)])
 def test_resident_launches_in_a_captured_graph(B, I, H, t, m):
     """A run whose sequential work goes out as chain, sweep and forward-batch launches, captured into
