@@ -338,11 +338,11 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
 
 /* Forward operations that follow each other (Algorithm 2's forward loop, and the consecutive
  * single-step pushes of a sub-sequence that fits into memory) are issued as "forward-chain"
- * launches where the shape allows it (bf16 operands, LSTM, H a multiple of 128 and gate weights
+ * launches where the shape allows it (bf16 operands, either cell, H a multiple of 128 and gate weights
  * that fit into the registers and LDS of one XCD's compute units): one launch then carries up to
  * 192 steps, keeps the gate weights on the chip, splits the batch over the 8 XCDs and lets the 32
  * compute units of an XCD exchange h through their shared L2.  Where the transposed recurrent
- * weights fit as well (H = 128, 256, 512 with I <= H/4 .. H), the runs of "forward operation keeping
+ * weights fit as well (LSTM, H = 128, 256, 512 with I <= H/4 .. H), the runs of "forward operation keeping
  * the internal state, then backward operation" that end every sub-sequence are issued the same way
  * ("sweep" launches, up to 32 pairs, internal states never leaving the registers).  Where only the
  * transposed recurrent weights fit (H = 1024), the forward operations of such a run -- they do not

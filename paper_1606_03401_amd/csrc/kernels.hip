@@ -1207,7 +1207,7 @@ __device__ inline bf16x8 load_frag_l2(const void* base, unsigned byte_off) {
   return cv.f;
 }
 
-template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
+template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW, int CELL>
 __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
   using T = __bf16;
   using M = Mma<T>;
@@ -1285,7 +1285,9 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
     c_state[q] = 0.0f;
     if (mine[q]) {
       bias[q] = *reinterpret_cast<const float4*>(p.bp + 4 * u);
-      c_state[q] = p.src[hhalf + (size_t)b * p.H + u];
+      // the state the pointwise step blends with, kept in this register from step to step:
+      // c_{s-1} (LSTM) or h_{s-1} in full precision (GRU)
+      c_state[q] = CELL ? HPlane<T>::load(p.src, b, u, nsh, p.H, hhalf) : p.src[hhalf + (size_t)b * p.H + u];
     }
   }
   const bool x_vec = (p.I & 3) == 0;
@@ -1414,8 +1416,8 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) G[r] += red[w * NT * 4 * 64 + icell[q] + r * 64];
       float second, gate[4];
-      const float h = cell_forward<0>(G, bias[q], c_state[q], second, gate);
-      c_state[q] = second;
+      const float h = cell_forward<CELL>(G, bias[q], c_state[q], second, gate);
+      c_state[q] = CELL ? h : second;
       const int b = ib[q], u = iu[q];
       if (publish) {
         // Units u and u + 1 of one sequence sit 16 lanes apart in this layout and next to each other
@@ -1435,7 +1437,7 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         dst.gates[e] = gate[0];
         dst.gates[plane + e] = gate[1];
         dst.gates[p.unit + e] = gate[2];
-        dst.gates[p.unit + plane + e] = gate[3];
+        if (CELL == 0) dst.gates[p.unit + plane + e] = gate[3];
       }
     }
     if (publish) {
@@ -1480,7 +1482,7 @@ static int group_share(const Dims& d, int candidate) {
 // Index into RES_CONFIGS for this shape, or -1 when the chain kernel does not apply; *nb_out = the
 // sequences per XCD to launch it with.
 static int resident_config(const Dims& d, int* nb_out = nullptr) {
-  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H) return -1;
+  if (!d.dtype || d.H % 128 != 0 || d.KH != d.H) return -1;   // either cell: the GRU's rows r, z, n_x, n_h fill the same four packed rows
   const int nsteps = d.KP / 32;
   const FwdConfig fc = forward_config<__bf16>(d);
   const int ks = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;   // the K split of the per-step kernels
@@ -1505,18 +1507,22 @@ size_t forward_chain_sync_bytes() { return (1024 + 64) * sizeof(unsigned); }
 size_t forward_chain_status_offset() { return 1024 * sizeof(unsigned); }
 unsigned forward_chain_arrivals(int steps) { return steps > 1 ? (unsigned)(steps - 1) * RES_MEMBERS : 0u; }
 
-template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
-static hipError_t launch_chain_cfg(const ResParams& p, hipStream_t st) {
+template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW, int CELL>
+static hipError_t launch_chain_cell(const ResParams& p, hipStream_t st) {
   const size_t lds = (size_t)KS * NRT * NBT * 4 * 64 * sizeof(float) + (size_t)KS * NRT * NSL * 64 * 8 * sizeof(__bf16);
   static bool configured = false;   // per instantiation; the attribute only has to be set once
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW, CELL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW><<<dim3(RES_WGS), dim3(64 * KS), lds, st>>>(p);
+  forward_chain_kernel<NRT, NSW, NSL, KS, NBT, NSXW, CELL><<<dim3(RES_WGS), dim3(64 * KS), lds, st>>>(p);
   return hipGetLastError();
+}
+template <int NRT, int NSW, int NSL, int KS, int NBT, int NSXW>
+static hipError_t launch_chain_cfg(const ResParams& p, int cell, hipStream_t st) {
+  return cell ? launch_chain_cell<NRT, NSW, NSL, KS, NBT, NSXW, 1>(p, st) : launch_chain_cell<NRT, NSW, NSL, KS, NBT, NSXW, 0>(p, st);
 }
 
 hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, const float* x_first, const float* src_unit,
@@ -1546,13 +1552,13 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
   p.unit = d.unit;
   for (int j = 0; j < count; ++j) p.step[j] = ResStep{steps[j].out, steps[j].gates};
   switch (cfg) {
-    case 0: return launch_chain_cfg<8, 5, 1, 8, 1, 1>(p, st);
-    case 1: return launch_chain_cfg<4, 5, 0, 4, 1, 1>(p, st);
-    case 2: return launch_chain_cfg<4, 5, 0, 4, 2, 1>(p, st);
-    case 3: return launch_chain_cfg<2, 4, 0, 4, 1, 2>(p, st);
-    case 4: return launch_chain_cfg<2, 4, 0, 4, 2, 2>(p, st);
-    case 5: return launch_chain_cfg<1, 2, 0, 4, 1, 1>(p, st);
-    default: return launch_chain_cfg<1, 2, 0, 4, 2, 1>(p, st);
+    case 0: return launch_chain_cfg<8, 5, 1, 8, 1, 1>(p, d.cell, st);
+    case 1: return launch_chain_cfg<4, 5, 0, 4, 1, 1>(p, d.cell, st);
+    case 2: return launch_chain_cfg<4, 5, 0, 4, 2, 1>(p, d.cell, st);
+    case 3: return launch_chain_cfg<2, 4, 0, 4, 1, 2>(p, d.cell, st);
+    case 4: return launch_chain_cfg<2, 4, 0, 4, 2, 2>(p, d.cell, st);
+    case 5: return launch_chain_cfg<1, 2, 0, 4, 1, 1>(p, d.cell, st);
+    default: return launch_chain_cfg<1, 2, 0, 4, 2, 1>(p, d.cell, st);
   }
 }
 

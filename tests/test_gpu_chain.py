@@ -197,6 +197,31 @@ def test_bounded_waits_give_up_and_report():
     _same(s.run_and_fetch(), good, "after restoring the bound")
 
 
+@pytest.mark.parametrize("B,I,H,t", [(64, 128, 128, 40), (37, 100, 128, 33), (64, 256, 256, 50), (150, 128, 512, 30),
+                                     (64, 256, 1024, 40)])
+def test_gru_forward_chains(B, I, H, t):
+    """The GRU core through forward-chain launches (h kept in full precision in registers from step
+    to step; its backward operations stay launch-per-step): bit for bit the launch-per-step path's
+    gradients for every strategy and several budgets, and the oracle's within tolerance."""
+    from paper_1606_03401_amd.session import Session
+    from test_gpu_parity import TOL, check_against_oracle, oracle_gradients
+    w = wl.Workload("gru-chain", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=4, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, dy_first_step=2, seed=1200 + B + H, cell=wl.CELL_GRU)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    base = _run(w, inp, wl.KIND_HSM, 3, chain=False)
+    check_against_oracle(w, inp, base, oracle_gradients(w, inp), TOL[w.gemm_dtype], label=f"gru chain {B}x{I}x{H} per-step: ")
+    for kind, m in ((wl.KIND_HSM, 1), (wl.KIND_HSM, 3), (wl.KIND_HSM, t), (wl.KIND_ISM, 2), (wl.KIND_ISM, t), (wl.KIND_MSM, 7)):
+        _same(_run(w, inp, kind, m, chain=True), base, (kind, m))
+    s = Session(w, inp, kind=wl.KIND_ISM, m=t)
+    mb.mebptt_profile_enable(1)
+    out = s.run_and_fetch()
+    prof = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    _same(out, base, "profiled")
+    assert prof.chain_steps >= t - 2 and prof.sweep_steps == 0 and prof.batch_steps == 0
+    assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+
+
 def test_batched_recomputation_with_the_loss_on_h():
     """The same path when the loss is half the sum of the squared outputs (dy_t = h_t): the backward-only
     sweep launch then takes the injected gradient from the states the forward-batch launch left in the
