@@ -363,8 +363,8 @@ int mebptt_run_status(const mebptt_lstm_desc* desc, const void* workspace, size_
                       int32_t* status);
 
 /* on = 0: from now on every forward and backward operation gets a launch of its own (or shares a
- * pair launch), whatever the shape (the path the forward-chain and sweep launches are checked
- * against, and the "before" of their measurement); on != 0 (the default) restores them.  They are
+ * pair launch), whatever the shape (the path the forward-chain, sweep and forward-batch launches
+ * are checked against, and the "before" of their measurement); on != 0 (the default) restores them.  They are
  * used only on a device that reports 256 compute units (8 XCDs of 32): on a partitioned device or
  * one with masked compute units the launch-per-step path runs regardless of this switch.
  * Process-wide; not to be toggled while a run is enqueued. */
