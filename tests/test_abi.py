@@ -27,6 +27,22 @@ def test_every_declared_symbol_is_exported_and_bound():
     assert "gfx950" in mb.mebptt_version()
 
 
+def test_recomputation_stage_in_the_workspace():
+    """The workspace carries a stage for recomputed internal states exactly on the shapes whose way
+    back through stored hidden states is a forward-batch launch plus a backward-only sweep launch
+    (bf16 LSTM, H = 1024, a batch the sweep kernel covers): as many states as a sweep launch carries
+    (32), at most 48 MiB, three units each.  The GRU of the same shape has the same workspace but for
+    the stage."""
+    def ws(B, I, H, cell):
+        return mb.mebptt_workspace_bytes(mb.make_desc(B, I, H, 100, 1, 0, 1, cell))
+    unit = lambda B, H: mb.mebptt_unit_bytes(mb.make_desc(B, 64, H, 100, 1, 0, 1, 0))
+    assert ws(64, 256, 1024, 0) - ws(64, 256, 1024, 1) == 32 * 3 * unit(64, 1024) == 48 << 20
+    assert ws(128, 64, 1024, 0) - ws(128, 64, 1024, 1) == 16 * 3 * unit(128, 1024) == 48 << 20
+    for B, I, H in ((256, 128, 512), (128, 512, 2048), (200, 64, 1024), (64, 256, 256)):
+        assert ws(B, I, H, 0) == ws(B, I, H, 1), (B, I, H)      # no stage: sweeps with forward operations, or no sweeps
+    assert ws(64, 256, 1024, 0) == mb.mebptt_workspace_bytes(mb.make_desc(64, 256, 1024, 5, 1, 0, 1, 0))   # independent of t
+
+
 def test_size_queries():
     d = mb.make_desc(64, 256, 1024, 1000, 1, 0, 1)
     unit = 2 * 64 * 1024 * 4
