@@ -724,6 +724,26 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   auto tm = [&](int cls, hipStream_t s, auto&& launch) -> hipError_t {
     return use_profiler ? timed(cls, s, launch) : launch();
   };
+  // A launch that carries `carried` operations (forward chain, sweep, forward batch): the measurement
+  // hook brackets each of them whole, on the run's stream, and records what it carried.
+  auto whole_launch = [&](int cls, int carried, hipStream_t s, auto&& launch) -> int {
+    const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
+    if (use_profiler) HIP_TRY(close_group());
+    Sample smp{cls, nullptr, nullptr, carried};
+    if (bracket) {
+      smp.start = g_prof.get();
+      smp.stop = g_prof.get();
+      if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
+      HIP_TRY(hipEventRecord(smp.start, s));
+    }
+    HIP_TRY(launch());
+    if (bracket) {
+      HIP_TRY(hipEventRecord(smp.stop, s));
+      g_prof.runs.push_back(smp);
+    }
+    if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[cls];
+    return MEBPTT_OK;
+  };
 
   std::lock_guard<std::mutex> lock(g_run_mutex);   // side stream, events, profiler and static scratch are shared
   if (g_prof.open.cls >= 0) {   // a run that failed midway left its last bracket open: forget it
@@ -921,24 +941,9 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     a.count = n;
     a.src = srcs;
     a.state = states;
-    const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
-    if (use_profiler) HIP_TRY(close_group());
-    Sample smp{MEBPTT_K_SWEEP, nullptr, nullptr, n};
-    if (bracket) {
-      smp.start = g_prof.get();
-      smp.stop = g_prof.get();
-      if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
-      HIP_TRY(hipEventRecord(smp.start, st));
-    }
-    HIP_TRY(launch_sweep(d, a, st));
-    if (bracket) {
-      HIP_TRY(hipEventRecord(smp.stop, st));
-      g_prof.runs.push_back(smp);
-    }
-    if (use_profiler && g_prof.every_n > 0) {
-      ++g_prof.launches[MEBPTT_K_SWEEP];
-      if (!states) g_prof.sweep_forward_steps += n;
-    }
+    rc = whole_launch(MEBPTT_K_SWEEP, n, st, [&] { return launch_sweep(d, a, st); });
+    if (rc) return rc;
+    if (use_profiler && g_prof.every_n > 0 && !states) g_prof.sweep_forward_steps += n;
     chain_base += forward_chain_arrivals(n);
     ++chain_launches;
     bwd += n;
@@ -993,21 +998,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
           if (rc) return rc;
         }
         for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
-        const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
-        if (use_profiler) HIP_TRY(close_group());
-        Sample smp{MEBPTT_K_FWD_BATCH, nullptr, nullptr, n};
-        if (bracket) {
-          smp.start = g_prof.get();
-          smp.stop = g_prof.get();
-          if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
-          HIP_TRY(hipEventRecord(smp.start, st));
-        }
-        HIP_TRY(launch_forward_batch(d, Wp, bp, n, xs, srcs, dsts, st));
-        if (bracket) {
-          HIP_TRY(hipEventRecord(smp.stop, st));
-          g_prof.runs.push_back(smp);
-        }
-        if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_FWD_BATCH];
+        rc = whole_launch(MEBPTT_K_FWD_BATCH, n, st, [&] { return launch_forward_batch(d, Wp, bp, n, xs, srcs, dsts, st); });
+        if (rc) return rc;
         fwd += n;
         rc = issue_sweep(s_hi, n, srcs, states);
         if (rc) return rc;
@@ -1086,24 +1078,12 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
             cs[j] = ChainStep{keep_state ? f.dst : nullptr, f.gates};
           }
           const float* x_first = x_of(fsteps[fi].step);
-          // Measurement hook: every chain launch is bracketed (they are few), with its step count.
-          const bool bracket = use_profiler && g_prof.every_n > 0 && g_prof.runs.size() < 100000;
-          if (use_profiler) HIP_TRY(close_group());
-          Sample smp{MEBPTT_K_CHAIN, nullptr, nullptr, n};
-          if (bracket) {
-            smp.start = g_prof.get();
-            smp.stop = g_prof.get();
-            if (!smp.start || !smp.stop) return set_error(MEBPTT_EHIP, "event creation failed");
-            HIP_TRY(hipEventRecord(smp.start, st));
-          }
-          HIP_TRY(launch_forward_chain(d, Wp, bp, x_first, cur, cs, n, ws + w.ring,
-                                       reinterpret_cast<unsigned*>(ws + w.sync), chain_base, chain_launches, st));
+          rc = whole_launch(MEBPTT_K_CHAIN, n, st, [&] {
+            return launch_forward_chain(d, Wp, bp, x_first, cur, cs, n, ws + w.ring, reinterpret_cast<unsigned*>(ws + w.sync),
+                                        chain_base, chain_launches, st);
+          });
+          if (rc) return rc;
           ++chain_launches;
-          if (bracket) {
-            HIP_TRY(hipEventRecord(smp.stop, st));
-            g_prof.runs.push_back(smp);
-          }
-          if (use_profiler && g_prof.every_n > 0) ++g_prof.launches[MEBPTT_K_CHAIN];
           chain_base += forward_chain_arrivals(n);
           cur = fsteps[fi + n - 1].dst;
           fi += n;
