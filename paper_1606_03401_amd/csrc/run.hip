@@ -975,35 +975,52 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         continue;
       }
     }
-    if (batch_ok && pair_at(oi)) {
+    // A backward operation whose internal state a forward run has just left in the working core,
+    // followed by such pairs for the steps below it, leads their launch: it is the first step of
+    // the sweep launch, on the state in the core, the others on the states in the stage.
+    const bool lead = batch_ok && op.op == MEBPTT_OP_BWD && op.dst == MEBPTT_LOC_CORE && pair_at(oi + 1) &&
+                      ops[oi + 1].step == op.step - 1;
+    if (batch_ok && (lead || pair_at(oi))) {
       // A run of such pairs for steps going down inside one chunk, every step's input state in a
       // slot: the forward operations do not depend on each other and go out as one launch that
       // leaves the internal states in the stage; one backward-only sweep launch then consumes them.
-      const int s_hi = op.step, chunk = (s_hi - 1) / CH;
-      const int n_max = std::min(sweep_max_steps(), w.stage_steps);
-      int n = 0;
+      const int s_hi = op.step, chunk = (s_hi - 1) / CH, nl = lead ? 1 : 0;
+      const size_t first = oi + (size_t)nl;   // schedule entry of the first pair
+      const int n_max = std::min(sweep_max_steps(), w.stage_steps) - nl;
+      int n = 0;   // pairs
       const float *srcs[64], *xs[64], *states[64];
       float* dsts[64];
-      while (n < n_max && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - n &&
-             ops[oi + 2 * (size_t)n].src >= 0 && (s_hi - n - 1) / CH == chunk) {
-        srcs[n] = loc(ops[oi + 2 * (size_t)n].src);
-        xs[n] = x + (size_t)(s_hi - n - 1) * d.B * d.I;
-        dsts[n] = reinterpret_cast<float*>(ws + w.stage) + (size_t)n * 3 * unit;
-        states[n] = dsts[n];
+      if (lead) {
+        srcs[0] = loc(op.src);
+        states[0] = loc(op.dst);
+        xs[0] = nullptr;
+        dsts[0] = nullptr;
+      }
+      while (n < n_max && pair_at(first + 2 * (size_t)n) && ops[first + 2 * (size_t)n].step == s_hi - nl - n &&
+             ops[first + 2 * (size_t)n].src >= 0 && (s_hi - nl - n - 1) / CH == chunk) {
+        srcs[nl + n] = loc(ops[first + 2 * (size_t)n].src);
+        xs[nl + n] = x + (size_t)(s_hi - nl - n - 1) * d.B * d.I;
+        dsts[nl + n] = reinterpret_cast<float*>(ws + w.stage) + (size_t)n * 3 * unit;
+        states[nl + n] = dsts[nl + n];
         ++n;
       }
-      if (n >= 2) {
+      if (n >= 1 && n + nl >= 2) {
         if (have_pending) {
           rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
           if (rc) return rc;
         }
-        for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
-        rc = whole_launch(MEBPTT_K_FWD_BATCH, n, st, [&] { return launch_forward_batch(d, Wp, bp, n, xs, srcs, dsts, st); });
+        if (lead) {
+          touch(op.dst, 3);
+          touch(op.src, 1);
+        }
+        for (int j = 0; j < n; ++j) touch(ops[first + 2 * (size_t)j].src, 1);
+        rc = whole_launch(MEBPTT_K_FWD_BATCH, n, st,
+                          [&] { return launch_forward_batch(d, Wp, bp, n, xs + nl, srcs + nl, dsts + nl, st); });
         if (rc) return rc;
         fwd += n;
-        rc = issue_sweep(s_hi, n, srcs, states);
+        rc = issue_sweep(s_hi, n + nl, srcs, states);
         if (rc) return rc;
-        oi += 2 * (size_t)n;
+        oi = first + 2 * (size_t)n;
         continue;
       }
     }

@@ -128,8 +128,8 @@ def test_batched_recomputation(B, I, H, t):
         assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.batch_steps
                 == out.stats.forward_ops)
         assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == t
-        if kind == wl.KIND_HSM:
-            assert prof.batch_steps == prof.sweep_steps
+        if kind == wl.KIND_HSM:   # a sweep launch may start with a step whose state a forward run left in the core
+            assert prof.batch_steps <= prof.sweep_steps <= prof.batch_steps + prof.launches[mb.K_SWEEP]
         if kind == wl.KIND_HSM and m == t:
             assert prof.batch_steps >= t - 8     # all but single steps left over at chunk boundaries
         if kind == wl.KIND_ISM:
