@@ -952,6 +952,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     return MEBPTT_OK;
   };
 
+  const float* handed_src = nullptr;   // input state of a step a forward chain handed over to the next sweep launch
+  int handed_step = 0;
   for (size_t oi = 0; oi < ops.size();) {
     const mebptt_op& op = ops[oi];
     if (bsweep_ok && stored_bwd_at(oi) && stored_bwd_at(oi + 1)) {
@@ -1024,21 +1026,26 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         continue;
       }
     }
-    if (sweep_ok && pair_at(oi)) {
-      // a run of such pairs for steps going down inside one chunk goes out as one sweep launch
-      const int s_hi = op.step, chunk = (s_hi - 1) / CH;
-      int n = 0;
+    if (sweep_ok && (handed_src || pair_at(oi))) {
+      // a run of such pairs for steps going down inside one chunk goes out as one sweep launch,
+      // starting with the step a forward chain handed over, if there is one (see below)
+      const int nl = handed_src ? 1 : 0;
+      const int s_hi = nl ? handed_step : op.step, chunk = (s_hi - 1) / CH;
+      int n = 0;   // pairs
       const float* srcs[64];
-      while (n < sweep_max_steps() && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - n &&
-             (s_hi - n - 1) / CH == chunk) {
-        srcs[n] = loc(ops[oi + 2 * (size_t)n].src);
+      srcs[0] = handed_src;
+      while (n + nl < sweep_max_steps() && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - nl - n &&
+             (s_hi - nl - n - 1) / CH == chunk) {
+        srcs[nl + n] = loc(ops[oi + 2 * (size_t)n].src);
         ++n;
       }
-      if (n >= 2) {
+      if (nl && n == 0) return set_error(MEBPTT_EINVAL, "internal: a handed-over step found no pair to join");
+      if (n + nl >= 2) {
         for (int j = 0; j < n; ++j) touch(ops[oi + 2 * (size_t)j].src, 1);
-        rc = issue_sweep(s_hi, n, srcs, nullptr);
+        rc = issue_sweep(s_hi, n + nl, srcs, nullptr);
         if (rc) return rc;
         oi += 2 * (size_t)n;
+        handed_src = nullptr;
         continue;
       }
     }
@@ -1048,14 +1055,26 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         while (oe < ops.size() && ops[oe].op == MEBPTT_OP_FWD_RUN && ops[oe].src == ops[oe - 1].dst &&
                ops[oe - 1].dst != MEBPTT_LOC_CORE)
           ++oe;
+      // Hand-over.  The last run of the chain would leave the internal state of its last step in the
+      // core for the backward operation that follows, and pairs for the steps below follow that.  A
+      // sweep launch recomputes internal states itself: the chain stops one step short (h of the step
+      // before is where the run's `prev` puts it anyway) and the sweep launch starts one step
+      // higher, at the handed-over step.  Every forward operation still runs exactly once.
+      const mebptt_op& last = ops[oe - 1];
+      const bool hand_over =
+          sweep_ok && last.count >= 2 && last.keep && last.dst == MEBPTT_LOC_CORE && oe + 2 < ops.size() &&
+          ops[oe].op == MEBPTT_OP_BWD && ops[oe].dst == MEBPTT_LOC_CORE && ops[oe].src == last.prev &&
+          ops[oe].step == last.step + last.count - 1 && pair_at(oe + 1) && ops[oe + 1].step == ops[oe].step - 1 &&
+          (ops[oe].step - 1) / CH == (ops[oe].step - 2) / CH;
       fsteps.clear();
       for (size_t k = oi; k < oe; ++k) {
         const mebptt_op& o = ops[k];
-        if (o.dst == MEBPTT_LOC_CORE) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
+        const bool short_run = hand_over && k == oe - 1;   // its last step goes to the sweep launch
+        if (o.dst == MEBPTT_LOC_CORE && !short_run) core_flip ^= 1;   // fresh core buffer: the held-back step may still read the other
         touch(o.src, 1);
-        touch(o.dst, o.keep ? 3 : 1);
+        if (!short_run) touch(o.dst, o.keep ? 3 : 1);
         if (o.count > 1) touch(o.prev, 1);
-        for (int j = 1; j <= o.count; ++j) {
+        for (int j = 1; j <= o.count - (short_run ? 1 : 0); ++j) {
           float* dst = (j == o.count) ? loc(o.dst)
                                       : (j == o.count - 1 ? loc(o.prev) : loc((j & 1) ? MEBPTT_LOC_T1 : MEBPTT_LOC_T0));
           fsteps.push_back(FStep{o.step + j - 1, dst, (j == o.count && o.keep) ? dst + unit : nullptr, j >= o.count - 1});
@@ -1130,7 +1149,13 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
           g_prof.runs.push_back(run_sample);
         }
       }
-      oi = oe;
+      if (hand_over) {
+        handed_src = loc(last.prev);
+        handed_step = ops[oe].step;
+        oi = oe + 1;   // past the backward operation: the sweep launch carries it
+      } else {
+        oi = oe;
+      }
       continue;
     } else if (op.op == MEBPTT_OP_BWD) {
       if (have_pending) {
