@@ -222,6 +222,45 @@ def test_gru_forward_chains(B, I, H, t):
     assert mb.mebptt_run_status(s.desc, s.workspace) == 0
 
 
+@pytest.mark.parametrize("B,I,H", [(64, 128, 128), (64, 256, 1024)])
+def test_runs_join_the_chain_before_them(B, I, H):
+    """Where memory runs out the schedule ends a re-forwarding chain with a run that leaves an internal
+    state in the working core, then the backward operation on it, then the pairs for the steps below.
+    That backward operation does not get a launch of its own: the sweep launch that follows carries
+    it (recomputing the state itself and the chain stopping one step short, or taking the state from
+    the core).  Counted from the launches, with every forward and backward operation still accounted
+    for exactly once and the gradients those of the launch-per-step path bit for bit."""
+    from paper_1606_03401_amd.session import Session
+    t, m = 150, 7
+    w = wl.Workload("join", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=m, gemm_dtype=wl.GEMM_BF16,
+                    loss=wl.LOSS_EXTERNAL_DY, seed=733 + H)
+    inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+    base = _run(w, inp, wl.KIND_HSM, m, chain=False)
+    s = Session(w, inp)
+    sched = s.plan.schedule()
+    CH = mb.mebptt_chunk_steps(s.desc)
+
+    def pair_below(i):      # entries i, i + 1: forward operation of one step keeping its state, backward operation of it
+        return (i + 1 < len(sched) and sched[i]["op"] == 1 and sched[i]["count"] == 1 and sched[i]["keep"]
+                and sched[i + 1]["op"] == 2 and sched[i + 1]["step"] == sched[i]["step"])
+    lone = [i for i in range(1, len(sched)) if sched[i]["op"] == 2 and sched[i - 1]["op"] == 1 and sched[i - 1]["count"] >= 2]
+    joinable = [i for i in lone if pair_below(i + 1) and sched[i + 1]["step"] == sched[i]["step"] - 1
+                and (sched[i]["step"] - 1) // CH == (sched[i]["step"] - 2) // CH]
+    assert len(joinable) >= 10              # the schedule has many such backward operations ...
+    lone, joinable = len(lone), len(joinable)
+    mb.mebptt_profile_enable(1)
+    out = s.run_and_fetch()
+    prof = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    _same(out, base, "joined runs")
+    assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+    # ... and none of them is launched alone (what is, are the ones no pair follows, and single pairs)
+    assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] <= lone - joinable + 3
+    assert (prof.launches[mb.K_FORWARD] + prof.launches[mb.K_PAIR] + prof.chain_steps + prof.sweep_forward_steps
+            + prof.batch_steps == out.stats.forward_ops == s.plan.forward_ops)
+    assert prof.launches[mb.K_BACKWARD] + prof.launches[mb.K_PAIR] + prof.sweep_steps == t
+
+
 def test_batched_recomputation_with_the_loss_on_h():
     """The same path when the loss is half the sum of the squared outputs (dy_t = h_t): the backward-only
     sweep launch then takes the injected gradient from the states the forward-batch launch left in the
