@@ -150,9 +150,9 @@ struct SweepArgs {
   float* dc;
   float* y_out;            // plane of step 1 first, or NULL
   const void* dG_next;     // dG block of step s_hi + 1, or NULL for the last step of the sequence
-  void* dG_chunk;
-  void* dGT;
-  void* aT;
+  void* dG_chunk[2];       // the two chunk buffers of each operand, indexed by chunk parity: a launch may cross
+  void* dGT[2];            // from one chunk of steps into the one below
+  void* aT[2];
   unsigned* sync;
   unsigned base, launch;
   int s_hi, count;

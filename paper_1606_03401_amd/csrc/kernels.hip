@@ -1589,13 +1589,13 @@ struct SweepParams {
   float* dc;             // running cell-state gradient plane
   float* y_out;          // outputs, plane of step 1 first, or NULL
   const void* dG_next;   // dG block of step s_hi + 1, or NULL when s_hi is the last step of the sequence
-  void* dG_chunk;        // this chunk's dG buffer (block of step s at slot (s-1) % CH)
-  void* dGT;
-  void* aT;
+  void* dG_chunk[2];     // the two chunk buffers: step s lives in buffer ((s-1) / CH) & 1, its block at slot (s-1) % CH
+  void* dGT[2];
+  void* aT[2];
   unsigned* sync;
   unsigned base, launch;
   long long wait_ticks;  // bound of every wait, in ticks of the 100 MHz wall clock
-  int s_hi, count;       // steps s_hi, s_hi - 1, ..., s_hi - count + 1 (all in one chunk)
+  int s_hi, count;       // steps s_hi, s_hi - 1, ..., s_hi - count + 1 (in at most two consecutive chunks)
   int B, I, H, KX, KH, BP, nb, G4, NX, KC, CH;
   size_t unit;
   const float* src[SWEEP_MAX_STEPS];   // src[j]: unit holding the state before step s_hi - j
@@ -1822,10 +1822,10 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
 
   for (int j = 0; j < p.count; ++j) {
     const int s = p.s_hi - j;                       // the step back-propagated now
-    const int slot = (s - 1) % p.CH;
+    const int slot = (s - 1) % p.CH, buf = ((s - 1) / p.CH) & 1;   // where step s lives in the chunk buffers
     const size_t dG_step = (size_t)p.BP * p.G4;     // elements of one step's dG block
-    const T* dG_next = (j == 0) ? reinterpret_cast<const T*>(p.dG_next)
-                                : reinterpret_cast<const T*>(p.dG_chunk) + (size_t)(slot + 1) * dG_step;
+    const T* dG_next = (j == 0) ? reinterpret_cast<const T*>(p.dG_next)   // step s + 1: maybe in the other buffer
+                                : reinterpret_cast<const T*>(p.dG_chunk[(s / p.CH) & 1]) + (size_t)(s % p.CH) * dG_step;
     if (j > 0) {
       // all 32 workgroups of this XCD have published their columns of dG of step s + 1?
       if (threadIdx.x == 0) {
@@ -1892,7 +1892,7 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
     }
     // pointwise backward of step s on the internal state held in registers
     const bool publish = j + 1 < p.count;
-    T* dG_cur = reinterpret_cast<T*>(p.dG_chunk) + (size_t)slot * dG_step;
+    T* dG_cur = reinterpret_cast<T*>(p.dG_chunk[buf]) + (size_t)slot * dG_step;
     const int ncs = p.KC / KSTEP, col0 = slot * p.B;
     T gq[IPT][4];
     float keep_h[IPT], keep_hprev[IPT];
@@ -1936,10 +1936,10 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
       if (!mine[q]) continue;
       const int b = ib[q], n = iu[q];
       const int col = col0 + b;
-      T* dGT = reinterpret_cast<T*>(p.dGT);
+      T* dGT = reinterpret_cast<T*>(p.dGT[buf]);
 #pragma unroll
       for (int r = 0; r < 4; ++r) dGT[ft_offset<T>(4 * n + r, col, ncs)] = gq[q][r];
-      reinterpret_cast<T*>(p.aT)[ft_offset<T>(p.NX + n, col, ncs)] = (T)keep_hprev[q];
+      reinterpret_cast<T*>(p.aT[buf])[ft_offset<T>(p.NX + n, col, ncs)] = (T)keep_hprev[q];
       if (p.y_out) p.y_out[(size_t)(s - 1) * plane + (size_t)b * p.H + n] = keep_h[q];
     }
     // the pointwise part of the next lower step's forward operation runs while the others arrive
@@ -2011,7 +2011,7 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   int nb = 0;
   const int cfg = sweep_config(d, &nb);
   if (cfg < 0 || a.count < 1 || a.count > SWEEP_MAX_STEPS) return hipErrorInvalidValue;
-  if ((a.s_hi - 1) / d.CH != (a.s_hi - a.count) / d.CH) return hipErrorInvalidValue;   // one chunk per launch
+  if ((a.s_hi - 1) / d.CH - (a.s_hi - a.count) / d.CH > 1) return hipErrorInvalidValue;   // two chunk buffers
   SweepParams p{};
   p.Wp = a.Wp;
   p.WTh = a.WTh;
@@ -2023,9 +2023,11 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   p.dc = a.dc;
   p.y_out = a.y_out;
   p.dG_next = a.dG_next;
-  p.dG_chunk = a.dG_chunk;
-  p.dGT = a.dGT;
-  p.aT = a.aT;
+  for (int i = 0; i < 2; ++i) {
+    p.dG_chunk[i] = a.dG_chunk[i];
+    p.dGT[i] = a.dGT[i];
+    p.aT[i] = a.aT[i];
+  }
   p.sync = a.sync;
   p.base = a.base;
   p.wait_ticks = g_wait_ticks;

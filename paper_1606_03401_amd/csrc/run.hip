@@ -909,15 +909,18 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // pushes; store-everything BPTT): consecutive ones go out as backward-only sweep launches.
   const bool bsweep_ok = resident_ok && can_run_backward_sweep(d);
   auto stored_bwd_at = [&](size_t i) { return i < ops.size() && ops[i].op == MEBPTT_OP_BWD && ops[i].dst >= 0; };
-  // One sweep launch for steps s_hi, s_hi - 1, ... (n of them, one chunk); states == nullptr: with forward operations.
+  // One sweep launch for steps s_hi, s_hi - 1, ... (n of them, in one chunk or crossing from one into
+  // the chunk below); states == nullptr: with forward operations.
   auto issue_sweep = [&](int s_hi, int n, const float* const* srcs, const float* const* states) -> int {
-    const int chunk = (s_hi - 1) / CH, buf = chunk & 1;
+    const int chunk_hi = (s_hi - 1) / CH, chunk_lo = (s_hi - n) / CH;
     if (have_pending) {
       rc = flush_backward(nullptr, nullptr, nullptr, nullptr);
       if (rc) return rc;
     }
-    rc = begin_chunk(chunk);
-    if (rc) return rc;
+    for (int c = chunk_hi; c >= chunk_lo; --c) {   // the buffers of every chunk the launch writes into must be free
+      rc = begin_chunk(c);
+      if (rc) return rc;
+    }
     rc = order_resident_launches();
     if (rc) return rc;
     SweepArgs a{};
@@ -931,9 +934,11 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     a.dc = dc;
     a.y_out = y_out;
     a.dG_next = (s_hi == t) ? nullptr : ws + w.dG[(s_hi / CH) & 1] + (size_t)(s_hi % CH) * dG_step;
-    a.dG_chunk = ws + w.dG[buf];
-    a.dGT = ws + w.dGT[buf];
-    a.aT = ws + w.aT[buf];
+    for (int i = 0; i < 2; ++i) {
+      a.dG_chunk[i] = ws + w.dG[i];
+      a.dGT[i] = ws + w.dGT[i];
+      a.aT[i] = ws + w.aT[i];
+    }
     a.sync = reinterpret_cast<unsigned*>(ws + w.sync);
     a.base = chain_base;
     a.launch = chain_launches;
@@ -948,7 +953,11 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     ++chain_launches;
     bwd += n;
     if (!states) fwd += n;
-    if ((s_hi - n) % CH == 0) return complete_chunk(chunk);   // the launch reached the first step of the chunk
+    for (int c = chunk_hi; c >= chunk_lo; --c)   // chunks whose first step the launch has back-propagated
+      if (c * CH + 1 >= s_hi - n + 1) {
+        rc = complete_chunk(c);
+        if (rc) return rc;
+      }
     return MEBPTT_OK;
   };
 
@@ -961,7 +970,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       int n = 0;
       const float *srcs[64], *states[64];
       while (n < sweep_max_steps() && stored_bwd_at(oi + (size_t)n) && ops[oi + (size_t)n].step == s_hi - n &&
-             (s_hi - n - 1) / CH == chunk) {
+             chunk - (s_hi - n - 1) / CH <= 1) {
         srcs[n] = loc(ops[oi + (size_t)n].src);
         states[n] = loc(ops[oi + (size_t)n].dst);
         ++n;
@@ -999,7 +1008,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         dsts[0] = nullptr;
       }
       while (n < n_max && pair_at(first + 2 * (size_t)n) && ops[first + 2 * (size_t)n].step == s_hi - nl - n &&
-             ops[first + 2 * (size_t)n].src >= 0 && (s_hi - nl - n - 1) / CH == chunk) {
+             ops[first + 2 * (size_t)n].src >= 0 && chunk - (s_hi - nl - n - 1) / CH <= 1) {
         srcs[nl + n] = loc(ops[first + 2 * (size_t)n].src);
         xs[nl + n] = x + (size_t)(s_hi - nl - n - 1) * d.B * d.I;
         dsts[nl + n] = reinterpret_cast<float*>(ws + w.stage) + (size_t)n * 3 * unit;
@@ -1035,7 +1044,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       const float* srcs[64];
       srcs[0] = handed_src;
       while (n + nl < sweep_max_steps() && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - nl - n &&
-             (s_hi - nl - n - 1) / CH == chunk) {
+             chunk - (s_hi - nl - n - 1) / CH <= 1) {
         srcs[nl + n] = loc(ops[oi + 2 * (size_t)n].src);
         ++n;
       }
@@ -1064,8 +1073,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       const bool hand_over =
           sweep_ok && last.count >= 2 && last.keep && last.dst == MEBPTT_LOC_CORE && oe + 2 < ops.size() &&
           ops[oe].op == MEBPTT_OP_BWD && ops[oe].dst == MEBPTT_LOC_CORE && ops[oe].src == last.prev &&
-          ops[oe].step == last.step + last.count - 1 && pair_at(oe + 1) && ops[oe + 1].step == ops[oe].step - 1 &&
-          (ops[oe].step - 1) / CH == (ops[oe].step - 2) / CH;
+          ops[oe].step == last.step + last.count - 1 && pair_at(oe + 1) && ops[oe + 1].step == ops[oe].step - 1;
       fsteps.clear();
       for (size_t k = oi; k < oe; ++k) {
         const mebptt_op& o = ops[k];
