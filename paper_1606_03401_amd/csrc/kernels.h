@@ -134,7 +134,7 @@ hipError_t launch_forward_chain(const Dims& d, const void* Wp, const float* bp, 
                                 unsigned launch, hipStream_t st);
 
 // A run of (forward operation keeping the internal state, backward operation) pairs for steps
-// s_hi, s_hi - 1, ..., all inside one weight-gradient chunk, in one launch with both weight
+// s_hi, s_hi - 1, ..., in one weight-gradient chunk or two consecutive ones, in one launch with both weight
 // operands resident on the chip (shapes for which can_run_sweep() holds).  src[j] is the unit
 // holding the state before step s_hi - j; the internal states never reach memory; everything a
 // backward step writes (dG, its transposed copies, y_out, the running dc) is written as by

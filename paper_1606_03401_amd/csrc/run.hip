@@ -992,7 +992,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
     const bool lead = batch_ok && op.op == MEBPTT_OP_BWD && op.dst == MEBPTT_LOC_CORE && pair_at(oi + 1) &&
                       ops[oi + 1].step == op.step - 1;
     if (batch_ok && (lead || pair_at(oi))) {
-      // A run of such pairs for steps going down inside one chunk, every step's input state in a
+      // A run of such pairs for steps going down (in at most two chunks), every step's input state in a
       // slot: the forward operations do not depend on each other and go out as one launch that
       // leaves the internal states in the stage; one backward-only sweep launch then consumes them.
       const int s_hi = op.step, chunk = (s_hi - 1) / CH, nl = lead ? 1 : 0;
@@ -1036,7 +1036,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       }
     }
     if (sweep_ok && (handed_src || pair_at(oi))) {
-      // a run of such pairs for steps going down inside one chunk goes out as one sweep launch,
+      // a run of such pairs for steps going down (in at most two chunks) goes out as one sweep launch,
       // starting with the step a forward chain handed over, if there is one (see below)
       const int nl = handed_src ? 1 : 0;
       const int s_hi = nl ? handed_step : op.step, chunk = (s_hi - 1) / CH;
