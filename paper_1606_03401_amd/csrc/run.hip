@@ -969,8 +969,11 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       const int s_hi = op.step, chunk = (s_hi - 1) / CH;
       int n = 0;
       const float *srcs[64], *states[64];
+      // These launches follow each other directly, so they stay inside one chunk: one that crossed into
+      // the chunk below would have to wait for the GEMMs of the chunk just completed, which read the
+      // buffers it is about to write (measured on store-everything BPTT: 10.3 -> 10.7 ms on cfg2).
       while (n < sweep_max_steps() && stored_bwd_at(oi + (size_t)n) && ops[oi + (size_t)n].step == s_hi - n &&
-             chunk - (s_hi - n - 1) / CH <= 1) {
+             (s_hi - n - 1) / CH == chunk) {
         srcs[n] = loc(ops[oi + (size_t)n].src);
         states[n] = loc(ops[oi + (size_t)n].dst);
         ++n;
