@@ -787,6 +787,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   int cur_chunk = -1;
 
   int64_t fwd = 0, bwd = 0;
+  int64_t gemm_mark[2] = {INT64_MIN / 2, INT64_MIN / 2};   // fwd + bwd when the GEMMs reading chunk buffer i were issued
   bool first_chunk = true;
   const size_t dG_step = (size_t)d.BP * d.G4 * op_b;   // bytes of one step inside a dG chunk buffer
   const bool fuse = can_fuse_pair(d);
@@ -823,9 +824,17 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       HIP_TRY(hipEventRecord(side->done[buf], st2));
       pending[buf] = true;
     }
+    gemm_mark[buf] = fwd + bwd;
     first_chunk = false;
     return MEBPTT_OK;
   };
+  // A sweep launch that starts in chunk c may run on into chunk c - 1, whose buffers the GEMMs of
+  // chunk c + 1 read: it then waits for them.  Worth it only if they were issued long enough ago to
+  // be done -- counted in operations enqueued on the run's stream since (a chunk's GEMMs take about
+  // as long as 15 - 30 of them; measured with 8, 16, 32 and 64: 16 is best on cfg2 and cfg4).  Launches that follow each other directly therefore end at the chunk
+  // boundary, as they always did; with the GEMMs on the run's own stream there is nothing to wait for.
+  constexpr int64_t CROSS_MIN_OPS = 16;
+  auto may_cross = [&](int chunk) { return !side || (fwd + bwd) - gemm_mark[(chunk - 1) & 1] >= CROSS_MIN_OPS; };
   // Before the first write into a chunk's buffers: their previous user (the GEMMs of the chunk
   // two before) must be done.
   auto begin_chunk = [&](int chunk) -> int {
@@ -969,11 +978,9 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       const int s_hi = op.step, chunk = (s_hi - 1) / CH;
       int n = 0;
       const float *srcs[64], *states[64];
-      // These launches follow each other directly, so they stay inside one chunk: one that crossed into
-      // the chunk below would have to wait for the GEMMs of the chunk just completed, which read the
-      // buffers it is about to write (measured on store-everything BPTT: 10.3 -> 10.7 ms on cfg2).
+      const int reach = may_cross(chunk) ? 1 : 0;   // (store-everything BPTT: these launches follow each other directly)
       while (n < sweep_max_steps() && stored_bwd_at(oi + (size_t)n) && ops[oi + (size_t)n].step == s_hi - n &&
-             (s_hi - n - 1) / CH == chunk) {
+             chunk - (s_hi - n - 1) / CH <= reach) {
         srcs[n] = loc(ops[oi + (size_t)n].src);
         states[n] = loc(ops[oi + (size_t)n].dst);
         ++n;
@@ -1001,6 +1008,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       const int s_hi = op.step, chunk = (s_hi - 1) / CH, nl = lead ? 1 : 0;
       const size_t first = oi + (size_t)nl;   // schedule entry of the first pair
       const int n_max = std::min(sweep_max_steps(), w.stage_steps) - nl;
+      const int reach = may_cross(chunk) ? 1 : 0;   // chunks below the first the launch may run into
       int n = 0;   // pairs
       const float *srcs[64], *xs[64], *states[64];
       float* dsts[64];
@@ -1011,7 +1019,7 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
         dsts[0] = nullptr;
       }
       while (n < n_max && pair_at(first + 2 * (size_t)n) && ops[first + 2 * (size_t)n].step == s_hi - nl - n &&
-             ops[first + 2 * (size_t)n].src >= 0 && chunk - (s_hi - nl - n - 1) / CH <= 1) {
+             ops[first + 2 * (size_t)n].src >= 0 && chunk - (s_hi - nl - n - 1) / CH <= reach) {
         srcs[nl + n] = loc(ops[first + 2 * (size_t)n].src);
         xs[nl + n] = x + (size_t)(s_hi - nl - n - 1) * d.B * d.I;
         dsts[nl + n] = reinterpret_cast<float*>(ws + w.stage) + (size_t)n * 3 * unit;
@@ -1043,11 +1051,12 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
       // starting with the step a forward chain handed over, if there is one (see below)
       const int nl = handed_src ? 1 : 0;
       const int s_hi = nl ? handed_step : op.step, chunk = (s_hi - 1) / CH;
+      const int reach = may_cross(chunk) ? 1 : 0;
       int n = 0;   // pairs
       const float* srcs[64];
       srcs[0] = handed_src;
       while (n + nl < sweep_max_steps() && pair_at(oi + 2 * (size_t)n) && ops[oi + 2 * (size_t)n].step == s_hi - nl - n &&
-             chunk - (s_hi - nl - n - 1) / CH <= 1) {
+             chunk - (s_hi - nl - n - 1) / CH <= reach) {
         srcs[nl + n] = loc(ops[oi + 2 * (size_t)n].src);
         ++n;
       }
