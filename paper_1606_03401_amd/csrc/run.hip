@@ -831,7 +831,8 @@ int run_impl(RunMode mode, const mebptt_lstm_desc* desc, const mebptt_plan_t* pl
   // A sweep launch that starts in chunk c may run on into chunk c - 1, whose buffers the GEMMs of
   // chunk c + 1 read: it then waits for them.  Worth it only if they were issued long enough ago to
   // be done -- counted in operations enqueued on the run's stream since (a chunk's GEMMs take about
-  // as long as 15 - 30 of them; measured with 8, 16, 32 and 64: 16 is best on cfg2 and cfg4).  Launches that follow each other directly therefore end at the chunk
+  // as long as 15 - 30 of them; thresholds of 8, 16, 32 and 64 were measured, 16 is the best on the
+  // workloads cfg2 and cfg4).  Launches that follow each other directly therefore end at the chunk
   // boundary, as they always did; with the GEMMs on the run's own stream there is nothing to wait for.
   constexpr int64_t CROSS_MIN_OPS = 16;
   auto may_cross = [&](int chunk) { return !side || (fwd + bwd) - gemm_mark[(chunk - 1) & 1] >= CROSS_MIN_OPS; };
