@@ -300,3 +300,31 @@ def test_resident_launches_in_a_captured_graph(B, I, H, t, m):
         assert mb.mebptt_run_status(s.desc, s.workspace) == 0
         if rep % 2 == 0:          # the program's own eager work between replays
             _same(s.run_and_fetch(), eager, ("eager after replay", rep))
+
+
+def test_random_shapes_budgets_and_strategies_bit_identical():
+    """Seeded random cases over the shape classes with resident launches, both cores, every strategy,
+    budgets from 1 to beyond t, sequences from 2 steps to several chunks, losses starting anywhere:
+    with the chain, sweep and forward-batch launches (and everything the executor does to join and
+    lengthen them) the gradients are those of the launch-per-step path bit for bit and finite."""
+    rng = np.random.default_rng(20260)
+    for case in range(160):
+        H = int(rng.choice([128, 256, 512, 1024]))
+        I = {128: int(rng.choice([8, 40, 64, 100, 128])), 256: int(rng.choice([136, 200, 256])),
+             512: int(rng.choice([16, 64, 100, 128])), 1024: int(rng.choice([32, 128, 250, 256]))}[H]
+        B = int(rng.choice([1, 3, 8, 17, 32, 50, 64, 100, 128, 200, 256]))
+        if H == 1024 and B > 128:
+            B = 64
+        t = int(rng.integers(2, 90)) if rng.random() < 0.85 else int(rng.integers(90, 300))
+        kind = int(rng.choice([wl.KIND_HSM, wl.KIND_ISM, wl.KIND_MSM]))
+        m = int(rng.integers(1, t + 2)) if kind != wl.KIND_MSM else int(rng.integers(2, 4 * t + 2))
+        w = wl.Workload("random", B=B, I=I, H=H, t=t, kind=kind, m=m, gemm_dtype=wl.GEMM_BF16, loss=wl.LOSS_EXTERNAL_DY,
+                        dy_first_step=int(rng.integers(1, t + 1)), seed=int(rng.integers(1, 10**6)),
+                        cell=int(rng.random() < 0.2))
+        inp = wl.make_inputs(w, nonzero_state=True, nonzero_bias=True)
+        what = (case, B, I, H, t, kind, m, w.dy_first_step, w.cell)
+        base = _run(w, inp, kind, m, chain=False)
+        got = _run(w, inp, kind, m, chain=True)
+        _same(got, base, what)
+        for f in FIELDS:
+            assert np.all(np.isfinite(getattr(got, f))), (what, f)
