@@ -1408,6 +1408,7 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
     const ResStep dst = p.step[j];
     T* ring_out = reinterpret_cast<T*>(p.ring) + (size_t)(j % RES_RING) * hhalf;
     const bool publish = j + 1 < p.count;
+    float keep_h[IPT], keep_second[IPT], keep_gate[IPT][4];
 #pragma unroll
     for (int q = 0; q < IPT; ++q) {
       if (!mine[q]) continue;
@@ -1415,9 +1416,9 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
       for (int w = 0; w < KS; ++w)   // fixed order, as in forward_body
 #pragma unroll
         for (int r = 0; r < 4; ++r) G[r] += red[w * NT * 4 * 64 + icell[q] + r * 64];
-      float second, gate[4];
-      const float h = cell_forward<CELL>(G, bias[q], c_state[q], second, gate);
-      c_state[q] = CELL ? h : second;
+      const float h = cell_forward<CELL>(G, bias[q], c_state[q], keep_second[q], keep_gate[q]);
+      keep_h[q] = h;
+      c_state[q] = CELL ? h : keep_second[q];
       const int b = ib[q], u = iu[q];
       if (publish) {
         // Units u and u + 1 of one sequence sit 16 lanes apart in this layout and next to each other
@@ -1428,22 +1429,31 @@ __global__ __launch_bounds__(64 * KS) void forward_chain_kernel(ResParams p) {
         if (((threadIdx.x >> 4) & 1) == 0)
           reinterpret_cast<unsigned*>(ring_out)[ft_offset<T>(b, u, nsh) >> 1] = hi16 | (other << 16);
       }
-      if (dst.out) {
-        HPlane<T>::store(dst.out, b, u, h, nsh, p.H, hhalf);
-        dst.out[hhalf + (size_t)b * p.H + u] = second;
-      }
-      if (dst.gates) {
-        const size_t e = (size_t)b * p.H + u, plane = (size_t)p.B * p.H;
-        dst.gates[e] = gate[0];
-        dst.gates[plane + e] = gate[1];
-        dst.gates[p.unit + e] = gate[2];
-        if (CELL == 0) dst.gates[p.unit + plane + e] = gate[3];
-      }
     }
     if (publish) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's slice of h has reached the L2
       __syncthreads();
       if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // What only later launches read goes out after the arrival: the other workgroups do not wait
+    // for these stores to be acknowledged.
+    if (dst.out || dst.gates) {
+#pragma unroll
+      for (int q = 0; q < IPT; ++q) {
+        if (!mine[q]) continue;
+        const int b = ib[q], u = iu[q];
+        if (dst.out) {
+          HPlane<T>::store(dst.out, b, u, keep_h[q], nsh, p.H, hhalf);
+          dst.out[hhalf + (size_t)b * p.H + u] = keep_second[q];
+        }
+        if (dst.gates) {
+          const size_t e = (size_t)b * p.H + u, plane = (size_t)p.B * p.H;
+          dst.gates[e] = keep_gate[q][0];
+          dst.gates[plane + e] = keep_gate[q][1];
+          dst.gates[p.unit + e] = keep_gate[q][2];
+          if (CELL == 0) dst.gates[p.unit + plane + e] = keep_gate[q][3];
+        }
+      }
     }
   }
 }
