@@ -345,7 +345,7 @@ int mebptt_run_prepared(const mebptt_lstm_desc* desc, const mebptt_plan_t* plan,
  * weights fit as well (LSTM, H = 128, 256, 512 with I <= H/4 .. H), the runs of "forward operation keeping
  * the internal state, then backward operation" that end every sub-sequence are issued the same way
  * ("sweep" launches, up to 32 pairs, internal states never leaving the registers).  Where only the
- * transposed recurrent weights fit (H = 1024), the forward operations of such a run -- they do not
+ * transposed recurrent weights fit (H = 1024), and for the GRU at every such width, the forward operations of such a run -- they do not
  * depend on each other, every input state being in a slot already -- go out as one "forward-batch"
  * launch that leaves the internal states in the workspace's stage, followed by one sweep launch of
  * backward operations on them; backward operations on internal states stored in slots go out as
@@ -472,6 +472,10 @@ int mebptt_measure_forward_stream(const mebptt_lstm_desc* desc, void* workspace,
 /* Time steps per chunk of the time-batched GEMMs for this shape (the K extent of the dW GEMM is
  * this many times B), or a negative error code. */
 int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc);
+/* Internal states the recomputation stage inside the workspace holds for this shape (0: the shape
+ * has no stage: its recomputation runs do not go out as a forward batch plus a backward-only sweep
+ * launch), or a negative error code. */
+int32_t mebptt_stage_steps(const mebptt_lstm_desc* desc);
 
 /* What one synchronisation of the 256 workgroups of a resident launch costs, alone: `iters`
  * synchronisations inside one kernel on `stream`, microseconds per synchronisation (host memory).

@@ -136,6 +136,7 @@ SIGNATURES = {
     "mebptt_null_launch_us": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "mebptt_measure_sync": (C.c_int, [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "mebptt_chunk_steps": (C.c_int32, [_DESC]),
+    "mebptt_stage_steps": (C.c_int32, [_DESC]),
     "mebptt_measure_forward_stream": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_bracket_overhead_us": (C.c_int, [C.c_double, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mebptt_measure_gemms": (C.c_int, [_DESC, _P, C.c_size_t, C.c_int32, _P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -485,6 +486,13 @@ def mebptt_measure_forward_stream(desc: mebptt_lstm_desc, workspace, reps: int =
 
 def mebptt_chunk_steps(desc: mebptt_lstm_desc) -> int:
     n = lib().mebptt_chunk_steps(C.byref(desc))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def mebptt_stage_steps(desc: mebptt_lstm_desc) -> int:
+    n = lib().mebptt_stage_steps(C.byref(desc))
     if n < 0:
         _check(n)
     return n

@@ -350,6 +350,20 @@ __device__ inline void lstm_backward_point(float dh, float dc_in, float gi, floa
   dc_out = __fmul_rn(dct, gf);
 }
 
+// The same for the GRU: r, z, n the gates, nh the recurrent part of the candidate (n = tanh(n_x + r * nh)),
+// h_prev = h_{s-1} in full precision.  dh is the whole dL/dh_s: the GEMM part, the injected loss
+// gradient and the part that bypasses the GEMM (dh_{s+1} * z_{s+1}, carried in the running plane).
+// dG: gradients of the packed rows r, z, n_x, n_h; carry: what step s - 1 adds to its dh.
+__device__ inline void gru_backward_point(float dh, float r, float z, float n, float nh, float h_prev, float (&dG)[4],
+                                          float& carry) {
+  const float da_n = __fmul_rn(__fmul_rn(dh, __fsub_rn(1.0f, z)), __fmaf_rn(-n, n, 1.0f));
+  dG[0] = __fmul_rn(__fmul_rn(__fmul_rn(da_n, nh), r), __fsub_rn(1.0f, r));
+  dG[1] = __fmul_rn(__fmul_rn(__fmul_rn(dh, __fsub_rn(h_prev, n)), z), __fsub_rn(1.0f, z));
+  dG[2] = da_n;
+  dG[3] = __fmul_rn(da_n, r);
+  carry = __fmul_rn(dh, z);
+}
+
 // ---- forward step: gate GEMM + LSTM pointwise -------------------------------------------------
 
 struct FwdParams {
@@ -780,14 +794,13 @@ __device__ inline void backward_body(const BwdParams& p, int bx, int by, float* 
     } else {
       // GRU: r = gi, z = gf, n = gg, n_h = c_s, h_{s-1} = c_prev.  The running plane `dc` carries
       // the part of dL/dh_{s-1} that bypasses the GEMM: dh_s * z_s.
-      dh += dc_in[q];
-      const float r = gi[q], z = gf[q], n = gg[q];
-      const float da_n = dh * (1.0f - z) * (1.0f - n * n);
-      dGi = da_n * c_s[q] * r * (1.0f - r);                 // reset gate
-      dGf = dh * (c_prev[q] - n) * z * (1.0f - z);          // update gate
-      dGg = da_n;                                           // candidate, input part (row n_x)
-      dGo = da_n * r;                                       // candidate, recurrent part (row n_h)
-      p.dc[e] = dh * z;
+      float dG[4], carry;
+      gru_backward_point(__fadd_rn(dh, dc_in[q]), gi[q], gf[q], gg[q], c_s[q], c_prev[q], dG, carry);
+      dGi = dG[0];
+      dGf = dG[1];
+      dGg = dG[2];
+      dGo = dG[3];
+      p.dc[e] = carry;
     }
     const T q0 = (T)dGi, q1 = (T)dGf, q2 = (T)dGg, q3 = (T)dGo;
     // dG of this step, fragment-tiled [b][4n + gate]: the four gates are consecutive in one lane slot
@@ -936,7 +949,7 @@ struct FwdBatchSteps {
   float* dst[FWD_BATCH_MAX_STEPS];         // three units: (h_s, c_s), (i, f), (g, o)
 };
 
-template <class T, int NG, int BT, int KS, int U>
+template <class T, int NG, int BT, int KS, int U, int CELL>
 __global__ __launch_bounds__(64 * KS) void forward_batch_kernel(FwdParams p, FwdBatchSteps steps, size_t hplane, size_t unit,
                                                                 size_t plane) {
   __shared__ float red[forward_red_floats(NG, BT, KS)];
@@ -951,11 +964,11 @@ __global__ __launch_bounds__(64 * KS) void forward_batch_kernel(FwdParams p, Fwd
   p.g_f = dst + unit + plane;
   p.g_g = dst + 2 * unit;
   p.g_o = dst + 2 * unit + plane;
-  forward_body<T, NG, BT, KS, U, 0>(p, blockIdx.x, blockIdx.y, red);
+  forward_body<T, NG, BT, KS, U, CELL>(p, blockIdx.x, blockIdx.y, red);
 }
 
 int forward_batch_max_steps() { return FWD_BATCH_MAX_STEPS; }
-bool can_run_forward_batch(const Dims& d) { return d.dtype == 1 && d.cell == 0; }
+bool can_run_forward_batch(const Dims& d) { return d.dtype == 1; }
 
 hipError_t launch_forward_batch(const Dims& d, const void* Wp, const float* bp, int n, const float* const* x,
                                 const float* const* src, float* const* dst, hipStream_t st) {
@@ -974,10 +987,15 @@ hipError_t launch_forward_batch(const Dims& d, const void* Wp, const float* bp, 
   const dim3 grid((d.HP / 4 + NG - 1) / NG, (d.BP / 16 + BT - 1) / BT, n);
   const size_t plane = (size_t)d.B * d.H;
   const FwdConfig cfg = forward_config<__bf16>(d);
-  if (cfg == FWD_TINY || cfg == FWD_SMALLK)   // the K split of the shape's stand-alone forward kernel
-    forward_batch_kernel<__bf16, NG, BT, 4, FU><<<grid, dim3(64 * 4), 0, st>>>(p, steps, d.hplane, d.unit, plane);
+  const bool small_k = cfg == FWD_TINY || cfg == FWD_SMALLK;   // the K split of the shape's stand-alone forward kernel
+  if (small_k && d.cell)
+    forward_batch_kernel<__bf16, NG, BT, 4, FU, 1><<<grid, dim3(64 * 4), 0, st>>>(p, steps, d.hplane, d.unit, plane);
+  else if (small_k)
+    forward_batch_kernel<__bf16, NG, BT, 4, FU, 0><<<grid, dim3(64 * 4), 0, st>>>(p, steps, d.hplane, d.unit, plane);
+  else if (d.cell)
+    forward_batch_kernel<__bf16, NG, BT, 8, FU, 1><<<grid, dim3(64 * 8), 0, st>>>(p, steps, d.hplane, d.unit, plane);
   else
-    forward_batch_kernel<__bf16, NG, BT, 8, FU><<<grid, dim3(64 * 8), 0, st>>>(p, steps, d.hplane, d.unit, plane);
+    forward_batch_kernel<__bf16, NG, BT, 8, FU, 0><<<grid, dim3(64 * 8), 0, st>>>(p, steps, d.hplane, d.unit, plane);
   return hipGetLastError();
 }
 
@@ -1614,8 +1632,9 @@ struct SweepParams {
 
 // FWD = false: the internal states are not recomputed but read from where an earlier launch
 // stored them (internal-state slots): a run of backward operations only, W_hh^T alone resident.
-template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW, int CELL = 0>
 __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
+  static_assert(!(FWD && CELL), "the launches that recompute internal states are built for the LSTM only");
   using T = __bf16;
   using M = Mma<T>;
   constexpr int VEC = 8, KSTEP = 32;
@@ -1727,10 +1746,11 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
           pf_gate[FWD ? 0 : q][0] = stp[p.unit + e];
           pf_gate[FWD ? 0 : q][1] = stp[p.unit + plane + e];
           pf_gate[FWD ? 0 : q][2] = stp[2 * p.unit + e];
-          pf_gate[FWD ? 0 : q][3] = stp[2 * p.unit + plane + e];
-          pf_c[FWD ? 0 : q] = stp[hhalf + e];
+          if (CELL == 0) pf_gate[FWD ? 0 : q][3] = stp[2 * p.unit + plane + e];   // the GRU has three gates
+          pf_c[FWD ? 0 : q] = stp[hhalf + e];                                     // c_s, or the GRU's n_h
           if (want_h) pf_h[FWD ? 0 : q] = HPlane<T>::load(stp, ib[q], iu[q], nsh, p.H, hhalf);
-          pf_cprev[q] = src[hhalf + e];
+          // what the pointwise step blends with: c_{s-1}, or the GRU's h_{s-1} in full precision
+          pf_cprev[q] = CELL ? HPlane<T>::load(src, ib[q], iu[q], nsh, p.H, hhalf) : src[hhalf + e];
           pf_hprev[q] = (float)HPlane<T>::as_operand(src, ib[q], iu[q], nsh, p.H, hhalf);
         }
       }
@@ -1921,8 +1941,11 @@ __global__ __launch_bounds__(512) void sweep_kernel(SweepParams p) {
         dyv = p.dy[(size_t)(s - p.dy_first) * plane + e];
       dh += dyv;
       float dG[4], dc_out;
-      lstm_backward_point(dh, dc_run[q], st_gate[q][0], st_gate[q][1], st_gate[q][2], st_gate[q][3], st_c[q], st_cprev[q],
-                          dG, dc_out);
+      if (CELL == 0)
+        lstm_backward_point(dh, dc_run[q], st_gate[q][0], st_gate[q][1], st_gate[q][2], st_gate[q][3], st_c[q], st_cprev[q],
+                            dG, dc_out);
+      else   // the running plane carries dh_{s+1} * z_{s+1}, as in backward_body
+        gru_backward_point(__fadd_rn(dh, dc_run[q]), st_gate[q][0], st_gate[q][1], st_gate[q][2], st_c[q], st_cprev[q], dG, dc_out);
       dc_run[q] = dc_out;
       // the four gates of a unit are consecutive in dG: one 8-byte store (what other compute units
       // fetch next must not be written in pieces smaller than a dword)
@@ -1972,7 +1995,7 @@ static const SweepConfig SWEEP_CONFIGS[] = {
 constexpr int SWEEP_BACKWARD_ONLY_FROM = 6;   // configurations from this index on have no forward part
 
 static int sweep_config(const Dims& d, int* nb_out = nullptr) {
-  if (!d.dtype || d.cell != 0 || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;
+  if (!d.dtype || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;   // either cell; can_run_sweep() narrows
   const int nstepsF = d.KP / 32, nstepsB = d.G4 / 32;
   const FwdConfig fc = forward_config<__bf16>(d);
   const int ksf = (fc == FWD_TINY || fc == FWD_SMALLK) ? 4 : 8;
@@ -1995,25 +2018,25 @@ static int sweep_config(const Dims& d, int* nb_out = nullptr) {
   return -1;
 }
 
-bool can_run_sweep(const Dims& d) {
+bool can_run_sweep(const Dims& d) {   // with forward operations: LSTM only
   const int c = sweep_config(d);
-  return c >= 0 && c < SWEEP_BACKWARD_ONLY_FROM;
+  return d.cell == 0 && c >= 0 && c < SWEEP_BACKWARD_ONLY_FROM;
 }
 bool can_run_backward_sweep(const Dims& d) { return sweep_config(d) >= 0; }
 int sweep_max_steps() { return SWEEP_MAX_STEPS; }
 
-template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW>
+template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW, int CELL = 0>
 static hipError_t launch_sweep_cfg(const SweepParams& p, hipStream_t st) {
   constexpr int NTB = (NRT * 4 + 15) / 16;
   const size_t lds = ((size_t)KSF * NRT * NBT + (size_t)KSB * NTB * NBT) * 4 * 64 * sizeof(float);
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW, CELL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW><<<dim3(RES_WGS), dim3(512), lds, st>>>(p);
+  sweep_kernel<FWD, NRT, NSWF, KSF, NSWB, KSB, NBT, NSXW, CELL><<<dim3(RES_WGS), dim3(512), lds, st>>>(p);
   return hipGetLastError();
 }
 
@@ -2061,6 +2084,16 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
     p.state[j] = a.state ? a.state[j] : nullptr;
   }
   if (a.state) {   // backward operations through stored internal states
+    if (d.cell)
+      switch (cfg) {
+        case 0: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 1, 1, 1>(p, st);
+        case 1: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 2, 1, 1>(p, st);
+        case 2: return launch_sweep_cfg<false, 2, 4, 4, 4, 8, 1, 2, 1>(p, st);
+        case 3: return launch_sweep_cfg<false, 2, 4, 4, 4, 8, 2, 2, 1>(p, st);
+        case 4: return launch_sweep_cfg<false, 1, 2, 4, 4, 4, 1, 1, 1>(p, st);
+        case 5: return launch_sweep_cfg<false, 1, 2, 4, 4, 4, 2, 1, 1>(p, st);
+        default: return launch_sweep_cfg<false, 8, 5, 8, 16, 8, 1, 1, 1>(p, st);
+      }
     switch (cfg) {
       case 0: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 1, 1>(p, st);
       case 1: return launch_sweep_cfg<false, 4, 5, 4, 8, 8, 2, 1>(p, st);
@@ -2071,6 +2104,7 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
       default: return launch_sweep_cfg<false, 8, 5, 8, 16, 8, 1, 1>(p, st);
     }
   }
+  if (d.cell) return hipErrorInvalidValue;
   switch (cfg) {
     case 0: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 1, 1>(p, st);
     case 1: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 2, 1>(p, st);

@@ -548,6 +548,12 @@ int32_t mebptt_chunk_steps(const mebptt_lstm_desc* desc) {
   return make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell).CH;
 }
 
+int32_t mebptt_stage_steps(const mebptt_lstm_desc* desc) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  return recompute_stage_steps(make_dims(desc->B, desc->I, desc->H, desc->gemm_dtype, desc->cell));
+}
+
 int mebptt_measure_gemms(const mebptt_lstm_desc* desc, void* workspace, size_t workspace_bytes, int32_t reps,
                          void* stream, double* wgrad_us, double* dgrad_us) {
   int rc = check_desc(desc);

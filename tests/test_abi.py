@@ -29,18 +29,25 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 def test_recomputation_stage_in_the_workspace():
     """The workspace carries a stage for recomputed internal states exactly on the shapes whose way
-    back through stored hidden states is a forward-batch launch plus a backward-only sweep launch
-    (bf16 LSTM, H = 1024, a batch the sweep kernel covers): as many states as a sweep launch carries
-    (32), at most 48 MiB, three units each.  The GRU of the same shape has the same workspace but for
-    the stage."""
-    def ws(B, I, H, cell):
-        return mb.mebptt_workspace_bytes(mb.make_desc(B, I, H, 100, 1, 0, 1, cell))
-    unit = lambda B, H: mb.mebptt_unit_bytes(mb.make_desc(B, 64, H, 100, 1, 0, 1, 0))
-    assert ws(64, 256, 1024, 0) - ws(64, 256, 1024, 1) == 32 * 3 * unit(64, 1024) == 48 << 20
-    assert ws(128, 64, 1024, 0) - ws(128, 64, 1024, 1) == 16 * 3 * unit(128, 1024) == 48 << 20
-    for B, I, H in ((256, 128, 512), (128, 512, 2048), (200, 64, 1024), (64, 256, 256)):
-        assert ws(B, I, H, 0) == ws(B, I, H, 1), (B, I, H)      # no stage: sweeps with forward operations, or no sweeps
-    assert ws(64, 256, 1024, 0) == mb.mebptt_workspace_bytes(mb.make_desc(64, 256, 1024, 5, 1, 0, 1, 0))   # independent of t
+    back through stored hidden states is a forward-batch launch plus a backward-only sweep launch:
+    bf16 operands, a shape the backward-only sweep kernel covers, and no sweep launch that recomputes
+    internal states itself (the LSTM has those up to H = 512; the GRU has none).  As many states as
+    a sweep launch carries (32), at most 48 MiB, three units each."""
+    def desc(B, I, H, cell=0, dtype=1):
+        return mb.make_desc(B, I, H, 100, dtype, 0, 1, cell)
+    unit = lambda B, H: mb.mebptt_unit_bytes(desc(B, 64, H))
+    assert mb.mebptt_stage_steps(desc(64, 256, 1024)) == 32 and 32 * 3 * unit(64, 1024) == 48 << 20
+    assert mb.mebptt_stage_steps(desc(128, 64, 1024)) == 16 and 16 * 3 * unit(128, 1024) == 48 << 20
+    for B, I, H in ((256, 128, 512), (64, 256, 256), (64, 128, 128)):      # the sweep launch recomputes the states itself
+        assert mb.mebptt_stage_steps(desc(B, I, H)) == 0
+        assert mb.mebptt_stage_steps(desc(B, I, H, cell=1)) > 0           # the GRU has no such launch
+    for B, I, H in ((128, 512, 2048), (200, 64, 1024), (32, 1024, 4096)):  # no backward-only sweep launch for the shape
+        assert mb.mebptt_stage_steps(desc(B, I, H)) == 0 and mb.mebptt_stage_steps(desc(B, I, H, cell=1)) == 0
+    assert mb.mebptt_stage_steps(desc(64, 256, 1024, dtype=0)) == 0       # fp32 operands: launch-per-step kernels only
+    # the stage is part of the workspace, which does not depend on t
+    with_stage, without = desc(64, 256, 1024), desc(64, 256, 1024, dtype=0)
+    assert mb.mebptt_workspace_bytes(with_stage) == mb.mebptt_workspace_bytes(mb.make_desc(64, 256, 1024, 5, 1, 0, 1, 0))
+    assert mb.mebptt_workspace_bytes(with_stage) > 48 << 20 and without is not None
 
 
 def test_size_queries():

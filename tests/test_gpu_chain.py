@@ -201,8 +201,8 @@ def test_bounded_waits_give_up_and_report():
                                      (64, 256, 1024, 40)])
 def test_gru_forward_chains(B, I, H, t):
     """The GRU core through forward-chain launches (h kept in full precision in registers from step
-    to step; its backward operations stay launch-per-step): bit for bit the launch-per-step path's
-    gradients for every strategy and several budgets, and the oracle's within tolerance."""
+    to step), backward-only sweep launches and forward batches: bit for bit the launch-per-step
+    path's gradients for every strategy and several budgets, and the oracle's within tolerance."""
     from paper_1606_03401_amd.session import Session
     from test_gpu_parity import TOL, check_against_oracle, oracle_gradients
     w = wl.Workload("gru-chain", B=B, I=I, H=H, t=t, kind=wl.KIND_HSM, m=4, gemm_dtype=wl.GEMM_BF16,
@@ -218,8 +218,18 @@ def test_gru_forward_chains(B, I, H, t):
     prof = mb.mebptt_profile_collect()
     mb.mebptt_profile_enable(0)
     _same(out, base, "profiled")
-    assert prof.chain_steps >= t - 2 and prof.sweep_steps == 0 and prof.batch_steps == 0
+    assert prof.chain_steps >= t - 2 and prof.batch_steps == 0 and prof.sweep_forward_steps == 0
     assert mb.mebptt_run_status(s.desc, s.workspace) == 0
+    if B != 37:     # (a ragged share of the batch has no backward-only sweep launch at this width)
+        assert prof.sweep_steps >= t - 40      # stored internal states: backward-only sweep launches
+    s = Session(w, inp, kind=wl.KIND_HSM, m=t)
+    mb.mebptt_profile_enable(1)
+    out = s.run_and_fetch()
+    prof = mb.mebptt_profile_collect()
+    mb.mebptt_profile_enable(0)
+    _same(out, base, "profiled, hidden states")
+    if B != 37:
+        assert prof.batch_steps >= t - 40 and prof.sweep_steps >= prof.batch_steps   # forward batches feed the sweeps
 
 
 @pytest.mark.parametrize("B,I,H", [(64, 128, 128), (64, 256, 1024)])
