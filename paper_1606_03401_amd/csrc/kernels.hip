@@ -1994,7 +1994,9 @@ static const SweepConfig SWEEP_CONFIGS[] = {
 };
 constexpr int SWEEP_BACKWARD_ONLY_FROM = 6;   // configurations from this index on have no forward part
 
-static int sweep_config(const Dims& d, int* nb_out = nullptr) {
+// backward_only: for a launch of backward operations on stored internal states, which never reads x
+// or the gate weights -- only the backward part of a configuration has to fit the shape.
+static int sweep_config(const Dims& d, int* nb_out = nullptr, bool backward_only = false) {
   if (!d.dtype || d.H % 128 != 0 || d.KH != d.H || d.HP != d.H) return -1;   // either cell; can_run_sweep() narrows
   const int nstepsF = d.KP / 32, nstepsB = d.G4 / 32;
   const FwdConfig fc = forward_config<__bf16>(d);
@@ -2006,8 +2008,8 @@ static int sweep_config(const Dims& d, int* nb_out = nullptr) {
     for (size_t i = 0; i < sizeof SWEEP_CONFIGS / sizeof SWEEP_CONFIGS[0]; ++i) {
       const SweepConfig& c = SWEEP_CONFIGS[i];
       if (c.nrt != d.H / 128 || c.ksb != ksb || c.nswb != nstepsB / ksb || c.nbt != nbt) continue;
-      // the forward part fixes the width of x as well; a backward-only launch never reads x
-      if ((int)i >= SWEEP_BACKWARD_ONLY_FROM ||
+      // the forward part fixes the width of x as well
+      if (backward_only || (int)i >= SWEEP_BACKWARD_ONLY_FROM ||
           (d.I % 8 == 0 && nstepsF % ksf == 0 && c.ksf == ksf && c.nswf == nstepsF / ksf &&
            c.nsxw == (d.KX / 32 + ksf - 1) / ksf)) {
         if (nb_out) *nb_out = nb;
@@ -2022,7 +2024,7 @@ bool can_run_sweep(const Dims& d) {   // with forward operations: LSTM only
   const int c = sweep_config(d);
   return d.cell == 0 && c >= 0 && c < SWEEP_BACKWARD_ONLY_FROM;
 }
-bool can_run_backward_sweep(const Dims& d) { return sweep_config(d) >= 0; }
+bool can_run_backward_sweep(const Dims& d) { return sweep_config(d, nullptr, true) >= 0; }
 int sweep_max_steps() { return SWEEP_MAX_STEPS; }
 
 template <bool FWD, int NRT, int NSWF, int KSF, int NSWB, int KSB, int NBT, int NSXW, int CELL = 0>
@@ -2042,7 +2044,7 @@ static hipError_t launch_sweep_cfg(const SweepParams& p, hipStream_t st) {
 
 hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
   int nb = 0;
-  const int cfg = sweep_config(d, &nb);
+  const int cfg = sweep_config(d, &nb, a.state != nullptr);
   if (cfg < 0 || a.count < 1 || a.count > SWEEP_MAX_STEPS) return hipErrorInvalidValue;
   if ((a.s_hi - 1) / d.CH - (a.s_hi - a.count) / d.CH > 1) return hipErrorInvalidValue;   // two chunk buffers
   SweepParams p{};
@@ -2104,7 +2106,7 @@ hipError_t launch_sweep(const Dims& d, const SweepArgs& a, hipStream_t st) {
       default: return launch_sweep_cfg<false, 8, 5, 8, 16, 8, 1, 1>(p, st);
     }
   }
-  if (d.cell) return hipErrorInvalidValue;
+  if (d.cell || cfg >= SWEEP_BACKWARD_ONLY_FROM) return hipErrorInvalidValue;
   switch (cfg) {
     case 0: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 1, 1>(p, st);
     case 1: return launch_sweep_cfg<true, 4, 5, 4, 8, 8, 2, 1>(p, st);
